@@ -1,0 +1,278 @@
+// C ABI of the MoE layer forward (see include/moe.h): argument validation,
+// capacity arithmetic, workspace carving and the launch sequence
+// gate -> dispatch -> expert FFN -> combine (Alg. 1 restricted to one GPU).
+// Host code only; every step of the path runs in the kernels it launches.
+#include "../../include/moe.h"
+
+#include <cmath>
+#include <initializer_list>
+
+#include "kernels.h"
+
+namespace {
+
+constexpr int kRowTile = 128;     // bM: per-expert buffers are aligned to this many rows
+constexpr int kGatePad = 128;     // WgT rows are padded to a multiple of the gate GEMM's column tile
+constexpr size_t kAlign = 256;
+
+size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+struct Plan {
+    int C, C_pad, E_pad, elem;
+    size_t off_wgt, off_logits, off_slot_token, off_slot_weight, off_counts, off_xe, off_h, off_y, total;
+};
+
+moe_status check_config(const moe_config* c) {
+    if (!c) return MOE_ERR_INVALID_ARG;
+    if (c->T <= 0 || c->H <= 0 || c->I <= 0 || c->E <= 0 || c->k <= 0 || c->k > c->E) return MOE_ERR_INVALID_ARG;
+    if (c->capacity_override < 0) return MOE_ERR_INVALID_ARG;
+    if (c->capacity_override == 0 && !(c->capacity_factor > 0.0f && std::isfinite(c->capacity_factor)))
+        return MOE_ERR_INVALID_ARG;
+    if (c->dtype < MOE_F32 || c->dtype > MOE_F16) return MOE_ERR_UNSUPPORTED;
+    if (c->act < MOE_ACT_RELU || c->act > MOE_ACT_IDENTITY) return MOE_ERR_UNSUPPORTED;
+    if (c->H % 8 != 0 || c->I % 8 != 0) return MOE_ERR_UNSUPPORTED;
+    if (c->E > MOE_MAX_EXPERTS) return MOE_ERR_UNSUPPORTED;
+    return MOE_OK;
+}
+
+moe_status capacity_of(const moe_config* c, int* C, int* C_pad) {
+    long long cap;
+    if (c->capacity_override > 0) {
+        cap = c->capacity_override;
+    } else {
+        const double v = std::ceil((double)c->capacity_factor * (double)c->k * (double)c->T / (double)c->E);
+        if (v > 2.0e9) return MOE_ERR_INVALID_ARG;
+        cap = v < 1.0 ? 1 : (long long)v;
+    }
+    const long long pad = (cap + kRowTile - 1) / kRowTile * kRowTile;
+    if (pad > 0x7fffffffLL) return MOE_ERR_INVALID_ARG;
+    *C = (int)cap;
+    *C_pad = (int)pad;
+    return MOE_OK;
+}
+
+moe_status make_plan(const moe_config* c, Plan* p) {
+    moe_status st = check_config(c);
+    if (st != MOE_OK) return st;
+    st = capacity_of(c, &p->C, &p->C_pad);
+    if (st != MOE_OK) return st;
+    p->elem = c->dtype == MOE_F32 ? 4 : 2;
+    p->E_pad = (int)align_up((size_t)c->E, kGatePad);
+    const size_t T = c->T, H = c->H, I = c->I, E = c->E, el = p->elem;
+    const size_t rows = E * (size_t)p->C_pad;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, kAlign); return o; };
+    p->off_wgt = take((size_t)p->E_pad * H * el);
+    p->off_logits = take(T * E * 4);
+    p->off_slot_token = take(E * (size_t)p->C * 4);
+    p->off_slot_weight = take(E * (size_t)p->C * 4);
+    p->off_counts = take((size_t)moe::route_chunks((long long)T * c->k) * E * 4);
+    p->off_xe = take(rows * H * el);
+    p->off_h = take(rows * I * el);
+    p->off_y = take(rows * H * el);
+    p->total = off;
+    return MOE_OK;
+}
+
+bool misaligned(const void* p) { return ((uintptr_t)p & 15u) != 0; }
+
+moe_status hip_status(hipError_t e) { return e == hipSuccess ? MOE_OK : MOE_ERR_HIP; }
+
+char* ws_at(void* ws, size_t off) { return (char*)ws + off; }
+
+// ---- stage launchers (arguments already validated) ---------------------------------
+
+moe_status run_gate(const moe_config* c, const Plan& p, void* ws, const void* x, const void* Wg,
+                    const float* gate_bias, float* logits, int32_t* topk_expert, float* topk_weight,
+                    hipStream_t s) {
+    void* wgt = ws_at(ws, p.off_wgt);
+    hipError_t e = moe::launch_transpose_pad(Wg, wgt, c->H, c->E, p.E_pad, c->dtype, s);
+    if (e != hipSuccess) return MOE_ERR_HIP;
+    moe::GemmArgs g{};
+    g.A = x; g.a_group_stride = 0; g.lda = c->H;
+    g.B = wgt; g.b_group_stride = 0; g.ldb = c->H;
+    g.C = logits; g.c_group_stride = 0; g.ldc = c->E;
+    g.bias = gate_bias; g.bias_group_stride = 0;
+    g.rows_dev = nullptr; g.rows_fixed = c->T; g.rows_cap = c->T;
+    g.groups = 1; g.max_rows = c->T;
+    g.N = c->E; g.K = c->H;
+    g.act = MOE_ACT_IDENTITY; g.dtype = c->dtype; g.b_is_nk = true; g.c_f32 = true;
+    e = moe::launch_grouped_gemm(g, s);
+    if (e != hipSuccess) return MOE_ERR_HIP;
+    return hip_status(moe::launch_topk(logits, c->T, c->E, c->k, topk_expert, topk_weight, s));
+}
+
+moe_status run_dispatch(const moe_config* c, const Plan& p, void* ws, const void* x,
+                        const int32_t* topk_expert, const float* topk_weight, int32_t* slot,
+                        int32_t* expert_demand, int32_t* slot_token, float* slot_weight, void* xe,
+                        hipStream_t s) {
+    hipError_t e = moe::launch_route(topk_expert, topk_weight, c->T, c->E, c->k, p.C,
+                                     (int32_t*)ws_at(ws, p.off_counts), slot, expert_demand, slot_token,
+                                     slot_weight, s);
+    if (e != hipSuccess) return MOE_ERR_HIP;
+    if (!xe) return MOE_OK;
+    return hip_status(moe::launch_pack(x, topk_expert, slot, c->T, c->H, c->k, c->E, p.C, p.C_pad, c->dtype, xe, s));
+}
+
+moe_status run_ffn(const moe_config* c, const Plan& p, void* ws, const void* xe,
+                   const int32_t* expert_demand, const void* W1, const void* b1, const void* W2,
+                   const void* b2, void* y, hipStream_t s) {
+    void* h = ws_at(ws, p.off_h);
+    const long long H = c->H, I = c->I;
+    moe::GemmArgs g{};
+    g.rows_dev = expert_demand; g.rows_fixed = 0; g.rows_cap = p.C;
+    g.groups = c->E; g.max_rows = p.C;
+    g.dtype = c->dtype; g.b_is_nk = false; g.c_f32 = false;
+    // task t1: h = phi1(xe W1 + b1)
+    g.A = xe; g.a_group_stride = (long long)p.C_pad * H; g.lda = c->H;
+    g.B = W1; g.b_group_stride = H * I; g.ldb = c->I;
+    g.C = h; g.c_group_stride = (long long)p.C_pad * I; g.ldc = c->I;
+    g.bias = b1; g.bias_group_stride = I;
+    g.N = c->I; g.K = c->H; g.act = c->act;
+    hipError_t e = moe::launch_grouped_gemm(g, s);
+    if (e != hipSuccess) return MOE_ERR_HIP;
+    // task t2: y = h W2 + b2
+    g.A = h; g.a_group_stride = (long long)p.C_pad * I; g.lda = c->I;
+    g.B = W2; g.b_group_stride = I * H; g.ldb = c->H;
+    g.C = y; g.c_group_stride = (long long)p.C_pad * H; g.ldc = c->H;
+    g.bias = b2; g.bias_group_stride = H;
+    g.N = c->H; g.K = c->I; g.act = MOE_ACT_IDENTITY;
+    return hip_status(moe::launch_grouped_gemm(g, s));
+}
+
+moe_status run_combine(const moe_config* c, const Plan& p, const void* y, const int32_t* topk_expert,
+                       const float* topk_weight, const int32_t* slot, void* out, hipStream_t s) {
+    return hip_status(moe::launch_combine(y, topk_expert, topk_weight, slot, c->T, c->H, c->k, c->E, p.C,
+                                          p.C_pad, c->dtype, out, s));
+}
+
+bool bad_required(std::initializer_list<const void*> ptrs) {
+    for (const void* q : ptrs)
+        if (!q || misaligned(q)) return true;
+    return false;
+}
+bool bad_optional(std::initializer_list<const void*> ptrs) {
+    for (const void* q : ptrs)
+        if (q && misaligned(q)) return true;
+    return false;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* moe_status_string(moe_status s) {
+    switch (s) {
+        case MOE_OK: return "ok";
+        case MOE_ERR_INVALID_ARG: return "invalid argument";
+        case MOE_ERR_UNSUPPORTED: return "unsupported configuration";
+        case MOE_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
+        case MOE_ERR_HIP: return "HIP launch error";
+    }
+    return "unknown status";
+}
+
+int32_t moe_row_tile(void) { return kRowTile; }
+
+moe_status moe_capacity(const moe_config* cfg, int32_t* C, int32_t* C_pad) {
+    moe_status st = check_config(cfg);
+    if (st != MOE_OK) return st;
+    int c = 0, cp = 0;
+    st = capacity_of(cfg, &c, &cp);
+    if (st != MOE_OK) return st;
+    if (C) *C = c;
+    if (C_pad) *C_pad = cp;
+    return MOE_OK;
+}
+
+moe_status moe_workspace_bytes(const moe_config* cfg, size_t* bytes) {
+    if (!bytes) return MOE_ERR_INVALID_ARG;
+    Plan p;
+    moe_status st = make_plan(cfg, &p);
+    if (st != MOE_OK) return st;
+    *bytes = p.total;
+    return MOE_OK;
+}
+
+moe_status moe_forward(const moe_config* cfg, void* workspace, size_t workspace_bytes, const void* x,
+                       const void* Wg, const float* gate_bias, const void* W1, const void* b1,
+                       const void* W2, const void* b2, void* out, float* gate_logits,
+                       int32_t* topk_expert, float* topk_weight, int32_t* slot, int32_t* expert_demand,
+                       void* stream) {
+    Plan p;
+    moe_status st = make_plan(cfg, &p);
+    if (st != MOE_OK) return st;
+    if (bad_required({workspace, x, Wg, W1, W2, out, topk_expert, topk_weight, slot, expert_demand}) ||
+        bad_optional({gate_bias, b1, b2, gate_logits}))
+        return MOE_ERR_INVALID_ARG;
+    if (workspace_bytes < p.total) return MOE_ERR_WORKSPACE_TOO_SMALL;
+    hipStream_t s = (hipStream_t)stream;
+    float* logits = gate_logits ? gate_logits : (float*)ws_at(workspace, p.off_logits);
+    int32_t* slot_token = (int32_t*)ws_at(workspace, p.off_slot_token);
+    float* slot_weight = (float*)ws_at(workspace, p.off_slot_weight);
+    void* xe = ws_at(workspace, p.off_xe);
+    void* y = ws_at(workspace, p.off_y);
+    st = run_gate(cfg, p, workspace, x, Wg, gate_bias, logits, topk_expert, topk_weight, s);
+    if (st != MOE_OK) return st;
+    st = run_dispatch(cfg, p, workspace, x, topk_expert, topk_weight, slot, expert_demand, slot_token, slot_weight, xe, s);
+    if (st != MOE_OK) return st;
+    st = run_ffn(cfg, p, workspace, xe, expert_demand, W1, b1, W2, b2, y, s);
+    if (st != MOE_OK) return st;
+    return run_combine(cfg, p, y, topk_expert, topk_weight, slot, out, s);
+}
+
+moe_status moe_gate(const moe_config* cfg, void* workspace, size_t workspace_bytes, const void* x,
+                    const void* Wg, const float* gate_bias, float* gate_logits, int32_t* topk_expert,
+                    float* topk_weight, void* stream) {
+    Plan p;
+    moe_status st = make_plan(cfg, &p);
+    if (st != MOE_OK) return st;
+    if (bad_required({workspace, x, Wg, gate_logits, topk_expert, topk_weight}) || bad_optional({gate_bias}))
+        return MOE_ERR_INVALID_ARG;
+    if (workspace_bytes < p.total) return MOE_ERR_WORKSPACE_TOO_SMALL;
+    return run_gate(cfg, p, workspace, x, Wg, gate_bias, gate_logits, topk_expert, topk_weight, (hipStream_t)stream);
+}
+
+moe_status moe_route(const moe_config* cfg, const float* gate_logits, int32_t* topk_expert,
+                     float* topk_weight, void* stream) {
+    moe_status st = check_config(cfg);
+    if (st != MOE_OK) return st;
+    if (bad_required({gate_logits, topk_expert, topk_weight})) return MOE_ERR_INVALID_ARG;
+    return hip_status(moe::launch_topk(gate_logits, cfg->T, cfg->E, cfg->k, topk_expert, topk_weight, (hipStream_t)stream));
+}
+
+moe_status moe_dispatch(const moe_config* cfg, void* workspace, size_t workspace_bytes, const void* x,
+                        const int32_t* topk_expert, const float* topk_weight, int32_t* slot,
+                        int32_t* expert_demand, int32_t* slot_token, float* slot_weight, void* xe,
+                        void* stream) {
+    Plan p;
+    moe_status st = make_plan(cfg, &p);
+    if (st != MOE_OK) return st;
+    if (bad_required({workspace, topk_expert, topk_weight, slot, expert_demand, slot_token, slot_weight}) ||
+        bad_optional({x, xe}) || (xe && !x))
+        return MOE_ERR_INVALID_ARG;
+    if (workspace_bytes < p.total) return MOE_ERR_WORKSPACE_TOO_SMALL;
+    return run_dispatch(cfg, p, workspace, x, topk_expert, topk_weight, slot, expert_demand, slot_token, slot_weight, xe, (hipStream_t)stream);
+}
+
+moe_status moe_expert_ffn(const moe_config* cfg, void* workspace, size_t workspace_bytes, const void* xe,
+                          const int32_t* expert_demand, const void* W1, const void* b1, const void* W2,
+                          const void* b2, void* y, void* stream) {
+    Plan p;
+    moe_status st = make_plan(cfg, &p);
+    if (st != MOE_OK) return st;
+    if (bad_required({workspace, xe, expert_demand, W1, W2, y}) || bad_optional({b1, b2})) return MOE_ERR_INVALID_ARG;
+    if (workspace_bytes < p.total) return MOE_ERR_WORKSPACE_TOO_SMALL;
+    return run_ffn(cfg, p, workspace, xe, expert_demand, W1, b1, W2, b2, y, (hipStream_t)stream);
+}
+
+moe_status moe_combine(const moe_config* cfg, const void* y, const int32_t* topk_expert,
+                       const float* topk_weight, const int32_t* slot, void* out, void* stream) {
+    Plan p;
+    moe_status st = make_plan(cfg, &p);
+    if (st != MOE_OK) return st;
+    if (bad_required({y, topk_expert, topk_weight, slot, out})) return MOE_ERR_INVALID_ARG;
+    return run_combine(cfg, p, y, topk_expert, topk_weight, slot, out, (hipStream_t)stream);
+}
+
+}  // extern "C"

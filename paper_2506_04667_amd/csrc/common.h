@@ -1,0 +1,68 @@
+// Shared device-side helpers of the HIP library (storage dtypes, vector types).
+// gfx950 only.  Nothing here is used by, or shared with, the CPU oracle.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace moe {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
+typedef __attribute__((ext_vector_type(8))) short s16x8;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+
+constexpr int kWave = 64;
+
+// Storage element tags.  16-bit types are carried as raw bits.
+struct F32 { typedef float store_t; static constexpr int kBytes = 4; static constexpr int kVec = 4; };
+struct BF16 { typedef uint16_t store_t; static constexpr int kBytes = 2; static constexpr int kVec = 8; };
+struct F16 { typedef uint16_t store_t; static constexpr int kBytes = 2; static constexpr int kVec = 8; };
+
+__device__ __forceinline__ float bf16_bits_to_float(uint16_t b) {
+    return __builtin_bit_cast(float, (uint32_t)b << 16);
+}
+// round to nearest even; inputs are finite by contract (NaN kept quiet)
+__device__ __forceinline__ uint16_t float_to_bf16_bits(float f) {
+    uint32_t u = __builtin_bit_cast(uint32_t, f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+__device__ __forceinline__ float f16_bits_to_float(uint16_t b) {
+    return (float)__builtin_bit_cast(_Float16, b);
+}
+__device__ __forceinline__ uint16_t float_to_f16_bits(float f) {
+    return __builtin_bit_cast(uint16_t, (_Float16)f);  // hardware conversion rounds to nearest even
+}
+
+template <class S> __device__ __forceinline__ float load_as_float(const void* p, size_t i);
+template <> __device__ __forceinline__ float load_as_float<F32>(const void* p, size_t i) { return ((const float*)p)[i]; }
+template <> __device__ __forceinline__ float load_as_float<BF16>(const void* p, size_t i) { return bf16_bits_to_float(((const uint16_t*)p)[i]); }
+template <> __device__ __forceinline__ float load_as_float<F16>(const void* p, size_t i) { return f16_bits_to_float(((const uint16_t*)p)[i]); }
+
+template <class S> __device__ __forceinline__ void store_from_float(void* p, size_t i, float v);
+template <> __device__ __forceinline__ void store_from_float<F32>(void* p, size_t i, float v) { ((float*)p)[i] = v; }
+template <> __device__ __forceinline__ void store_from_float<BF16>(void* p, size_t i, float v) { ((uint16_t*)p)[i] = float_to_bf16_bits(v); }
+template <> __device__ __forceinline__ void store_from_float<F16>(void* p, size_t i, float v) { ((uint16_t*)p)[i] = float_to_f16_bits(v); }
+
+template <class S> __device__ __forceinline__ float bits16_to_float(uint16_t b);
+template <> __device__ __forceinline__ float bits16_to_float<BF16>(uint16_t b) { return bf16_bits_to_float(b); }
+template <> __device__ __forceinline__ float bits16_to_float<F16>(uint16_t b) { return f16_bits_to_float(b); }
+template <class S> __device__ __forceinline__ uint16_t float_to_bits16(float f);
+template <> __device__ __forceinline__ uint16_t float_to_bits16<BF16>(float f) { return float_to_bf16_bits(f); }
+template <> __device__ __forceinline__ uint16_t float_to_bits16<F16>(float f) { return float_to_f16_bits(f); }
+
+// phi_1 of the first FFN task, on the fp32 accumulator (act codes of moe_act)
+__device__ __forceinline__ float apply_act(float v, int act) {
+    switch (act) {
+        case 0: return fmaxf(v, 0.0f);
+        case 1: return 0.5f * v * (1.0f + tanhf(0.7978845608028654f * (v + 0.044715f * v * v * v)));
+        case 2: return 0.5f * v * (1.0f + erff(v * 0.7071067811865476f));
+        default: return v;
+    }
+}
+
+}  // namespace moe

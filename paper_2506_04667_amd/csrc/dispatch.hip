@@ -1,0 +1,146 @@
+// Dispatch on one GPU (Alg. 1 "Dispatch"): builds the routing table
+// T_phi(e, c) = (token, combine weight) with token-order slot assignment and
+// drops beyond the capacity C, then packs the kept token rows into the per-expert
+// buffer xe[E, C_pad, H] (the one-GPU residue of the symmetric layout's (C, H)
+// cells, capacity aligned to the row tile as in Sec. 3.2.1).
+//
+// Slot assignment is integer work and fully deterministic: the (token, choice)
+// pairs, in token-major order, are cut into chunks of kChunk pairs;
+//   1. count:   one thread per (chunk, expert) counts the chunk's pairs naming it;
+//   2. scan:    one thread per expert turns the counts into exclusive chunk bases
+//               and the expert's total demand;
+//   3. scatter: one wavefront per chunk walks its pairs 64 at a time; a lane's
+//               slot is base + (pairs of the same expert in earlier steps) +
+//               (lower lanes naming the same expert in this step).
+#include "common.h"
+#include "kernels.h"
+
+namespace moe {
+namespace {
+
+constexpr int kChunk = 256;
+
+__global__ __launch_bounds__(256) void route_count_kernel(const int32_t* __restrict__ topk_expert, long long P,
+                                                          int E, int n_chunks, int32_t* __restrict__ counts,
+                                                          int32_t* __restrict__ slot_token,
+                                                          float* __restrict__ slot_weight, long long EC) {
+    const long long gid = blockIdx.x * (long long)blockDim.x + threadIdx.x;
+    const long long stride = (long long)gridDim.x * blockDim.x;
+    for (long long q = gid; q < EC; q += stride) {   // empty routing table
+        slot_token[q] = -1;
+        slot_weight[q] = 0.0f;
+    }
+    for (long long q = gid; q < (long long)n_chunks * E; q += stride) {
+        const int c = (int)(q / E), e = (int)(q % E);
+        const long long p0 = (long long)c * kChunk;
+        const long long p1 = p0 + kChunk < P ? p0 + kChunk : P;
+        int cnt = 0;
+        for (long long p = p0; p < p1; ++p) cnt += (topk_expert[p] == e);
+        counts[q] = cnt;
+    }
+}
+
+__global__ __launch_bounds__(256) void route_scan_kernel(int32_t* __restrict__ counts, int n_chunks, int E,
+                                                         int32_t* __restrict__ expert_demand) {
+    const int e = blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= E) return;
+    int run = 0;
+    for (int c = 0; c < n_chunks; ++c) {
+        const int t = counts[(size_t)c * E + e];
+        counts[(size_t)c * E + e] = run;
+        run += t;
+    }
+    expert_demand[e] = run;
+}
+
+__global__ __launch_bounds__(64) void route_scatter_kernel(const int32_t* __restrict__ topk_expert,
+                                                           const float* __restrict__ topk_weight, long long P,
+                                                           int E, int k, int C, const int32_t* __restrict__ base,
+                                                           int32_t* __restrict__ slot,
+                                                           int32_t* __restrict__ slot_token,
+                                                           float* __restrict__ slot_weight) {
+    extern __shared__ int32_t run[];                 // [E] slots handed out so far, per expert
+    const int c = blockIdx.x, lane = threadIdx.x;
+    for (int e = lane; e < E; e += kWave) run[e] = base[(size_t)c * E + e];
+    __syncthreads();
+    const int nbits = E > 1 ? 32 - __clz(E - 1) : 0;
+    const long long p_end = ((long long)c + 1) * kChunk < P ? ((long long)c + 1) * kChunk : P;
+    for (long long p0 = (long long)c * kChunk; p0 < p_end; p0 += kWave) {
+        const long long p = p0 + lane;
+        int e = p < p_end ? topk_expert[p] : -1;
+        const bool valid = (e >= 0 && e < E);
+        if (!valid) e = 0;
+        // lanes naming the same expert: intersect ballots over the bits of e
+        unsigned long long same = __ballot(valid);
+        for (int b = 0; b < nbits; ++b) {
+            const bool bit = (e >> b) & 1;
+            const unsigned long long bal = __ballot(valid && bit);
+            same &= bit ? bal : ~bal;
+        }
+        const unsigned long long below = (1ull << lane) - 1ull;
+        const int rank = __popcll(same & below);
+        const int group = __popcll(same);
+        const int s = valid ? run[e] + rank : 0;
+        __syncthreads();
+        if (valid && rank == group - 1) run[e] = s + 1;
+        __syncthreads();
+        if (p < p_end) {
+            const bool kept = valid && s < C;
+            slot[p] = kept ? s : -1;
+            if (kept) {
+                slot_token[(size_t)e * C + s] = (int32_t)(p / k);
+                slot_weight[(size_t)e * C + s] = topk_weight[p];
+            }
+        }
+    }
+}
+
+// One workgroup per token: the row is read once and written to each kept slot.
+__global__ __launch_bounds__(256) void pack_kernel(const u32x4* __restrict__ x, const int32_t* __restrict__ topk_expert,
+                                                   const int32_t* __restrict__ slot, int row_chunks, int k, int E,
+                                                   int C, int C_pad, u32x4* __restrict__ xe) {
+    const int t = blockIdx.x;
+    for (int c = threadIdx.x; c < row_chunks; c += blockDim.x) {
+        const u32x4 v = x[(size_t)t * row_chunks + c];
+        for (int j = 0; j < k; ++j) {
+            const int s = slot[(size_t)t * k + j];
+            if (s < 0 || s >= C) continue;
+            const int e = topk_expert[(size_t)t * k + j];
+            if (e < 0 || e >= E) continue;
+            xe[((size_t)e * C_pad + s) * row_chunks + c] = v;
+        }
+    }
+}
+
+}  // namespace
+
+int route_chunks(long long pairs) { return (int)((pairs + kChunk - 1) / kChunk); }
+
+hipError_t launch_route(const int32_t* topk_expert, const float* topk_weight, int T, int E, int k, int C,
+                        int32_t* counts, int32_t* slot, int32_t* expert_demand, int32_t* slot_token,
+                        float* slot_weight, hipStream_t stream) {
+    const long long P = (long long)T * k;
+    const int n_chunks = route_chunks(P);
+    const long long work = (long long)n_chunks * E;
+    const long long EC = (long long)E * C;
+    long long blocks = ((work > EC ? work : EC) + 255) / 256;
+    if (blocks > 65535) blocks = 65535;
+    hipLaunchKernelGGL(route_count_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, topk_expert, P, E, n_chunks,
+                       counts, slot_token, slot_weight, EC);
+    hipLaunchKernelGGL(route_scan_kernel, dim3((E + 255) / 256), dim3(256), 0, stream, counts, n_chunks, E,
+                       expert_demand);
+    hipLaunchKernelGGL(route_scatter_kernel, dim3(n_chunks), dim3(64), (size_t)E * sizeof(int32_t), stream,
+                       topk_expert, topk_weight, P, E, k, C, counts, slot, slot_token, slot_weight);
+    return hipGetLastError();
+}
+
+hipError_t launch_pack(const void* x, const int32_t* topk_expert, const int32_t* slot, int T, int H, int k,
+                       int E, int C, int C_pad, int dtype, void* xe, hipStream_t stream) {
+    const int bytes = dtype == 0 ? 4 : 2;
+    const int row_chunks = H * bytes / 16;
+    hipLaunchKernelGGL(pack_kernel, dim3(T), dim3(256), 0, stream, (const u32x4*)x, topk_expert, slot,
+                       row_chunks, k, E, C, C_pad, (u32x4*)xe);
+    return hipGetLastError();
+}
+
+}  // namespace moe

@@ -1,0 +1,53 @@
+// Internal launcher interface between the C-ABI translation unit and the kernel
+// translation units.  Every launcher enqueues on `stream` and returns the
+// hipGetLastError() of its launches.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace moe {
+
+// Grouped tile GEMM: for each group g (an expert, or the single gate "group")
+//   C[g][r][n] = epilogue( sum_k A[g][r][k] * B[g][k][n] + bias[g][n] ),  r < rows(g)
+// rows(g) = rows_fixed if rows_dev == nullptr, else min(rows_dev[g], rows_cap).
+// B is [K][N] row-major per group ("NN"), or, when b_is_nk, [N][K] row-major
+// (K contiguous).  Accumulation is fp32.
+struct GemmArgs {
+    const void* A; long long a_group_stride; int lda;       // elements
+    const void* B; long long b_group_stride; int ldb;
+    void* C; long long c_group_stride; int ldc;
+    const void* bias; long long bias_group_stride;          // nullptr = none
+    const int32_t* rows_dev; int rows_fixed; int rows_cap;
+    int groups; int max_rows;                               // grid extent in rows
+    int N; int K;
+    int act;                                                // moe_act, applied after the bias
+    int dtype;                                              // storage of A, B (and of C, bias unless c_f32)
+    bool b_is_nk;
+    bool c_f32;                                             // C and bias are fp32 (gate logits)
+};
+hipError_t launch_grouped_gemm(const GemmArgs& a, hipStream_t stream);
+
+// WgT[n][h] = Wg[h][n] for n < E, zero rows for E <= n < E_pad.
+hipError_t launch_transpose_pad(const void* Wg, void* WgT, int H, int E, int E_pad, int dtype,
+                                hipStream_t stream);
+
+// Top-k selection and combine weights from fp32 logits.
+hipError_t launch_topk(const float* logits, int T, int E, int k, int32_t* topk_expert,
+                       float* topk_weight, hipStream_t stream);
+
+// Token-order slot assignment.  `counts` is scratch of route_chunks(P) * E ints.
+int route_chunks(long long pairs);
+hipError_t launch_route(const int32_t* topk_expert, const float* topk_weight, int T, int E, int k,
+                        int C, int32_t* counts, int32_t* slot, int32_t* expert_demand,
+                        int32_t* slot_token, float* slot_weight, hipStream_t stream);
+
+// xe[e][slot][:] = x[token][:] for every kept (token, choice).
+hipError_t launch_pack(const void* x, const int32_t* topk_expert, const int32_t* slot, int T, int H,
+                       int k, int E, int C, int C_pad, int dtype, void* xe, hipStream_t stream);
+
+// out[t][:] = sum_j w[t][j] * y[e][slot][:] over kept choices, fp32.
+hipError_t launch_combine(const void* y, const int32_t* topk_expert, const float* topk_weight,
+                          const int32_t* slot, int T, int H, int k, int E, int C, int C_pad,
+                          int dtype, void* out, hipStream_t stream);
+
+}  // namespace moe

@@ -1,0 +1,200 @@
+"""GPU parity tests: the HIP path, called through the C ABI, against the CPU oracle
+on the same seeded inputs (protocol in tests/parity.py)."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2506_04667_amd import binding as moe
+from paper_2506_04667_amd.inputs import WORKLOADS, make_inputs, scaled
+
+import parity
+
+pytestmark = pytest.mark.gpu
+
+
+def _run(oracle, w, staged=False, tokens=None, gate_bias=None):
+    print("case", w, "staged", staged, flush=True)
+    cpu = make_inputs(w)
+    if gate_bias is not None:
+        cpu["gate_bias"] = gate_bias
+    dev = parity.to_device(cpu)
+    b, host = parity.gpu_forward(w, dev, staged=staged)
+    rep = parity.check_layer(oracle, w, cpu, b, host, tokens=tokens)
+    print("  ", rep, flush=True)
+    return cpu, dev, b, host, rep
+
+
+# ------------------------------------------------------------ the benchmark's small configurations
+
+def test_tiny_f32_full(oracle):
+    cpu, dev, b, host, rep = _run(oracle, WORKLOADS["tiny_f32"])
+    assert rep["dropped"] == 0
+
+
+def test_tiny_f32_staged_matches_fused_call(oracle):
+    w = WORKLOADS["tiny_f32"]
+    cpu = make_inputs(w)
+    dev = parity.to_device(cpu)
+    b1, h1 = parity.gpu_forward(w, dev, staged=False)
+    b2, h2 = parity.gpu_forward(w, dev, staged=True)
+    for n in h1:
+        np.testing.assert_array_equal(h1[n], h2[n], err_msg=n)
+    assert torch.equal(b1.out, b2.out)
+
+
+def test_small_f32_full(oracle):
+    # capacity 320 is four standard deviations above the mean demand of 256: nothing is dropped here
+    _run(oracle, WORKLOADS["small_f32"])
+
+
+# ------------------------------------------------------------ reduced 16-bit cases: several tiles, ragged tails
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16", "f32"])
+def test_reduced_ragged_with_biases(oracle, dtype):
+    # rows per expert ~ 190 +- (two row tiles, ragged); I = 840 and H = 328 leave ragged column and k tiles
+    w = scaled(WORKLOADS["paper_bf16_e128"], name="reduced", T=757, H=328, I=840, E=8, k=2, capacity_factor=1.0,
+               dtype=dtype, seed=11, with_bias=True, act="gelu_tanh")
+    cpu, dev, b, host, rep = _run(oracle, w, staged=True)
+    assert rep["dropped"] > 0
+    # staged intermediates: routing tables and the packed buffer are bit-exact
+    slot, demand = parity.check_routing(oracle, w, host, b.C, b.slot_token.cpu().numpy(), b.slot_weight.cpu().numpy())
+    st = b.slot_token.cpu().numpy()
+    xe = b.xe.cpu()
+    x = cpu["x"]
+    for e in range(w.E):
+        n_e = min(int(demand[e]), b.C)
+        assert torch.equal(xe[e, :n_e], x[torch.from_numpy(st[e, :n_e]).long()])
+    # expert outputs row by row against the oracle's FFN
+    pt = [int(st[e, s]) for e in range(w.E) for s in range(min(int(demand[e]), b.C))][::37]
+    pe = [e for e in range(w.E) for s in range(min(int(demand[e]), b.C))][::37]
+    ps = [s for e in range(w.E) for s in range(min(int(demand[e]), b.C))][::37]
+    y_ref = oracle.ffn_rows(cpu["x"], cpu["W1"], cpu["b1"], cpu["W2"], cpu["b2"], pt, pe, w.H, w.I, w.act, w.dtype)
+    y_gpu = parity.to_np64(b.y)[pe, ps]
+    parity.assert_close(y_gpu, y_ref, parity.TOL[dtype], "y rows")
+
+
+@pytest.mark.parametrize("act", ["relu", "gelu_erf", "identity"])
+def test_activations_bf16(oracle, act):
+    w = scaled(WORKLOADS["paper_bf16_e128"], name="acts", T=300, H=128, I=256, E=4, k=2, capacity_factor=2.0,
+               seed=12, act=act)
+    _run(oracle, w)
+
+
+# ------------------------------------------------------------ paper-scale configurations, sampled outputs
+
+def _sample_tokens(host, n, seed):
+    rng = np.random.default_rng(seed)
+    T = host["slot"].shape[0]
+    toks = set(rng.choice(T, size=n, replace=False).tolist())
+    dropped_any = np.nonzero((host["slot"] < 0).any(axis=1))[0]
+    toks.update(dropped_any[:8].tolist())              # tokens that lost a choice
+    toks.update([0, T - 1])
+    return sorted(toks)
+
+
+@pytest.mark.parametrize("name", ["paper_bf16_e128", "skew_f16_e128", "paper_f32_e64"])
+def test_paper_scale_sampled(oracle, name):
+    w = WORKLOADS[name]
+    print("case", w, flush=True)
+    cpu = make_inputs(w)
+    dev = parity.to_device(cpu)
+    b, host = parity.gpu_forward(w, dev)
+    tokens = _sample_tokens(host, 48, 99)
+    rep = parity.check_layer(oracle, w, cpu, b, host, tokens=tokens)
+    print("  ", rep, flush=True)
+    demand = host["expert_demand"]
+    assert demand.sum() == w.T * w.k
+    if name == "skew_f16_e128":
+        assert (demand > b.C).any() and (demand < 8).any()
+    else:
+        assert rep["dropped"] > 0
+    # properties that hold at any size: every kept pair's packed row is the token's row
+    assert (host["slot"] < b.C).all()
+    out = parity.to_np64(b.out)
+    all_dropped = (host["slot"] < 0).all(axis=1)
+    assert (out[all_dropped] == 0).all()
+    # determinism: a second run is bit-identical
+    b2, host2 = parity.gpu_forward(w, dev)
+    assert torch.equal(b.out, b2.out)
+    for n in host:
+        np.testing.assert_array_equal(host[n], host2[n], err_msg=n)
+
+
+# ------------------------------------------------------------ selection and slotting edge cases
+
+def test_route_tie_heavy_logits(oracle):
+    rng = np.random.default_rng(3)
+    for T, E, k in [(257, 4, 1), (64, 7, 7), (1000, 130, 5), (33, 1, 1), (500, 64, 64), (129, 300, 3)]:
+        logits = rng.integers(-2, 3, size=(T, E)).astype(np.float32)
+        logits[logits == 0] *= rng.choice([1.0, -1.0], size=int((logits == 0).sum())).astype(np.float32)
+        cfg = moe.make_config(T, 8, 8, E, k, 1.0, "relu", "f32")
+        gl = torch.from_numpy(logits).cuda()
+        te = torch.empty((T, k), dtype=torch.int32, device="cuda")
+        tw = torch.empty((T, k), dtype=torch.float32, device="cuda")
+        moe.moe_route(cfg, gl, te, tw)
+        torch.cuda.synchronize()
+        te_ref, tw_ref = oracle.topk(logits, k)
+        np.testing.assert_array_equal(te.cpu().numpy(), te_ref)
+        np.testing.assert_allclose(tw.cpu().numpy(), tw_ref, rtol=1e-5, atol=1e-7)
+
+
+@pytest.mark.parametrize("T,E,k,C", [(1, 1, 1, 0), (5, 3, 3, 2), (1000, 6, 2, 1), (4099, 37, 3, 0), (777, 128, 2, 7),
+                                     (3000, 2, 2, 1000), (70000, 16, 4, 0)])
+def test_dispatch_slots_bit_exact(oracle, T, E, k, C):
+    rng = np.random.default_rng(T + E)
+    # skewed choices: some experts overflow, some stay empty
+    logits = (rng.standard_normal((T, E)) + np.linspace(0, 4, E)).astype(np.float32)
+    if E > 4:
+        logits[:, 1] = -50.0                                  # an expert nobody picks (k < E)
+    te, tw = oracle.topk(logits, k)
+    cfg = moe.make_config(T, 8, 8, E, k, 1.0, "relu", "f32", capacity_override=C)
+    b = moe.Buffers(cfg).alloc_staged()
+    te_d, tw_d = torch.from_numpy(te).cuda(), torch.from_numpy(tw).cuda()
+    moe.moe_dispatch(cfg, b.workspace, None, te_d, tw_d, b.slot, b.expert_demand, b.slot_token, b.slot_weight, None)
+    torch.cuda.synchronize()
+    slot, demand, st, sw = oracle.slots(te, tw, E, b.C)
+    np.testing.assert_array_equal(b.slot.cpu().numpy(), slot)
+    np.testing.assert_array_equal(b.expert_demand.cpu().numpy(), demand)
+    np.testing.assert_array_equal(b.slot_token.cpu().numpy(), st)
+    np.testing.assert_array_equal(b.slot_weight.cpu().numpy(), sw)
+
+
+def test_all_tokens_to_one_expert_and_empty_experts(oracle):
+    w = scaled(WORKLOADS["paper_bf16_e128"], name="one_expert", T=400, H=64, I=64, E=8, k=1, capacity_factor=1.0,
+               seed=13, dtype="f32", act="relu")
+    gb = torch.zeros(8)
+    gb[5] = 1000.0                                            # every token picks expert 5; C = 50 -> 350 drops
+    cpu, dev, b, host, rep = _run(oracle, w, gate_bias=gb)
+    assert rep["kept"] == 50 and rep["dropped"] == 350
+    assert list(host["expert_demand"]) == [0, 0, 0, 0, 0, 400, 0, 0]
+
+
+def test_k_equals_E_and_single_token(oracle):
+    w = scaled(WORKLOADS["tiny_f32"], name="kE", T=65, H=64, I=72, E=5, k=5, capacity_factor=1.0, seed=14)
+    _run(oracle, w)
+    w = scaled(WORKLOADS["tiny_f32"], name="one_token", T=1, H=8, I=8, E=3, k=2, capacity_factor=1.0, seed=15)
+    _run(oracle, w)
+    w = scaled(WORKLOADS["tiny_f32"], name="E1", T=130, H=72, I=136, E=1, k=1, capacity_factor=0.5, seed=16, dtype="bf16")
+    cpu, dev, b, host, rep = _run(oracle, w)
+    assert rep["kept"] == 65
+
+
+def test_capacity_override_paper_layout_reading(oracle):
+    # the layout section's capacity reading (no factor k): C = ceil(T / E)
+    w = scaled(WORKLOADS["tiny_f32"], name="override", T=512, H=64, I=128, E=8, k=2, capacity_factor=1.0, seed=17,
+               capacity_override=64)
+    cpu, dev, b, host, rep = _run(oracle, w)
+    assert b.C == 64 and rep["dropped"] >= 512
+
+
+def test_error_codes_on_device_calls():
+    cfg = moe.make_config(128, 64, 128, 4, 1, 2.0, "relu", "f32")
+    b = moe.Buffers(cfg)
+    small = torch.empty(16, dtype=torch.uint8, device="cuda")
+    x = torch.zeros((128, 64), device="cuda")
+    with pytest.raises(moe.MoeError) as e:
+        moe.moe_gate(cfg, small, x, x, None, b.gate_logits, b.topk_expert, b.topk_weight)
+    assert e.value.code == -3
+    with pytest.raises(moe.MoeError) as e:
+        moe.moe_gate(cfg, b.workspace, None, x, None, b.gate_logits, b.topk_expert, b.topk_weight)
+    assert e.value.code == -1
