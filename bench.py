@@ -39,7 +39,7 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=32)
     ap.add_argument("--warmup", type=int, default=32)
     ap.add_argument("--workload", default="paper_bf16_e128")
-    ap.add_argument("--cpu-baseline-tokens", type=int, default=256,
+    ap.add_argument("--cpu-baseline-tokens", type=int, default=16384,
                     help="tokens in the oracle's timed sample (0 = skip the cpu_baseline leg)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch one plain 1 GiB device copy (reference for hardware counters)")
@@ -132,7 +132,7 @@ def main():
     ffn_ms = stage_ms["expert_ffn"]
     launch_ms = ffn_ms / 2.0
     flops_per_launch = 2.0 * R * H * I
-    bytes_per_launch = (E * H * I + R * H + R * I) * el            # weights once + A rows + C rows (H = I here or averaged)
+    bytes_per_launch = (E * H * I + R * H + R * I) * el            # weights once + A rows + C rows; the sum is the same for both launches
     hbm_time = bytes_per_launch / (PEAK["hbm_gbs"] * 1e9)
     mfma_time = flops_per_launch / (PEAK["mfma_tflops"][w.dtype] * 1e12)
     traffic = read_traffic(w.name, w.dtype)
