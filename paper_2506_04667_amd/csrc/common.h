@@ -55,12 +55,31 @@ template <class S> __device__ __forceinline__ uint16_t float_to_bits16(float f);
 template <> __device__ __forceinline__ uint16_t float_to_bits16<BF16>(float f) { return float_to_bf16_bits(f); }
 template <> __device__ __forceinline__ uint16_t float_to_bits16<F16>(float f) { return float_to_f16_bits(f); }
 
+// two fp32 values -> two 16-bit storage values packed in a dword (lo in bits 0-15), round to nearest even
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
+template <class S> __device__ __forceinline__ uint32_t pack2(float lo, float hi);
+template <> __device__ __forceinline__ uint32_t pack2<BF16>(float lo, float hi) {
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{lo, hi}, bf16x2));
+}
+template <> __device__ __forceinline__ uint32_t pack2<F16>(float lo, float hi) {
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{lo, hi}, f16x2));
+}
+
 // phi_1 of the first FFN task, on the fp32 accumulator (act codes of moe_act)
+template <int ACT>
+__device__ __forceinline__ float apply_act_t(float v) {
+    if constexpr (ACT == 0) return fmaxf(v, 0.0f);
+    else if constexpr (ACT == 1) return 0.5f * v * (1.0f + tanhf(0.7978845608028654f * (v + 0.044715f * v * v * v)));
+    else if constexpr (ACT == 2) return 0.5f * v * (1.0f + erff(v * 0.7071067811865476f));
+    else return v;
+}
 __device__ __forceinline__ float apply_act(float v, int act) {
     switch (act) {
-        case 0: return fmaxf(v, 0.0f);
-        case 1: return 0.5f * v * (1.0f + tanhf(0.7978845608028654f * (v + 0.044715f * v * v * v)));
-        case 2: return 0.5f * v * (1.0f + erff(v * 0.7071067811865476f));
+        case 0: return apply_act_t<0>(v);
+        case 1: return apply_act_t<1>(v);
+        case 2: return apply_act_t<2>(v);
         default: return v;
     }
 }

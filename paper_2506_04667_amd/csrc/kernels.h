@@ -27,6 +27,11 @@ struct GemmArgs {
 };
 hipError_t launch_grouped_gemm(const GemmArgs& a, hipStream_t stream);
 
+// Weight-streaming variant for the 16-bit expert FFN tasks (direct-to-LDS, deep prefetch);
+// launch_grouped_gemm routes eligible shapes to it.
+bool stream_gemm_eligible(const GemmArgs& a);
+hipError_t launch_grouped_gemm_stream(const GemmArgs& a, hipStream_t stream);
+
 // WgT[n][h] = Wg[h][n] for n < E, zero rows for E <= n < E_pad.
 hipError_t launch_transpose_pad(const void* Wg, void* WgT, int H, int E, int E_pad, int dtype,
                                 hipStream_t stream);
