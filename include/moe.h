@@ -80,7 +80,8 @@ int32_t moe_row_tile(void);
 moe_status moe_capacity(const moe_config* cfg, int32_t* C, int32_t* C_pad);
 
 /* Bytes of device workspace that moe_forward and the staged calls need for this
- * configuration. */
+ * configuration (gate scratch, routing tables, the FFN intermediate h and the
+ * expert outputs y; the staged calls take xe and y from the caller). */
 moe_status moe_workspace_bytes(const moe_config* cfg, size_t* bytes);
 
 /* The whole layer (Alg. 1 restricted to one GPU: gate -> dispatch -> expert FFN
@@ -95,7 +96,10 @@ moe_status moe_workspace_bytes(const moe_config* cfg, size_t* bytes);
  *        slot[T,k]             slot of (token, choice) in its expert's buffer, -1 = dropped;
  *                              slots are handed out in token order, then choice order
  *        expert_demand[E]      pairs that named each expert, before the capacity cut
- * All outputs except gate_logits are required. */
+ * All outputs except gate_logits are required.  On this path the packed copy xe
+ * is not materialised: the first FFN task reads its rows from x through the
+ * routing table (slot -> token), which is what the payload-efficient dispatch of
+ * Sec. 3.2.1 amounts to on one GPU. */
 moe_status moe_forward(const moe_config* cfg, void* workspace, size_t workspace_bytes,
                        const void* x, const void* Wg, const float* gate_bias,
                        const void* W1, const void* b1, const void* W2, const void* b2,

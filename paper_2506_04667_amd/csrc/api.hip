@@ -19,7 +19,7 @@ size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 struct Plan {
     int C, C_pad, E_pad, elem;
-    size_t off_wgt, off_logits, off_slot_token, off_slot_weight, off_counts, off_xe, off_h, off_y, total;
+    size_t off_wgt, off_logits, off_slot_token, off_slot_weight, off_counts, off_h, off_y, total;
 };
 
 moe_status check_config(const moe_config* c) {
@@ -67,7 +67,6 @@ moe_status make_plan(const moe_config* c, Plan* p) {
     p->off_slot_token = take(E * (size_t)p->C * 4);
     p->off_slot_weight = take(E * (size_t)p->C * 4);
     p->off_counts = take((size_t)moe::route_chunks((long long)T * c->k) * E * 4);
-    p->off_xe = take(rows * H * el);
     p->off_h = take(rows * I * el);
     p->off_y = take(rows * H * el);
     p->total = off;
@@ -114,7 +113,9 @@ moe_status run_dispatch(const moe_config* c, const Plan& p, void* ws, const void
     return hip_status(moe::launch_pack(x, topk_expert, slot, c->T, c->H, c->k, c->E, p.C, p.C_pad, c->dtype, xe, s));
 }
 
-moe_status run_ffn(const moe_config* c, const Plan& p, void* ws, const void* xe,
+// xe: packed rows [E, C_pad, H]; or, with slot_token given, the token matrix x[T, H] whose rows the
+// first GEMM gathers through slot_token[E, C] (no packed copy).
+moe_status run_ffn(const moe_config* c, const Plan& p, void* ws, const void* xe, const int32_t* slot_token,
                    const int32_t* expert_demand, const void* W1, const void* b1, const void* W2,
                    const void* b2, void* y, hipStream_t s) {
     void* h = ws_at(ws, p.off_h);
@@ -125,6 +126,7 @@ moe_status run_ffn(const moe_config* c, const Plan& p, void* ws, const void* xe,
     g.dtype = c->dtype; g.b_is_nk = false; g.c_f32 = false;
     // task t1: h = phi1(xe W1 + b1)
     g.A = xe; g.a_group_stride = (long long)p.C_pad * H; g.lda = c->H;
+    g.a_row_index = slot_token; g.a_index_stride = p.C;
     g.B = W1; g.b_group_stride = H * I; g.ldb = c->I;
     g.C = h; g.c_group_stride = (long long)p.C_pad * I; g.ldc = c->I;
     g.bias = b1; g.bias_group_stride = I;
@@ -133,6 +135,7 @@ moe_status run_ffn(const moe_config* c, const Plan& p, void* ws, const void* xe,
     if (e != hipSuccess) return MOE_ERR_HIP;
     // task t2: y = h W2 + b2
     g.A = h; g.a_group_stride = (long long)p.C_pad * I; g.lda = c->I;
+    g.a_row_index = nullptr; g.a_index_stride = 0;
     g.B = W2; g.b_group_stride = I * H; g.ldb = c->H;
     g.C = y; g.c_group_stride = (long long)p.C_pad * H; g.ldc = c->H;
     g.bias = b2; g.bias_group_stride = H;
@@ -210,13 +213,14 @@ moe_status moe_forward(const moe_config* cfg, void* workspace, size_t workspace_
     float* logits = gate_logits ? gate_logits : (float*)ws_at(workspace, p.off_logits);
     int32_t* slot_token = (int32_t*)ws_at(workspace, p.off_slot_token);
     float* slot_weight = (float*)ws_at(workspace, p.off_slot_weight);
-    void* xe = ws_at(workspace, p.off_xe);
     void* y = ws_at(workspace, p.off_y);
     st = run_gate(cfg, p, workspace, x, Wg, gate_bias, logits, topk_expert, topk_weight, s);
     if (st != MOE_OK) return st;
-    st = run_dispatch(cfg, p, workspace, x, topk_expert, topk_weight, slot, expert_demand, slot_token, slot_weight, xe, s);
+    // Dispatch builds the routing table only; the first FFN GEMM gathers its rows from x through
+    // slot_token, so the packed copy xe is never materialised on this path.
+    st = run_dispatch(cfg, p, workspace, x, topk_expert, topk_weight, slot, expert_demand, slot_token, slot_weight, nullptr, s);
     if (st != MOE_OK) return st;
-    st = run_ffn(cfg, p, workspace, xe, expert_demand, W1, b1, W2, b2, y, s);
+    st = run_ffn(cfg, p, workspace, x, slot_token, expert_demand, W1, b1, W2, b2, y, s);
     if (st != MOE_OK) return st;
     return run_combine(cfg, p, y, topk_expert, topk_weight, slot, out, s);
 }
@@ -263,7 +267,7 @@ moe_status moe_expert_ffn(const moe_config* cfg, void* workspace, size_t workspa
     if (st != MOE_OK) return st;
     if (bad_required({workspace, xe, expert_demand, W1, W2, y}) || bad_optional({b1, b2})) return MOE_ERR_INVALID_ARG;
     if (workspace_bytes < p.total) return MOE_ERR_WORKSPACE_TOO_SMALL;
-    return run_ffn(cfg, p, workspace, xe, expert_demand, W1, b1, W2, b2, y, (hipStream_t)stream);
+    return run_ffn(cfg, p, workspace, xe, nullptr, expert_demand, W1, b1, W2, b2, y, (hipStream_t)stream);
 }
 
 moe_status moe_combine(const moe_config* cfg, const void* y, const int32_t* topk_expert,

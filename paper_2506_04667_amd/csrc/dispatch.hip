@@ -6,8 +6,8 @@
 //
 // Slot assignment is integer work and fully deterministic: the (token, choice)
 // pairs, in token-major order, are cut into chunks of kChunk pairs;
-//   1. count:   one thread per (chunk, expert) counts the chunk's pairs naming it;
-//   2. scan:    one thread per expert turns the counts into exclusive chunk bases
+//   1. count:   one workgroup per chunk histograms its pairs by expert (LDS integer atomics);
+//   2. scan:    one wavefront per expert turns the counts into exclusive chunk bases
 //               and the expert's total demand;
 //   3. scatter: one wavefront per chunk walks its pairs 64 at a time; a lane's
 //               slot is base + (pairs of the same expert in earlier steps) +
@@ -20,37 +20,50 @@ namespace {
 
 constexpr int kChunk = 256;
 
-__global__ __launch_bounds__(256) void route_count_kernel(const int32_t* __restrict__ topk_expert, long long P,
-                                                          int E, int n_chunks, int32_t* __restrict__ counts,
-                                                          int32_t* __restrict__ slot_token,
-                                                          float* __restrict__ slot_weight, long long EC) {
+// One workgroup per chunk of kChunk pairs: per-expert counts in an LDS histogram (integer atomics, so
+// the result does not depend on their order); also clears the routing table.
+__global__ __launch_bounds__(kChunk) void route_count_kernel(const int32_t* __restrict__ topk_expert, long long P,
+                                                             int E, int32_t* __restrict__ counts,
+                                                             int32_t* __restrict__ slot_token,
+                                                             float* __restrict__ slot_weight, long long EC) {
+    extern __shared__ int32_t hist[];                // [E]
     const long long gid = blockIdx.x * (long long)blockDim.x + threadIdx.x;
     const long long stride = (long long)gridDim.x * blockDim.x;
     for (long long q = gid; q < EC; q += stride) {   // empty routing table
         slot_token[q] = -1;
         slot_weight[q] = 0.0f;
     }
-    for (long long q = gid; q < (long long)n_chunks * E; q += stride) {
-        const int c = (int)(q / E), e = (int)(q % E);
-        const long long p0 = (long long)c * kChunk;
-        const long long p1 = p0 + kChunk < P ? p0 + kChunk : P;
-        int cnt = 0;
-        for (long long p = p0; p < p1; ++p) cnt += (topk_expert[p] == e);
-        counts[q] = cnt;
+    for (int e = threadIdx.x; e < E; e += kChunk) hist[e] = 0;
+    __syncthreads();
+    const long long p = (long long)blockIdx.x * kChunk + threadIdx.x;
+    if (p < P) {
+        const int e = topk_expert[p];
+        if (e >= 0 && e < E) atomicAdd(&hist[e], 1);
     }
+    __syncthreads();
+    for (int e = threadIdx.x; e < E; e += kChunk) counts[(size_t)blockIdx.x * E + e] = hist[e];
 }
 
+// One wavefront per expert: exclusive scan of its per-chunk counts, 64 chunks at a time.
 __global__ __launch_bounds__(256) void route_scan_kernel(int32_t* __restrict__ counts, int n_chunks, int E,
                                                          int32_t* __restrict__ expert_demand) {
-    const int e = blockIdx.x * blockDim.x + threadIdx.x;
+    const int e = blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
+    const int lane = threadIdx.x % kWave;
     if (e >= E) return;
-    int run = 0;
-    for (int c = 0; c < n_chunks; ++c) {
-        const int t = counts[(size_t)c * E + e];
-        counts[(size_t)c * E + e] = run;
-        run += t;
+    int carry = 0;
+    for (int c0 = 0; c0 < n_chunks; c0 += kWave) {
+        const int c = c0 + lane;
+        const int v = c < n_chunks ? counts[(size_t)c * E + e] : 0;
+        int incl = v;
+#pragma unroll
+        for (int off = 1; off < kWave; off <<= 1) {
+            const int t = __shfl_up(incl, off);
+            if (lane >= off) incl += t;
+        }
+        if (c < n_chunks) counts[(size_t)c * E + e] = carry + incl - v;
+        carry += __shfl(incl, kWave - 1);
     }
-    expert_demand[e] = run;
+    if (lane == 0) expert_demand[e] = carry;
 }
 
 __global__ __launch_bounds__(64) void route_scatter_kernel(const int32_t* __restrict__ topk_expert,
@@ -121,13 +134,10 @@ hipError_t launch_route(const int32_t* topk_expert, const float* topk_weight, in
                         float* slot_weight, hipStream_t stream) {
     const long long P = (long long)T * k;
     const int n_chunks = route_chunks(P);
-    const long long work = (long long)n_chunks * E;
     const long long EC = (long long)E * C;
-    long long blocks = ((work > EC ? work : EC) + 255) / 256;
-    if (blocks > 65535) blocks = 65535;
-    hipLaunchKernelGGL(route_count_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, topk_expert, P, E, n_chunks,
-                       counts, slot_token, slot_weight, EC);
-    hipLaunchKernelGGL(route_scan_kernel, dim3((E + 255) / 256), dim3(256), 0, stream, counts, n_chunks, E,
+    hipLaunchKernelGGL(route_count_kernel, dim3(n_chunks), dim3(kChunk), (size_t)E * sizeof(int32_t), stream,
+                       topk_expert, P, E, counts, slot_token, slot_weight, EC);
+    hipLaunchKernelGGL(route_scan_kernel, dim3((E + 3) / 4), dim3(256), 0, stream, counts, n_chunks, E,
                        expert_demand);
     hipLaunchKernelGGL(route_scatter_kernel, dim3(n_chunks), dim3(64), (size_t)E * sizeof(int32_t), stream,
                        topk_expert, topk_weight, P, E, k, C, counts, slot, slot_token, slot_weight);

@@ -30,7 +30,11 @@ __global__ __launch_bounds__(256) void transpose_pad_kernel(const elem* __restri
 // floats so that -0.0 and +0.0 tie), where "remaining" means strictly after the
 // previous pick in that order, so no per-expert mark is needed and E is
 // unbounded.  The rounds run twice: first to get the softmax denominator over the
-// k selected logits, then to write experts and weights.
+// k selected logits, then to write experts and weights.  With IN_REGS the row
+// (E <= 64 * kRegVals) is read once into registers; otherwise it is re-read.
+constexpr int kRegVals = 8;
+
+template <bool IN_REGS>
 __global__ __launch_bounds__(256) void topk_kernel(const float* __restrict__ logits, int T, int E, int k,
                                                    int32_t* __restrict__ topk_expert,
                                                    float* __restrict__ topk_weight) {
@@ -39,6 +43,11 @@ __global__ __launch_bounds__(256) void topk_kernel(const float* __restrict__ log
     if (token >= T) return;
     const float* l = logits + (size_t)token * E;
     constexpr int kNone = 0x7fffffff;
+    float vals[kRegVals];
+    if (IN_REGS) {
+#pragma unroll
+        for (int i = 0; i < kRegVals; ++i) vals[i] = lane + i * kWave < E ? l[lane + i * kWave] : 0.0f;
+    }
     float m = 0.0f, sum = 0.0f;
     for (int pass = 0; pass < 2; ++pass) {
         float last_v = 0.0f;
@@ -46,11 +55,17 @@ __global__ __launch_bounds__(256) void topk_kernel(const float* __restrict__ log
         for (int j = 0; j < k; ++j) {
             float bv = 0.0f;
             int bi = kNone;
-            for (int e = lane; e < E; e += kWave) {
-                const float v = l[e];
+            auto consider = [&](float v, int e) {
                 const bool avail = (j == 0) || (v < last_v) || (v == last_v && e > last_i);
                 const bool better = (bi == kNone) || (v > bv);  // e ascends: equal values keep the earlier index
                 if (avail && better) { bv = v; bi = e; }
+            };
+            if (IN_REGS) {
+#pragma unroll
+                for (int i = 0; i < kRegVals; ++i)
+                    if (lane + i * kWave < E) consider(vals[i], lane + i * kWave);
+            } else {
+                for (int e = lane; e < E; e += kWave) consider(l[e], e);
             }
 #pragma unroll
             for (int off = 32; off >= 1; off >>= 1) {
@@ -86,8 +101,11 @@ hipError_t launch_transpose_pad(const void* Wg, void* WgT, int H, int E, int E_p
 hipError_t launch_topk(const float* logits, int T, int E, int k, int32_t* topk_expert,
                        float* topk_weight, hipStream_t stream) {
     const int tokens_per_block = 256 / kWave;
-    hipLaunchKernelGGL(topk_kernel, dim3((T + tokens_per_block - 1) / tokens_per_block), dim3(256), 0, stream,
-                       logits, T, E, k, topk_expert, topk_weight);
+    const dim3 grid((T + tokens_per_block - 1) / tokens_per_block);
+    if (E <= kWave * kRegVals)
+        hipLaunchKernelGGL(topk_kernel<true>, grid, dim3(256), 0, stream, logits, T, E, k, topk_expert, topk_weight);
+    else
+        hipLaunchKernelGGL(topk_kernel<false>, grid, dim3(256), 0, stream, logits, T, E, k, topk_expert, topk_weight);
     return hipGetLastError();
 }
 

@@ -116,7 +116,7 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_kernel(GemmArgs a) 
     const int rows = a.rows_dev ? min(a.rows_dev[grp], a.rows_cap) : a.rows_fixed;
     if (row0 >= rows) return;
 
-    const elem* A = (const elem*)a.A + (size_t)grp * a.a_group_stride;
+    const elem* A = (const elem*)a.A + (a.a_row_index ? (size_t)0 : (size_t)grp * a.a_group_stride);
     const elem* B = (const elem*)a.B + (size_t)grp * a.b_group_stride;
     const int K = a.K, N = a.N;
 
@@ -125,6 +125,14 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_kernel(GemmArgs a) 
     const int wm = wave / WN, wn = wave % WN;
     const int l32 = lane & 31, g2 = lane >> 5;
 
+    // global row of each A chunk this thread loads (through the gather table when there is one)
+    int a_grow[C::A_LOADS];
+#pragma unroll
+    for (int i = 0; i < C::A_LOADS; ++i) {
+        const int r = row0 + ((tid + i * THREADS) >> 3);
+        a_grow[i] = (a.a_row_index && r < rows) ? a.a_row_index[(size_t)grp * a.a_index_stride + r] : r;
+    }
+
     u32x4 ra[C::A_LOADS], rb[C::B_LOADS];
     auto load_global = [&](int k0) {
 #pragma unroll
@@ -132,7 +140,7 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_kernel(GemmArgs a) 
             const int c = tid + i * THREADS;
             const int r = c >> 3, kc = (c & 7) * VEC;
             const bool ok = (row0 + r < rows) && (k0 + kc < K);
-            ra[i] = ok ? *(const u32x4*)(A + (size_t)(row0 + r) * a.lda + k0 + kc) : u32x4{0, 0, 0, 0};
+            ra[i] = ok ? *(const u32x4*)(A + (size_t)a_grow[i] * a.lda + k0 + kc) : u32x4{0, 0, 0, 0};
         }
 #pragma unroll
         for (int i = 0; i < C::B_LOADS; ++i) {

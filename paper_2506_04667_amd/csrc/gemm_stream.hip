@@ -25,6 +25,9 @@
 //            read back in MFMA operand order with ds_read_b64_tr_b16.
 // Rows at or beyond the live row count are fetched from the last live row (their
 // products land in output rows that are never stored); columns beyond N likewise.
+// Because every lane supplies its own global address, the activation rows can be
+// gathered straight from the token matrix through the routing table (slot -> token):
+// the payload-efficient dispatch of Sec. 3.2.1 without a packed copy.
 //
 // The MFMAs take the weight fragment as their first operand, so a lane's
 // accumulators hold, for ONE token row, runs of four consecutive output columns.
@@ -113,7 +116,7 @@ __global__ __launch_bounds__(THREADS) void ffn_gemm_stream_kernel(GemmArgs a) {
     const int l32 = lane & 31, g2 = lane >> 5;
 
     // ---- per-lane global addresses of this wavefront's four 1 KB copies per K-tile ----
-    const elem* A = (const elem*)a.A + (size_t)grp * a.a_group_stride;
+    const elem* A = (const elem*)a.A + (a.a_row_index ? (size_t)0 : (size_t)grp * a.a_group_stride);
     const elem* B = (const elem*)a.B + (size_t)grp * a.b_group_stride;
     const unsigned char* ga[2];
     const unsigned char* gb[2];
@@ -123,7 +126,8 @@ __global__ __launch_bounds__(THREADS) void ffn_gemm_stream_kernel(GemmArgs a) {
         {   // A: 16 rows x 64 B per copy
             const int r = blk * 16 + (lane >> 2), p = lane & 3;
             const int c = p ^ ((r >> 2) & 3);
-            const int grow = min(row0 + r, rows - 1);
+            int grow = min(row0 + r, rows - 1);
+            if (a.a_row_index) grow = a.a_row_index[(size_t)grp * a.a_index_stride + grow];
             ga[j] = (const unsigned char*)(A + (size_t)grow * a.lda + c * 8);
         }
         {   // B: 2 k-rows x 512 B per copy

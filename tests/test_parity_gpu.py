@@ -124,7 +124,7 @@ def test_paper_scale_sampled(oracle, name):
 
 def test_route_tie_heavy_logits(oracle):
     rng = np.random.default_rng(3)
-    for T, E, k in [(257, 4, 1), (64, 7, 7), (1000, 130, 5), (33, 1, 1), (500, 64, 64), (129, 300, 3)]:
+    for T, E, k in [(257, 4, 1), (64, 7, 7), (1000, 130, 5), (33, 1, 1), (500, 64, 64), (129, 300, 3), (50, 600, 4)]:
         logits = rng.integers(-2, 3, size=(T, E)).astype(np.float32)
         logits[logits == 0] *= rng.choice([1.0, -1.0], size=int((logits == 0).sum())).astype(np.float32)
         cfg = moe.make_config(T, 8, 8, E, k, 1.0, "relu", "f32")
