@@ -7,9 +7,12 @@
 //
 //   * tile 256 x 256 per workgroup (8 wavefronts as 2 x 4, 128 rows x 64 columns
 //     each, MFMA 32x32x16): an expert with <= 256 live rows reads its weights once;
-//   * K-tile 32 and a ring of NS LDS stages of 32 KB (A 256 x 32, B 32 x 256);
-//     global -> LDS copies are direct (global_load_lds_dwordx4: no VGPR staging),
-//     issued NS-1 K-tiles ahead, so (NS-1) x 32 KB are in flight per CU;
+//   * K-tile 32.  Weights (from HBM) go through a ring of NS LDS stages of 16 KB
+//     (32 x 256), requested NS-1 K-tiles ahead; activations (re-read from L2 by the
+//     8 column tiles of an expert) go through 2 stages of 32 KB that hold two
+//     K-tiles each (256 rows x 128 B), so that every L2 request is a full 128-byte
+//     line -- the L1's outstanding-request queue, not HBM, is what saturates first;
+//     global -> LDS copies are direct (global_load_lds_dwordx4: no VGPR staging);
 //   * the copies are issued from inline asm and waited for with explicit
 //     s_waitcnt vmcnt(n) + s_barrier, because a compiler-visible LDS-DMA makes every
 //     later LDS read wait for all outstanding copies;
@@ -20,7 +23,7 @@
 // A direct copy writes 64 lanes x 16 B to 1024 contiguous LDS bytes (lane i at
 // base + 16 i), while each lane picks its own global address; the XOR swizzles below
 // are therefore applied on the global side (which 16-byte chunk a lane fetches).
-//   A stage: row pitch 64 B; chunk c of row r lives at c ^ ((r >> 2) & 3).
+//   A stage: row pitch 128 B; chunk c of row r lives at c ^ ((r >> 1) & 7).
 //   B stage: [k][n], row pitch 512 B; chunk c of row k lives at c ^ ((k & 3) << 1);
 //            read back in MFMA operand order with ds_read_b64_tr_b16.
 // Rows at or beyond the live row count are fetched from the last live row (their
@@ -34,7 +37,7 @@
 // The epilogue applies bias and activation in registers, packs each run to 8 bytes,
 // transposes through the (now idle) LDS and stores full 128-byte row segments.
 //
-// Requires K % 32 == 0 and N % 8 == 0; other shapes use the generic kernel.
+// Requires K % 64 == 0 and N % 8 == 0; other shapes use the generic kernel.
 #include "common.h"
 #include "kernels.h"
 
@@ -46,8 +49,11 @@ typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
 constexpr int kXcds = 8;
 constexpr int BM = 256, BN = 256, BK = 32, THREADS = 512;
-constexpr int A_BYTES = BM * BK * 2, B_BYTES = BK * BN * 2, STAGE_BYTES = A_BYTES + B_BYTES;
+constexpr int A_STAGE = BM * 128;                       // 256 rows x 64 k (two K-tiles)
+constexpr int A_STAGES = 2;
+constexpr int B_STAGE = BK * BN * 2;                    // 32 k x 256 columns
 constexpr int B_ROW_BYTES = BN * 2;
+constexpr int B_REGION = A_STAGES * A_STAGE;            // weights ring starts after the activation stages
 constexpr int TM = 4, TN = 2, WN = 4;                   // 32x32 MFMA tiles per wavefront; wavefronts along N
 constexpr int EPI_BYTES_PER_WAVE = 128 * 128;           // 128 rows x 64 columns x 2 B
 
@@ -82,8 +88,8 @@ struct Frags {                                          // MFMA operands of one 
 template <class S, int NS, int ACT>
 __global__ __launch_bounds__(THREADS) void ffn_gemm_stream_kernel(GemmArgs a) {
     typedef uint16_t elem;
-    constexpr int COPIES_PER_TILE = 4;                  // per wavefront: 2 for A, 2 for B
-    static_assert(NS * STAGE_BYTES >= 8 * EPI_BYTES_PER_WAVE, "epilogue staging must fit in the ring");
+    static_assert(NS == 5, "the wait counts below are derived for five weight stages");
+    static_assert(B_REGION + NS * B_STAGE >= 8 * EPI_BYTES_PER_WAVE, "epilogue staging must fit in the rings");
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
     // ---- task decode: all tiles of an expert on one XCD (ids are dealt round-robin to XCDs) ----
@@ -115,42 +121,47 @@ __global__ __launch_bounds__(THREADS) void ffn_gemm_stream_kernel(GemmArgs a) {
     const int wm = wave / WN, wn = wave % WN;
     const int l32 = lane & 31, g2 = lane >> 5;
 
-    // ---- per-lane global addresses of this wavefront's four 1 KB copies per K-tile ----
+    // ---- per-lane global addresses of this wavefront's 1 KB copies ----
     const elem* A = (const elem*)a.A + (a.a_row_index ? (size_t)0 : (size_t)grp * a.a_group_stride);
     const elem* B = (const elem*)a.B + (size_t)grp * a.b_group_stride;
-    const unsigned char* ga[2];
-    const unsigned char* gb[2];
+    const unsigned char* ga[4];                         // activations: 4 copies of 8 rows x 128 B per K-tile pair
+    const unsigned char* gb[2];                         // weights: 2 copies of 2 k-rows x 512 B per K-tile
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int r = (wave * 4 + j) * 8 + (lane >> 3), p = lane & 7;
+        const int c = p ^ ((r >> 1) & 7);
+        int grow = min(row0 + r, rows - 1);
+        if (a.a_row_index) grow = a.a_row_index[(size_t)grp * a.a_index_stride + grow];
+        ga[j] = (const unsigned char*)(A + (size_t)grow * a.lda + c * 8);
+    }
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
-        const int blk = wave * 2 + j;
-        {   // A: 16 rows x 64 B per copy
-            const int r = blk * 16 + (lane >> 2), p = lane & 3;
-            const int c = p ^ ((r >> 2) & 3);
-            int grow = min(row0 + r, rows - 1);
-            if (a.a_row_index) grow = a.a_row_index[(size_t)grp * a.a_index_stride + grow];
-            ga[j] = (const unsigned char*)(A + (size_t)grow * a.lda + c * 8);
-        }
-        {   // B: 2 k-rows x 512 B per copy
-            const int k = blk * 2 + (lane >> 5), p = lane & 31;
-            const int c = p ^ ((k & 3) << 1);
-            const int n = min(n0 + c * 8, N - 8);
-            gb[j] = (const unsigned char*)(B + (size_t)k * a.ldb + n);
-        }
+        const int k = (wave * 2 + j) * 2 + (lane >> 5), p = lane & 31;
+        const int c = p ^ ((k & 3) << 1);
+        const int n = min(n0 + c * 8, N - 8);
+        gb[j] = (const unsigned char*)(B + (size_t)k * a.ldb + n);
     }
-    const size_t a_step = (size_t)BK * 2, b_step = (size_t)BK * a.ldb * 2;
+    const size_t b_step = (size_t)BK * a.ldb * 2;
     const uint32_t lds_base = (uint32_t)(size_t)(__attribute__((address_space(3))) unsigned char*)smem;
-    const uint32_t lds_wave = lds_base + wave * 2048;
+    const uint32_t lds_a_wave = lds_base + wave * 4096;
+    const uint32_t lds_b_wave = lds_base + B_REGION + wave * 2048;
 
-    int issue_stage = 0;
-    auto issue_tile = [&]() {
-        const uint32_t d = lds_wave + issue_stage * STAGE_BYTES;
-        copy_to_lds(ga[0], d);
-        copy_to_lds(ga[1], d + 1024);
-        copy_to_lds(gb[0], d + A_BYTES);
-        copy_to_lds(gb[1], d + A_BYTES + 1024);
-        ga[0] += a_step; ga[1] += a_step;
+    int a_issue_stage = 0, b_issue_stage = 0;
+    auto issue_a = [&]() {                              // next pair of K-tiles of the activation rows
+        const uint32_t d = lds_a_wave + a_issue_stage * A_STAGE;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            copy_to_lds(ga[j], d + j * 1024);
+            ga[j] += 128;
+        }
+        a_issue_stage ^= 1;
+    };
+    auto issue_b = [&]() {                              // next K-tile of the weights
+        const uint32_t d = lds_b_wave + b_issue_stage * B_STAGE;
+        copy_to_lds(gb[0], d);
+        copy_to_lds(gb[1], d + 1024);
         gb[0] += b_step; gb[1] += b_step;
-        issue_stage = issue_stage + 1 == NS ? 0 : issue_stage + 1;
+        b_issue_stage = b_issue_stage + 1 == NS ? 0 : b_issue_stage + 1;
     };
 
     f32x16 acc[TM][TN];
@@ -163,25 +174,28 @@ __global__ __launch_bounds__(THREADS) void ffn_gemm_stream_kernel(GemmArgs a) {
 
     // ---- per-lane LDS read offsets ----
     const int a_row = wm * TM * 32 + l32;
-    const int a_sw = (a_row >> 2) & 3;                  // same for every 32-row MFMA tile of this lane
+    const int a_sw = (a_row >> 1) & 7;                  // same for every 32-row MFMA tile of this lane
     const int L = lane & 15, nb = (lane >> 4) & 1;
     const int bk = g2 * 8 + (L >> 2);                   // k of the first transpose read; second is k + 4
-    int a_rd[2], b_rd[TN];
+    int a_rd[2][2], b_rd[TN];                           // [half of the 64-wide stage][k-step]
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks) a_rd[ks] = a_row * 64 + ((((ks << 1) | g2) ^ a_sw) << 4);
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) a_rd[h][ks] = a_row * 128 + ((((h << 2) | (ks << 1) | g2) ^ a_sw) << 4);
 #pragma unroll
     for (int tn = 0; tn < TN; ++tn) {
         const int chunk = (wn * TN + tn) * 4 + nb * 2 + ((L & 3) >> 1);
-        b_rd[tn] = A_BYTES + bk * B_ROW_BYTES + ((chunk ^ ((bk & 3) << 1)) << 4) + (L & 1) * 8;
+        b_rd[tn] = B_REGION + bk * B_ROW_BYTES + ((chunk ^ ((bk & 3) << 1)) << 4) + (L & 1) * 8;
     }
 
-    auto load_frags = [&](int stage, Frags& f, int ks) {
-        const unsigned char* st = smem + stage * STAGE_BYTES;
+    // operands of k-step ks of the K-tile in activation stage sa (half h) and weight stage sb
+    auto load_frags = [&](int sa, int h, int sb, Frags& f, int ks) {
+        const unsigned char* pa = smem + sa * A_STAGE + a_rd[h][ks];
 #pragma unroll
-        for (int tm = 0; tm < TM; ++tm) f.x[tm] = *(const s16x8*)(st + a_rd[ks] + tm * 32 * 64);
+        for (int tm = 0; tm < TM; ++tm) f.x[tm] = *(const s16x8*)(pa + tm * 32 * 128);
 #pragma unroll
         for (int tn = 0; tn < TN; ++tn) {
-            const unsigned char* p = st + b_rd[tn] + ks * 16 * B_ROW_BYTES;
+            const unsigned char* p = smem + sb * B_STAGE + b_rd[tn] + ks * 16 * B_ROW_BYTES;
             s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)p);
             s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 4 * B_ROW_BYTES));
             f.w[tn] = s16x8{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
@@ -195,30 +209,57 @@ __global__ __launch_bounds__(THREADS) void ffn_gemm_stream_kernel(GemmArgs a) {
     };
 
     // ---- main loop ----
-    // K-tile u lives in stage u % NS and is consumed as two 16-wide k-steps.  The operands of the next
-    // k-step are read from LDS while the MFMAs of the current one run; between the two k-steps of tile t
-    // the wave waits for tile t+1, and tile t+NS is requested into the stage tile t just vacated.
-    const int nk = K / BK;
-    for (int s = 0; s < NS - 1; ++s)
-        if (s < nk) issue_tile();
-    if (nk - 1 >= NS - 2) wait_copies_and_barrier<COPIES_PER_TILE * (NS - 2)>();
+    // K-tile t: weights in stage t % NS, activations in stage (t / 2) % 2, half t % 2; consumed as two
+    // 16-wide k-steps.  The operands of the next k-step are read from LDS while the MFMAs of the current one
+    // run.  Between the two k-steps of tile t the wave waits for tile t+1, then requests weights tile t+NS
+    // (into the stage tile t vacated) and, after an odd t, the activation pair (t+3)/2 (into the stage the
+    // pair t/2 vacated).  Copies of one wave complete in issue order, which in steady state reads
+    //   ... A B B | A B B | A B B ...        (A = 4 copies, B = 2 copies)
+    // so "tile t+1 has landed" is vmcnt(14) before an odd tile (only its weights are new: the newer
+    // copies are A B B A B) and vmcnt(4) before an even tile (its activation pair is new: newer are B B).
+    const int nk = K / BK;                              // even
+    const int npair = nk / 2;
+    // requests of the virtual steps -5 .. -1, in steady-state order: B0 B1 A0 B2 B3 A1 B4
+    if (0 < nk) issue_b();
+    if (1 < nk) issue_b();
+    issue_a();
+    if (2 < nk) issue_b();
+    if (3 < nk) issue_b();
+    if (1 < npair) issue_a();
+    if (4 < nk) issue_b();
+    if (nk >= 6) wait_copies_and_barrier<4>();          // A0 and B0 (and more) have landed
     else wait_copies_and_barrier<0>();
-    if (NS - 1 < nk) issue_tile();
     Frags f0, f1;
-    load_frags(0, f0, 0);
-    int stage = 0;
-    for (int t = 0; t < nk; ++t) {
-        load_frags(stage, f1, 1);
+    load_frags(0, 0, 0, f0, 0);
+    int sb = 0;                                         // weight stage of tile t
+    for (int t = 0; t < nk; t += 2) {
+        const int sa = (t >> 1) & 1;
+        // ---- even tile t ----
+        load_frags(sa, 0, sb, f1, 1);
         __builtin_amdgcn_sched_barrier(0);
         mma(f0);
         __builtin_amdgcn_sched_barrier(0);
-        stage = stage + 1 == NS ? 0 : stage + 1;
-        if (t + 1 < nk) {
-            if (nk - 2 - t >= NS - 2) wait_copies_and_barrier<COPIES_PER_TILE * (NS - 2)>();
+        int sb1 = sb + 1 == NS ? 0 : sb + 1;
+        if (t <= nk - 5) wait_copies_and_barrier<14>();
+        else wait_copies_and_barrier<0>();
+        if (t + NS < nk) issue_b();
+        load_frags(sa, 1, sb1, f0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        mma(f1);
+        __builtin_amdgcn_sched_barrier(0);
+        // ---- odd tile t + 1 ----
+        load_frags(sa, 1, sb1, f1, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        mma(f0);
+        __builtin_amdgcn_sched_barrier(0);
+        sb = sb1 + 1 == NS ? 0 : sb1 + 1;
+        if (t + 2 < nk) {
+            if (t + 1 <= nk - 5) wait_copies_and_barrier<4>();
             else wait_copies_and_barrier<0>();
-            // every wave holds the rest of tile t in registers: its stage can be refilled
-            if (t + NS < nk) issue_tile();
-            load_frags(stage, f0, 0);
+            // every wave holds the rest of the pair in registers: its activation stage can be refilled
+            if ((t + 4) / 2 < npair) issue_a();
+            if (t + 1 + NS < nk) issue_b();
+            load_frags(sa ^ 1, 0, sb, f0, 0);
             __builtin_amdgcn_sched_barrier(0);
         }
         mma(f1);
@@ -271,7 +312,7 @@ __global__ __launch_bounds__(THREADS) void ffn_gemm_stream_kernel(GemmArgs a) {
 template <class S, int NS, int ACT>
 hipError_t launch_stream_t(const GemmArgs& a, hipStream_t stream) {
     auto kernel = ffn_gemm_stream_kernel<S, NS, ACT>;
-    constexpr int lds_bytes = NS * STAGE_BYTES;
+    constexpr int lds_bytes = B_REGION + NS * B_STAGE;
     static bool attr_set = false;                       // LDS above 64 KB must be requested once per kernel
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
@@ -290,17 +331,17 @@ hipError_t launch_stream_t(const GemmArgs& a, hipStream_t stream) {
 template <class S>
 hipError_t launch_stream_act(const GemmArgs& a, hipStream_t stream) {
     switch (a.act) {
-        case 0: return launch_stream_t<S, 4, 0>(a, stream);
-        case 1: return launch_stream_t<S, 4, 1>(a, stream);
-        case 2: return launch_stream_t<S, 4, 2>(a, stream);
-        default: return launch_stream_t<S, 4, 3>(a, stream);
+        case 0: return launch_stream_t<S, 5, 0>(a, stream);
+        case 1: return launch_stream_t<S, 5, 1>(a, stream);
+        case 2: return launch_stream_t<S, 5, 2>(a, stream);
+        default: return launch_stream_t<S, 5, 3>(a, stream);
     }
 }
 
 }  // namespace
 
 bool stream_gemm_eligible(const GemmArgs& a) {
-    return a.dtype != 0 && !a.b_is_nk && !a.c_f32 && a.rows_dev != nullptr && a.K % BK == 0 && a.K >= BK &&
+    return a.dtype != 0 && !a.b_is_nk && !a.c_f32 && a.rows_dev != nullptr && a.K % (2 * BK) == 0 && a.K >= 2 * BK &&
            a.N % 8 == 0 && a.N >= 256 && a.max_rows > 128 && a.lda % 8 == 0 && a.ldb % 8 == 0 && a.ldc % 8 == 0;
 }
 
