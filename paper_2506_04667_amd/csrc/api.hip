@@ -89,6 +89,7 @@ moe_status run_gate(const moe_config* c, const Plan& p, void* ws, const void* x,
     if (e != hipSuccess) return MOE_ERR_HIP;
     moe::GemmArgs g{};
     g.A = x; g.a_group_stride = 0; g.lda = c->H;
+    g.a_row_index = nullptr; g.a_index_stride = 0; g.a_rows_total = c->T;
     g.B = wgt; g.b_group_stride = 0; g.ldb = c->H;
     g.C = logits; g.c_group_stride = 0; g.ldc = c->E;
     g.bias = gate_bias; g.bias_group_stride = 0;
@@ -127,6 +128,7 @@ moe_status run_ffn(const moe_config* c, const Plan& p, void* ws, const void* xe,
     // task t1: h = phi1(xe W1 + b1)
     g.A = xe; g.a_group_stride = (long long)p.C_pad * H; g.lda = c->H;
     g.a_row_index = slot_token; g.a_index_stride = p.C;
+    g.a_rows_total = slot_token ? c->T : p.C_pad;
     g.B = W1; g.b_group_stride = H * I; g.ldb = c->I;
     g.C = h; g.c_group_stride = (long long)p.C_pad * I; g.ldc = c->I;
     g.bias = b1; g.bias_group_stride = I;
@@ -136,6 +138,7 @@ moe_status run_ffn(const moe_config* c, const Plan& p, void* ws, const void* xe,
     // task t2: y = h W2 + b2
     g.A = h; g.a_group_stride = (long long)p.C_pad * I; g.lda = c->I;
     g.a_row_index = nullptr; g.a_index_stride = 0;
+    g.a_rows_total = p.C_pad;
     g.B = W2; g.b_group_stride = I * H; g.ldb = c->H;
     g.C = y; g.c_group_stride = (long long)p.C_pad * H; g.ldc = c->H;
     g.bias = b2; g.bias_group_stride = H;

@@ -2,23 +2,26 @@
 // (C1 <- phi1(A B1 + D1), C2 <- C1 B2 + D2; Sec. 3.1).  At the paper's expert-scaling
 // shape an expert has only ~256 live rows, so each weight matrix is used by one row
 // tile and the kernel is bound by streaming weights from HBM once, not by the
-// matrix cores.  The design therefore maximises bytes in flight per CU and keeps
-// the LDS and MFMA pipes busy at the same time:
+// matrix cores.  The design keeps the copy engine busy without a break:
 //
-//   * tile 256 x 256 per workgroup (8 wavefronts as 2 x 4, 128 rows x 64 columns
-//     each, MFMA 32x32x16): an expert with <= 256 live rows reads its weights once;
-//   * K-tile 32.  Weights (from HBM) go through a ring of NS LDS stages of 16 KB
-//     (32 x 256), requested NS-1 K-tiles ahead; activations (re-read from L2 by the
-//     8 column tiles of an expert) go through 2 stages of 32 KB that hold two
-//     K-tiles each (256 rows x 128 B), so that every L2 request is a full 128-byte
-//     line -- the L1's outstanding-request queue, not HBM, is what saturates first;
-//     global -> LDS copies are direct (global_load_lds_dwordx4: no VGPR staging);
-//   * the copies are issued from inline asm and waited for with explicit
-//     s_waitcnt vmcnt(n) + s_barrier, because a compiler-visible LDS-DMA makes every
-//     later LDS read wait for all outstanding copies;
+//   * persistent workgroups, one per CU (the paper's processors, Sec. 3, without a
+//     scheduler: the task list is static once routing is known).  A workgroup walks
+//     its (expert, row tile, column tile) tasks and treats all their K-tiles as one
+//     stream, so the copies of the next task are in flight while the current one
+//     finishes and while its epilogue runs -- no drain between tasks;
+//   * tile 256 x 256 (8 wavefronts as 2 x 4, 128 rows x 64 columns each, MFMA
+//     32x32x16): an expert with <= 256 live rows reads its weights exactly once;
+//   * K-tile 32.  Weights (from HBM) go through a ring of 4 LDS stages of 16 KB
+//     (32 x 256), requested 3 K-tiles ahead; activations (re-read from L2 by the 8
+//     column tiles of an expert) go through 2 stages of 32 KB that hold two K-tiles
+//     each (256 rows x 128 B), so every L2 request is a full 128-byte line;
+//   * global -> LDS copies are direct (global_load_lds_dwordx4: no VGPR staging),
+//     issued from inline asm and waited for with explicit s_waitcnt vmcnt(n) +
+//     s_barrier: a compiler-visible LDS-DMA makes every later LDS read wait for all
+//     outstanding copies;
 //   * MFMA operand fragments are double-buffered in registers at k-step (16)
 //     granularity: while the MFMAs of one k-step run, the LDS reads of the next are
-//     in flight, across the K-tile boundary too.
+//     in flight, across K-tile and task boundaries too.
 //
 // A direct copy writes 64 lanes x 16 B to 1024 contiguous LDS bytes (lane i at
 // base + 16 i), while each lane picks its own global address; the XOR swizzles below
@@ -35,11 +38,14 @@
 // The MFMAs take the weight fragment as their first operand, so a lane's
 // accumulators hold, for ONE token row, runs of four consecutive output columns.
 // The epilogue applies bias and activation in registers, packs each run to 8 bytes,
-// transposes through the (now idle) LDS and stores full 128-byte row segments.
+// transposes 32 rows at a time through a wave-private LDS area and stores full
+// 128-byte row segments.
 //
-// Requires K % 64 == 0 and N % 8 == 0; other shapes use the generic kernel.
+// Requires K % 64 == 0, K >= 192 and N % 8 == 0; other shapes use the generic kernel.
 #include "common.h"
 #include "kernels.h"
+
+#include <type_traits>
 
 namespace moe {
 namespace {
@@ -49,13 +55,17 @@ typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
 constexpr int kXcds = 8;
 constexpr int BM = 256, BN = 256, BK = 32, THREADS = 512;
+constexpr int TM = 4, TN = 2, WN = 4;                   // 32x32 MFMA tiles per wavefront; wavefronts along N
 constexpr int A_STAGE = BM * 128;                       // 256 rows x 64 k (two K-tiles)
 constexpr int A_STAGES = 2;
 constexpr int B_STAGE = BK * BN * 2;                    // 32 k x 256 columns
+constexpr int B_STAGES = 4;
 constexpr int B_ROW_BYTES = BN * 2;
 constexpr int B_REGION = A_STAGES * A_STAGE;            // weights ring starts after the activation stages
-constexpr int TM = 4, TN = 2, WN = 4;                   // 32x32 MFMA tiles per wavefront; wavefronts along N
-constexpr int EPI_BYTES_PER_WAVE = 128 * 128;           // 128 rows x 64 columns x 2 B
+constexpr int EPI_REGION = B_REGION + B_STAGES * B_STAGE;
+constexpr int EPI_BYTES_PER_WAVE = 32 * 128;            // 32 rows x 64 columns x 2 B
+constexpr int LDS_BYTES = EPI_REGION + 8 * EPI_BYTES_PER_WAVE;
+static_assert(LDS_BYTES <= 160 * 1024, "LDS budget of a gfx950 CU");
 
 template <class S> struct Mma16;
 template <> struct Mma16<BF16> {
@@ -69,9 +79,20 @@ template <> struct Mma16<F16> {
     }
 };
 
-// 64 lanes x 16 bytes from per-lane global addresses to LDS [lds_addr, lds_addr + 1024)
-__device__ __forceinline__ void copy_to_lds(const void* gptr, uint32_t lds_addr) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(gptr) : "memory");
+// Tell the compiler that a value is the same in every lane (it then lives in scalar registers).
+__device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
+__device__ __forceinline__ const unsigned char* uniform(const unsigned char* p) {
+    const uint64_t v = (uint64_t)p;
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return (const unsigned char*)(((uint64_t)hi << 32) | lo);
+}
+
+// 64 lanes x 16 bytes from global addresses base + per-lane byte offset to LDS [lds_addr, lds_addr + 1024).
+// A wave-uniform base in scalar registers plus 32-bit lane offsets keeps the copy cursors out of the
+// vector registers, which the accumulators and operand fragments fill almost completely.
+__device__ __forceinline__ void copy_to_lds(const unsigned char* base, uint32_t lane_off, uint32_t lds_addr) {
+    base = uniform(base);
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(lane_off), "s"(base) : "memory");
 }
 
 // own copies older than the newest N have landed; own LDS reads are complete; then meet the other waves
@@ -81,39 +102,58 @@ __device__ __forceinline__ void wait_copies_and_barrier() {
 }
 
 struct Frags {                                          // MFMA operands of one 16-wide k-step
-    s16x8 x[TM];                                        // activations, per row tile
-    s16x8 w[TN];                                        // weights, per column tile
+    u32x4 x[TM];                                        // activations, per row tile: 8 k-values of the lane's row
+    u32x4 w[TN];                                        // weights, per column tile: 8 k-values of the lane's column
+                                                        // (dwords 0-1 and 2-3 come from two transpose reads)
 };
 
-template <class S, int NS, int ACT>
-__global__ __launch_bounds__(THREADS) void ffn_gemm_stream_kernel(GemmArgs a) {
+struct Task {                                           // wave-uniform description of one output tile
+    int grp, row0, n0, rows;
+};
+
+template <class S, int ACT>
+__global__ __launch_bounds__(THREADS) void ffn_gemm_stream_kernel(GemmArgs a, int total_ids) {
     typedef uint16_t elem;
-    static_assert(NS == 5, "the wait counts below are derived for five weight stages");
-    static_assert(B_REGION + NS * B_STAGE >= 8 * EPI_BYTES_PER_WAVE, "epilogue staging must fit in the rings");
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
-    // ---- task decode: all tiles of an expert on one XCD (ids are dealt round-robin to XCDs) ----
-    const int ncol = (a.N + BN - 1) / BN;
+    const int K = a.K, N = a.N;
+    const int ncol = (N + BN - 1) / BN;
     const int nrow = (a.max_rows + BM - 1) / BM;
-    int grp, rt, ct;
-    {
-        const int id = blockIdx.x, per_group = nrow * ncol;
+    const int per_group = nrow * ncol;
+    const int stride_ids = gridDim.x;
+
+    // Task ids are dealt so that all tiles of an expert run on one XCD at the same time (workgroup ids go
+    // round-robin to the 8 XCDs, each with its own L2).  Returns false for ids that hold no work.
+    auto task_of = [&](int id, Task& t) -> bool {
+        int grp, r;
         if (a.groups >= kXcds) {
             const int x = id % kXcds, s = id / kXcds;
             grp = (s / per_group) * kXcds + x;
-            rt = (s % per_group) / ncol;
-            ct = (s % per_group) % ncol;
+            r = s % per_group;
         } else {
             grp = id / per_group;
-            rt = (id % per_group) / ncol;
-            ct = (id % per_group) % ncol;
+            r = id % per_group;
         }
+        if (grp >= a.groups) return false;
+        t.grp = uniform(grp);
+        t.row0 = uniform((r / ncol) * BM);
+        t.n0 = uniform((r % ncol) * BN);
+        t.rows = uniform(min(a.rows_dev[grp], a.rows_cap));
+        return t.row0 < t.rows;
+    };
+    // first id >= `id` (in steps of the grid size) that holds work, or total_ids
+    auto next_task = [&](int id, Task& t) -> int {
+        for (; id < total_ids; id += stride_ids)
+            if (task_of(id, t)) return id;
+        return total_ids;
+    };
+
+    int ntasks = 0;
+    {
+        Task t;
+        for (int id = blockIdx.x; id < total_ids; id += stride_ids) ntasks += task_of(id, t) ? 1 : 0;
     }
-    if (grp >= a.groups) return;
-    const int row0 = rt * BM, n0 = ct * BN;
-    const int rows = min(a.rows_dev[grp], a.rows_cap);
-    if (row0 >= rows) return;
-    const int K = a.K, N = a.N;
+    if (ntasks == 0) return;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -121,47 +161,87 @@ __global__ __launch_bounds__(THREADS) void ffn_gemm_stream_kernel(GemmArgs a) {
     const int wm = wave / WN, wn = wave % WN;
     const int l32 = lane & 31, g2 = lane >> 5;
 
-    // ---- per-lane global addresses of this wavefront's 1 KB copies ----
-    const elem* A = (const elem*)a.A + (a.a_row_index ? (size_t)0 : (size_t)grp * a.a_group_stride);
-    const elem* B = (const elem*)a.B + (size_t)grp * a.b_group_stride;
-    const unsigned char* ga[4];                         // activations: 4 copies of 8 rows x 128 B per K-tile pair
-    const unsigned char* gb[2];                         // weights: 2 copies of 2 k-rows x 512 B per K-tile
+    // ---- addresses of this wavefront's 1 KB copies, per task: uniform base + per-lane byte offset ----
+    // activations: 4 copies of 8 rows x 128 B per K-tile pair; weights: 2 copies of 2 k-rows x 512 B per K-tile
+    auto task_bases = [&](const Task& t, const unsigned char*& base_a, const unsigned char*& base_b) __attribute__((always_inline)) {
+        base_a = uniform((const unsigned char*)((const elem*)a.A + (a.a_row_index ? (size_t)0 : (size_t)t.grp * a.a_group_stride)));
+        base_b = uniform((const unsigned char*)((const elem*)a.B + (size_t)t.grp * a.b_group_stride));
+    };
+    auto task_offsets = [&](const Task& t, uint32_t (&oa)[4], uint32_t (&ob)[2]) __attribute__((always_inline)) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const int r = (wave * 4 + j) * 8 + (lane >> 3), p = lane & 7;
-        const int c = p ^ ((r >> 1) & 7);
-        int grow = min(row0 + r, rows - 1);
-        if (a.a_row_index) grow = a.a_row_index[(size_t)grp * a.a_index_stride + grow];
-        ga[j] = (const unsigned char*)(A + (size_t)grow * a.lda + c * 8);
-    }
+        for (int j = 0; j < 4; ++j) {
+            const int r = (wave * 4 + j) * 8 + (lane >> 3), p = lane & 7;
+            const int c = p ^ ((r >> 1) & 7);
+            int grow = min(t.row0 + r, t.rows - 1);
+            if (a.a_row_index) grow = a.a_row_index[(size_t)t.grp * a.a_index_stride + grow];
+            oa[j] = (uint32_t)grow * (uint32_t)(a.lda * 2) + c * 16;
+        }
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        const int k = (wave * 2 + j) * 2 + (lane >> 5), p = lane & 31;
-        const int c = p ^ ((k & 3) << 1);
-        const int n = min(n0 + c * 8, N - 8);
-        gb[j] = (const unsigned char*)(B + (size_t)k * a.ldb + n);
+        for (int j = 0; j < 2; ++j) {
+            const int k = (wave * 2 + j) * 2 + (lane >> 5), p = lane & 31;
+            const int c = p ^ ((k & 3) << 1);
+            const int n = min(t.n0 + c * 8, N - 8);
+            ob[j] = (uint32_t)k * (uint32_t)(a.ldb * 2) + n * 2;
+        }
+    };
+
+    const int nk = K / BK;                              // K-tiles per task (even, >= 6)
+    const int npair = nk / 2;
+    const int U = ntasks * nk;                          // K-tiles in this workgroup's whole stream
+
+    Task cur, nxt;                                      // task being multiplied; the one after it
+    int nxt_id = next_task(blockIdx.x, cur);
+    const unsigned char *a_base, *b_base;               // copy cursors: bases advance along K
+    const unsigned char *na_base, *nb_base;             // bases of the task after `cur`
+    uint32_t a_off[4], b_off[2], na_off[4], nb_off[2];
+    task_bases(cur, a_base, b_base);
+    task_offsets(cur, a_off, b_off);
+    nxt = cur;
+    nxt_id = next_task(nxt_id + stride_ids, nxt);
+    if (nxt_id < total_ids) {
+        task_bases(nxt, na_base, nb_base);
+        task_offsets(nxt, na_off, nb_off);
+    } else {
+        na_base = a_base; nb_base = b_base;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) na_off[j] = a_off[j];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) nb_off[j] = b_off[j];
     }
+    int a_left = npair, b_left = nk;                    // requests left before a cursor moves to the next task
+
     const size_t b_step = (size_t)BK * a.ldb * 2;
     const uint32_t lds_base = (uint32_t)(size_t)(__attribute__((address_space(3))) unsigned char*)smem;
     const uint32_t lds_a_wave = lds_base + wave * 4096;
     const uint32_t lds_b_wave = lds_base + B_REGION + wave * 2048;
 
     int a_issue_stage = 0, b_issue_stage = 0;
-    auto issue_a = [&]() {                              // next pair of K-tiles of the activation rows
+    auto issue_a = [&]() __attribute__((always_inline)) {                              // next pair of K-tiles of the activation rows
         const uint32_t d = lds_a_wave + a_issue_stage * A_STAGE;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            copy_to_lds(ga[j], d + j * 1024);
-            ga[j] += 128;
+        for (int j = 0; j < 4; ++j) copy_to_lds(a_base, a_off[j], d + j * 1024);
+        if (--a_left == 0) {
+            a_left = npair;
+            a_base = na_base;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) a_off[j] = na_off[j];
+        } else {
+            a_base += 128;
         }
         a_issue_stage ^= 1;
     };
-    auto issue_b = [&]() {                              // next K-tile of the weights
+    auto issue_b = [&]() __attribute__((always_inline)) {                              // next K-tile of the weights
         const uint32_t d = lds_b_wave + b_issue_stage * B_STAGE;
-        copy_to_lds(gb[0], d);
-        copy_to_lds(gb[1], d + 1024);
-        gb[0] += b_step; gb[1] += b_step;
-        b_issue_stage = b_issue_stage + 1 == NS ? 0 : b_issue_stage + 1;
+        copy_to_lds(b_base, b_off[0], d);
+        copy_to_lds(b_base, b_off[1], d + 1024);
+        if (--b_left == 0) {
+            b_left = nk;
+            b_base = nb_base;
+            b_off[0] = nb_off[0]; b_off[1] = nb_off[1];
+        } else {
+            b_base += b_step;
+        }
+        b_issue_stage = b_issue_stage + 1 == B_STAGES ? 0 : b_issue_stage + 1;
     };
 
     f32x16 acc[TM][TN];
@@ -175,7 +255,7 @@ __global__ __launch_bounds__(THREADS) void ffn_gemm_stream_kernel(GemmArgs a) {
     // ---- per-lane LDS read offsets ----
     const int a_row = wm * TM * 32 + l32;
     const int a_sw = (a_row >> 1) & 7;                  // same for every 32-row MFMA tile of this lane
-    const int L = lane & 15, nb = (lane >> 4) & 1;
+    const int L = lane & 15, nb16 = (lane >> 4) & 1;
     const int bk = g2 * 8 + (L >> 2);                   // k of the first transpose read; second is k + 4
     int a_rd[2][2], b_rd[TN];                           // [half of the 64-wide stage][k-step]
 #pragma unroll
@@ -184,165 +264,243 @@ __global__ __launch_bounds__(THREADS) void ffn_gemm_stream_kernel(GemmArgs a) {
         for (int ks = 0; ks < 2; ++ks) a_rd[h][ks] = a_row * 128 + ((((h << 2) | (ks << 1) | g2) ^ a_sw) << 4);
 #pragma unroll
     for (int tn = 0; tn < TN; ++tn) {
-        const int chunk = (wn * TN + tn) * 4 + nb * 2 + ((L & 3) >> 1);
+        const int chunk = (wn * TN + tn) * 4 + nb16 * 2 + ((L & 3) >> 1);
         b_rd[tn] = B_REGION + bk * B_ROW_BYTES + ((chunk ^ ((bk & 3) << 1)) << 4) + (L & 1) * 8;
     }
 
-    // operands of k-step ks of the K-tile in activation stage sa (half h) and weight stage sb
-    auto load_frags = [&](int sa, int h, int sb, Frags& f, int ks) {
+    // Read i (0..7) of the operands of k-step ks of the K-tile in activation stage sa (half h) and weight
+    // stage sb: the first column tile's weights, the row tiles' activations, the second column tile's weights.
+    auto read_frag = [&](int i, int sa, int h, int sb, Frags& f, int ks) __attribute__((always_inline)) {
+        const unsigned char* pw = smem + sb * B_STAGE + ks * 16 * B_ROW_BYTES;
         const unsigned char* pa = smem + sa * A_STAGE + a_rd[h][ks];
-#pragma unroll
-        for (int tm = 0; tm < TM; ++tm) f.x[tm] = *(const s16x8*)(pa + tm * 32 * 128);
-#pragma unroll
-        for (int tn = 0; tn < TN; ++tn) {
-            const unsigned char* p = smem + sb * B_STAGE + b_rd[tn] + ks * 16 * B_ROW_BYTES;
-            s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)p);
-            s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 4 * B_ROW_BYTES));
-            f.w[tn] = s16x8{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+        switch (i) {
+            case 0: case 1: case 3: case 4: {
+                const int tn = i >= 3, half = (i == 1 || i == 4);
+                const u32x2 t = __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                                                              (lds_s16x4*)(pw + b_rd[tn] + half * 4 * B_ROW_BYTES)));
+                f.w[tn][2 * half] = t[0];
+                f.w[tn][2 * half + 1] = t[1];
+                break;
+            }
+            case 2: f.x[0] = *(const u32x4*)(pa); break;
+            case 5: f.x[1] = *(const u32x4*)(pa + 1 * 32 * 128); break;
+            case 6: f.x[2] = *(const u32x4*)(pa + 2 * 32 * 128); break;
+            default: f.x[3] = *(const u32x4*)(pa + 3 * 32 * 128); break;
         }
     };
-    auto mma = [&](const Frags& f) {
-#pragma unroll
-        for (int tm = 0; tm < TM; ++tm)
-#pragma unroll
-            for (int tn = 0; tn < TN; ++tn) acc[tm][tn] = Mma16<S>::run(f.w[tn], f.x[tm], acc[tm][tn]);
+    // MFMA i (0..7) of a k-step: row tile i / 2, column tile i % 2
+    auto mma_one = [&](int i, const Frags& f) __attribute__((always_inline)) {
+        const int tm = i >> 1, tn = i & 1;
+        acc[tm][tn] = Mma16<S>::run(__builtin_bit_cast(s16x8, f.w[tn]), __builtin_bit_cast(s16x8, f.x[tm]), acc[tm][tn]);
     };
-
-    // ---- main loop ----
-    // K-tile t: weights in stage t % NS, activations in stage (t / 2) % 2, half t % 2; consumed as two
-    // 16-wide k-steps.  The operands of the next k-step are read from LDS while the MFMAs of the current one
-    // run.  Between the two k-steps of tile t the wave waits for tile t+1, then requests weights tile t+NS
-    // (into the stage tile t vacated) and, after an odd t, the activation pair (t+3)/2 (into the stage the
-    // pair t/2 vacated).  Copies of one wave complete in issue order, which in steady state reads
-    //   ... A B B | A B B | A B B ...        (A = 4 copies, B = 2 copies)
-    // so "tile t+1 has landed" is vmcnt(14) before an odd tile (only its weights are new: the newer
-    // copies are A B B A B) and vmcnt(4) before an even tile (its activation pair is new: newer are B B).
-    const int nk = K / BK;                              // even
-    const int npair = nk / 2;
-    // requests of the virtual steps -5 .. -1, in steady-state order: B0 B1 A0 B2 B3 A1 B4
-    if (0 < nk) issue_b();
-    if (1 < nk) issue_b();
-    issue_a();
-    if (2 < nk) issue_b();
-    if (3 < nk) issue_b();
-    if (1 < npair) issue_a();
-    if (4 < nk) issue_b();
-    if (nk >= 6) wait_copies_and_barrier<4>();          // A0 and B0 (and more) have landed
-    else wait_copies_and_barrier<0>();
-    Frags f0, f1;
-    load_frags(0, 0, 0, f0, 0);
-    int sb = 0;                                         // weight stage of tile t
-    for (int t = 0; t < nk; t += 2) {
-        const int sa = (t >> 1) & 1;
-        // ---- even tile t ----
-        load_frags(sa, 0, sb, f1, 1);
-        __builtin_amdgcn_sched_barrier(0);
-        mma(f0);
-        __builtin_amdgcn_sched_barrier(0);
-        int sb1 = sb + 1 == NS ? 0 : sb + 1;
-        if (t <= nk - 5) wait_copies_and_barrier<14>();
-        else wait_copies_and_barrier<0>();
-        if (t + NS < nk) issue_b();
-        load_frags(sa, 1, sb1, f0, 0);
-        __builtin_amdgcn_sched_barrier(0);
-        mma(f1);
-        __builtin_amdgcn_sched_barrier(0);
-        // ---- odd tile t + 1 ----
-        load_frags(sa, 1, sb1, f1, 1);
-        __builtin_amdgcn_sched_barrier(0);
-        mma(f0);
-        __builtin_amdgcn_sched_barrier(0);
-        sb = sb1 + 1 == NS ? 0 : sb1 + 1;
-        if (t + 2 < nk) {
-            if (t + 1 <= nk - 5) wait_copies_and_barrier<4>();
-            else wait_copies_and_barrier<0>();
-            // every wave holds the rest of the pair in registers: its activation stage can be refilled
-            if ((t + 4) / 2 < npair) issue_a();
-            if (t + 1 + NS < nk) issue_b();
-            load_frags(sa ^ 1, 0, sb, f0, 0);
+    // One k-step with the operand reads of the next one slotted between its MFMAs, so that issuing them
+    // costs no matrix-pipe time.  The order is pinned: the scheduler may not move anything across a fence.
+    auto step_same_tile = [&](const Frags& cur_f, Frags& nxt_f, int sa, int h, int sb, int ks) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            mma_one(i, cur_f);
+            read_frag(i, sa, h, sb, nxt_f, ks);
             __builtin_amdgcn_sched_barrier(0);
         }
-        mma(f1);
-        __builtin_amdgcn_sched_barrier(0);
-    }
+    };
 
-    // ---- epilogue ----
-    // All waves must be done reading the ring before it is reused as staging space.
-    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
-    unsigned char* epi = smem + wave * EPI_BYTES_PER_WAVE;   // [128 rows][64 columns] of this wavefront, 128 B pitch
-    const int col_w = n0 + wn * (TN * 32);                   // first column of this wavefront
+    // ---- epilogue of task `cur`: bias, activation, conversion, transposed store; then advance to the next task ----
+    unsigned char* epi = smem + EPI_REGION + wave * EPI_BYTES_PER_WAVE;   // [32 rows][64 columns], 128 B pitch
+    auto finish_task = [&]() __attribute__((always_inline)) {
+        const int col_w = cur.n0 + wn * (TN * 32);      // first column of this wavefront
+        const size_t c_base = (size_t)cur.grp * a.c_group_stride;
+        u32x2 bias_bits[TN][4];
+        if (a.bias) {
 #pragma unroll
-    for (int tn = 0; tn < TN; ++tn) {
+            for (int tn = 0; tn < TN; ++tn)
 #pragma unroll
-        for (int qa = 0; qa < 4; ++qa) {
-            // accumulator elements 4 qa .. 4 qa + 3: columns c .. c + 3 of one token row
-            const int c_local = tn * 32 + qa * 8 + g2 * 4;
-            float bias[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-            if (a.bias) {
-                const int c = min(col_w + c_local, N - 4);
-                const u32x2 bv = *(const u32x2*)((const elem*)a.bias + (size_t)grp * a.bias_group_stride + c);
-#pragma unroll
-                for (int b = 0; b < 4; ++b) {
-                    const uint32_t word = b < 2 ? bv[0] : bv[1];
-                    bias[b] = bits16_to_float<S>((uint16_t)((b & 1) ? (word >> 16) : (word & 0xffffu)));
+                for (int qa = 0; qa < 4; ++qa) {
+                    const int c = min(col_w + tn * 32 + qa * 8 + g2 * 4, N - 4);
+                    bias_bits[tn][qa] = *(const u32x2*)((const elem*)a.bias + (size_t)cur.grp * a.bias_group_stride + c);
                 }
-            }
+        }
 #pragma unroll
-            for (int tm = 0; tm < TM; ++tm) {
-                float v[4];
+        for (int tm = 0; tm < TM; ++tm) {
+            // accumulator elements 4 qa .. 4 qa + 3 of tile (tm, tn): columns c .. c + 3 of token row l32
 #pragma unroll
-                for (int b = 0; b < 4; ++b) v[b] = apply_act_t<ACT>(acc[tm][tn][qa * 4 + b] + bias[b]);
-                const int r_local = tm * 32 + l32;
-                const int chunk = (c_local >> 3) ^ ((r_local >> 1) & 7);
-                *(u32x2*)(epi + r_local * 128 + (chunk << 4) + g2 * 8) = u32x2{pack2<S>(v[0], v[1]), pack2<S>(v[2], v[3])};
+            for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+                for (int qa = 0; qa < 4; ++qa) {
+                    float v[4];
+#pragma unroll
+                    for (int b = 0; b < 4; ++b) {
+                        float bias = 0.0f;
+                        if (a.bias) {
+                            const uint32_t word = b < 2 ? bias_bits[tn][qa][0] : bias_bits[tn][qa][1];
+                            bias = bits16_to_float<S>((uint16_t)((b & 1) ? (word >> 16) : (word & 0xffffu)));
+                        }
+                        v[b] = apply_act_t<ACT>(acc[tm][tn][qa * 4 + b] + bias);
+                        acc[tm][tn][qa * 4 + b] = 0.0f;
+                    }
+                    const int chunk = (tn * 4 + qa) ^ ((l32 >> 1) & 7);
+                    *(u32x2*)(epi + l32 * 128 + (chunk << 4) + g2 * 8) = u32x2{pack2<S>(v[0], v[1]), pack2<S>(v[2], v[3])};
+                }
+            // a wavefront's LDS operations complete in order: the reads below see the writes above, and the
+            // writes of the next pass come after these reads
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int r_local = i * 8 + (lane >> 3), chunk = lane & 7;
+                const u32x4 v = *(const u32x4*)(epi + r_local * 128 + ((chunk ^ ((r_local >> 1) & 7)) << 4));
+                const int row = cur.row0 + (wm * TM + tm) * 32 + r_local, col = col_w + chunk * 8;
+                if (row < cur.rows && col < N) *(u32x4*)((elem*)a.C + c_base + (size_t)row * a.ldc + col) = v;
             }
         }
-    }
-    // a wavefront's LDS operations complete in order: the reads below see the writes above
-    const size_t c_base = (size_t)grp * a.c_group_stride;
+        // Both copy cursors have moved on to `nxt` by now (they run at most 4 K-tiles ahead and K >= 6
+        // K-tiles), so its successor's addresses can replace `nxt`'s.  The loads this needs are waited for
+        // here, where every copy in flight is one the next K-tiles need anyway.
+        cur = nxt;
+        if (nxt_id < total_ids) {
+            nxt_id = next_task(nxt_id + stride_ids, nxt);
+            if (nxt_id < total_ids) {
+                task_bases(nxt, na_base, nb_base);
+                task_offsets(nxt, na_off, nb_off);
+            }
+        }
+    };
+
+    // ---- main loop over the stream of K-tiles u = 0 .. U-1 ----
+    // K-tile u: weights in stage u % 4, activations in stage (u / 2) % 2, half u % 2; consumed as two
+    // 16-wide k-steps.  The operands of the next k-step are read from LDS while the MFMAs of the current one
+    // run.  Between the two k-steps of tile u the wave waits for tile u+1, then requests weights tile u+4
+    // (into the stage tile u vacated) and, after an odd u, the activation pair (u+3)/2 (into the stage the
+    // pair u/2 vacated).  Copies of one wave complete in issue order, which in steady state reads
+    //   ... B | A B | B | A B | B | A B ...      (A = 4 copies, B = 2 copies; one group per K-tile)
+    // so "tile u+1 has landed" is vmcnt(8) before an odd tile (only its weights are new: the newer copies
+    // are B A B) and vmcnt(4) before an even tile (its activation pair is new: the newer copies are B B).
+    // Other vector memory operations in flight only make these waits stricter.
+    // requests of the virtual steps -4 .. -1, in steady-state order: B0 A0 B1 B2 A1 B3
+    issue_b();
+    issue_a();
+    issue_b();
+    issue_b();
+    issue_a();
+    issue_b();
+    wait_copies_and_barrier<4>();                       // A0 and B0 (and more) have landed
+    Frags f0, f1;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        const int r_local = i * 8 + (lane >> 3), chunk = lane & 7;
-        const u32x4 v = *(const u32x4*)(epi + r_local * 128 + ((chunk ^ ((r_local >> 1) & 7)) << 4));
-        const int row = row0 + wm * (TM * 32) + r_local, col = col_w + chunk * 8;
-        if (row < rows && col < N) *(u32x4*)((elem*)a.C + c_base + (size_t)row * a.ldc + col) = v;
-    }
+    for (int i = 0; i < 8; ++i) read_frag(i, 0, 0, 0, f0, 0);
+    int sb = 0;                                         // weight stage of tile u
+    int k_done = 0;                                     // K-tiles of `cur` multiplied so far
+
+    // One pair of K-tiles (u even, u + 1).  STEADY: u <= U - 6, so every request below exists and the wait
+    // counts above hold; otherwise nothing more is requested and the waits are for everything in flight.
+    // LAST: u + 2 == U, nothing follows.
+    auto pair_of_tiles = [&](int u, auto steady_tag, auto last_tag) __attribute__((always_inline)) {
+        constexpr bool STEADY = decltype(steady_tag)::value, LAST = decltype(last_tag)::value;
+        const int sa = (u >> 1) & 1;
+        // ---- even tile u: first k-step, reading its second ----
+        step_same_tile(f0, f1, sa, 0, sb, 1);
+        // second k-step: half of its MFMAs cover the wait for tile u+1, whose first k-step is then read
+        const int sb1 = (sb + 1) & (B_STAGES - 1);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) mma_one(i, f1);
+        __builtin_amdgcn_sched_barrier(0);
+        wait_copies_and_barrier<STEADY ? 8 : 0>();
+        if (STEADY) issue_b();
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 4; i < 8; ++i) {
+            mma_one(i, f1);
+            read_frag(2 * (i - 4), sa, 1, sb1, f0, 0);
+            read_frag(2 * (i - 4) + 1, sa, 1, sb1, f0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        // ---- odd tile u + 1 ----
+        step_same_tile(f0, f1, sa, 1, sb1, 1);
+        sb = (sb1 + 1) & (B_STAGES - 1);
+        if (!LAST) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) mma_one(i, f1);
+            __builtin_amdgcn_sched_barrier(0);
+            wait_copies_and_barrier<STEADY ? 4 : 0>();
+            // every wave holds the rest of the pair in registers: its activation stage can be refilled
+            if (STEADY) {
+                issue_a();
+                issue_b();
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int i = 4; i < 8; ++i) {
+                mma_one(i, f1);
+                read_frag(2 * (i - 4), sa ^ 1, 0, sb, f0, 0);
+                read_frag(2 * (i - 4) + 1, sa ^ 1, 0, sb, f0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) mma_one(i, f1);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        k_done += 2;
+        if (k_done == nk) {
+            k_done = 0;
+            finish_task();
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+    int u = 0;
+    for (; u <= U - 6; u += 2) pair_of_tiles(u, std::true_type{}, std::false_type{});
+    pair_of_tiles(u, std::false_type{}, std::false_type{});          // u == U - 4
+    pair_of_tiles(u + 2, std::false_type{}, std::true_type{});       // u == U - 2
 }
 
-template <class S, int NS, int ACT>
+int device_cu_count() {
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+            n = 256;
+        cus = n;
+    }
+    return cus;
+}
+
+template <class S, int ACT>
 hipError_t launch_stream_t(const GemmArgs& a, hipStream_t stream) {
-    auto kernel = ffn_gemm_stream_kernel<S, NS, ACT>;
-    constexpr int lds_bytes = B_REGION + NS * B_STAGE;
+    auto kernel = ffn_gemm_stream_kernel<S, ACT>;
     static bool attr_set = false;                       // LDS above 64 KB must be requested once per kernel
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     const long long ncol = (a.N + BN - 1) / BN, nrow = (a.max_rows + BM - 1) / BM;
     const long long groups = a.groups >= kXcds ? (long long)(a.groups + kXcds - 1) / kXcds * kXcds : a.groups;
-    const long long blocks = groups * nrow * ncol;
-    if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(THREADS), lds_bytes, stream, a);
+    const long long total = groups * nrow * ncol;
+    if (total > 0x7fffffffLL) return hipErrorInvalidValue;
+    // one persistent workgroup per CU; a multiple of the XCD count keeps an expert's tiles on one XCD
+    long long grid = device_cu_count() / kXcds * kXcds;
+    if (grid < kXcds) grid = kXcds;
+    if (grid > total) grid = total;
+    hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(THREADS), LDS_BYTES, stream, a, (int)total);
     return hipGetLastError();
 }
 
 template <class S>
 hipError_t launch_stream_act(const GemmArgs& a, hipStream_t stream) {
     switch (a.act) {
-        case 0: return launch_stream_t<S, 5, 0>(a, stream);
-        case 1: return launch_stream_t<S, 5, 1>(a, stream);
-        case 2: return launch_stream_t<S, 5, 2>(a, stream);
-        default: return launch_stream_t<S, 5, 3>(a, stream);
+        case 0: return launch_stream_t<S, 0>(a, stream);
+        case 1: return launch_stream_t<S, 1>(a, stream);
+        case 2: return launch_stream_t<S, 2>(a, stream);
+        default: return launch_stream_t<S, 3>(a, stream);
     }
 }
 
 }  // namespace
 
 bool stream_gemm_eligible(const GemmArgs& a) {
-    return a.dtype != 0 && !a.b_is_nk && !a.c_f32 && a.rows_dev != nullptr && a.K % (2 * BK) == 0 && a.K >= 2 * BK &&
-           a.N % 8 == 0 && a.N >= 256 && a.max_rows > 128 && a.lda % 8 == 0 && a.ldb % 8 == 0 && a.ldc % 8 == 0;
+    return a.dtype != 0 && !a.b_is_nk && !a.c_f32 && a.rows_dev != nullptr && a.K % (2 * BK) == 0 &&
+           a.K >= 6 * BK && a.N % 8 == 0 && a.N >= 256 && a.max_rows > 128 && a.lda % 8 == 0 && a.ldb % 8 == 0 &&
+           a.ldc % 8 == 0 &&
+           // copies address an operand as a 64-bit base plus 32-bit byte offsets
+           (long long)a.a_rows_total * a.lda * 2 < (1ll << 32) && (long long)a.K * a.ldb * 2 < (1ll << 32);
 }
 
 hipError_t launch_grouped_gemm_stream(const GemmArgs& a, hipStream_t stream) {

@@ -17,6 +17,7 @@ struct GemmArgs {
     // optional gather: row r of group g is A[a_row_index[g * a_index_stride + r]] (a_group_stride unused);
     // entries of live rows are valid row numbers of A
     const int32_t* a_row_index; long long a_index_stride;
+    long long a_rows_total;                                 // rows of A reachable from one group's base
     const void* B; long long b_group_stride; int ldb;
     void* C; long long c_group_stride; int ldc;
     const void* bias; long long bias_group_stride;          // nullptr = none
