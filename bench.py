@@ -48,7 +48,7 @@ def parse_args():
 
 def read_traffic(workload, dtype):
     """HBM bytes per launch of the dominant kernel, from the committed counter summary (or None)."""
-    path = os.path.join(ROOT, "profiles", "grouped_gemm_%s_%s_traffic.txt" % (dtype, workload))
+    path = os.path.join(ROOT, "profiles", "ffn_gemm_stream_%s_%s_traffic.txt" % (dtype, workload))
     try:
         m = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(path).read(), flags=re.M)
         return float(m.group(1)) if m else None
@@ -136,15 +136,16 @@ def main():
     hbm_time = bytes_per_launch / (PEAK["hbm_gbs"] * 1e9)
     mfma_time = flops_per_launch / (PEAK["mfma_tflops"][w.dtype] * 1e12)
     traffic = read_traffic(w.name, w.dtype)
+    kernel_name = ("ffn_gemm_stream_kernel" if w.dtype != "f32" else "grouped_gemm_kernel") + " (expert FFN, 2 launches/step)"
     ach_gbs = bytes_per_launch / (launch_ms * 1e-3) / 1e9
     ach_tf = flops_per_launch / (launch_ms * 1e-3) / 1e12
     roof_hbm = {"bound": "hbm", "achieved": round(ach_gbs, 1), "peak": PEAK["hbm_gbs"], "unit": "GB/s",
                 "frac": round(ach_gbs / PEAK["hbm_gbs"], 4), "traffic": traffic,
-                "kernel": "grouped_gemm_kernel (FFN, 2 launches/step)", "launch_ms": round(launch_ms, 4),
+                "kernel": kernel_name, "launch_ms": round(launch_ms, 4),
                 "algorithmic_bytes_per_launch": bytes_per_launch}
     roof_mfma = {"bound": "mfma", "achieved": round(ach_tf, 1), "peak": PEAK["mfma_tflops"][w.dtype],
                  "unit": "TFLOP/s", "frac": round(ach_tf / PEAK["mfma_tflops"][w.dtype], 4), "traffic": traffic,
-                 "kernel": "grouped_gemm_kernel (FFN, 2 launches/step)", "launch_ms": round(launch_ms, 4),
+                 "kernel": kernel_name, "launch_ms": round(launch_ms, 4),
                  "algorithmic_flops_per_launch": flops_per_launch}
     binding_is_hbm = hbm_time >= mfma_time
     roofline = roof_hbm if binding_is_hbm else roof_mfma
