@@ -132,7 +132,8 @@ def main():
     ffn_ms = stage_ms["expert_ffn"]
     launch_ms = ffn_ms / 2.0
     flops_per_launch = 2.0 * R * H * I
-    bytes_per_launch = (E * H * I + R * H + R * I) * el            # weights once + A rows + C rows; the sum is the same for both launches
+    live = int((demand > 0).sum())                                 # experts nobody picked cost no weight traffic
+    bytes_per_launch = (live * H * I + R * H + R * I) * el         # weights once + A rows + C rows; the sum is the same for both launches
     hbm_time = bytes_per_launch / (PEAK["hbm_gbs"] * 1e9)
     mfma_time = flops_per_launch / (PEAK["mfma_tflops"][w.dtype] * 1e12)
     traffic = read_traffic(w.name, w.dtype)
@@ -178,7 +179,7 @@ def main():
         "tokens_per_s": round(T / (ms_per_step * 1e-3), 1),
         "kept_rows": R, "dropped_pairs": dropped,
         "expert_demand": {"min": int(demand.min()), "median": int(demand.median()), "max": int(demand.max()),
-                          "empty": int((demand == 0).sum())},
+                          "empty": E - live},
         "stage_ms": {n: round(v, 4) for n, v in stage_ms.items()},
         "ffn_tflops": round(4.0 * R * H * I / (ffn_ms * 1e-3) / 1e12, 1),
         "ffn_mfma_frac": round(4.0 * R * H * I / (ffn_ms * 1e-3) / 1e12 / PEAK["mfma_tflops"][w.dtype], 4),

@@ -19,7 +19,7 @@ size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 struct Plan {
     int C, C_pad, E_pad, elem;
-    size_t off_wgt, off_logits, off_slot_token, off_slot_weight, off_counts, off_h, off_y, total;
+    size_t off_wgt, off_logits, off_slot_token, off_slot_weight, off_counts, off_units, off_h, off_y, total;
 };
 
 moe_status check_config(const moe_config* c) {
@@ -67,6 +67,7 @@ moe_status make_plan(const moe_config* c, Plan* p) {
     p->off_slot_token = take(E * (size_t)p->C * 4);
     p->off_slot_weight = take(E * (size_t)p->C * 4);
     p->off_counts = take((size_t)moe::route_chunks((long long)T * c->k) * E * 4);
+    p->off_units = take(moe::ffn_units_ints(c->E, p->C) * 4);
     p->off_h = take(rows * I * el);
     p->off_y = take(rows * H * el);
     p->total = off;
@@ -125,6 +126,14 @@ moe_status run_ffn(const moe_config* c, const Plan& p, void* ws, const void* xe,
     g.rows_dev = expert_demand; g.rows_fixed = 0; g.rows_cap = p.C;
     g.groups = c->E; g.max_rows = p.C;
     g.dtype = c->dtype; g.b_is_nk = false; g.c_f32 = false;
+    // both tasks walk the same live (expert, row tile) units
+    int32_t* units = (int32_t*)ws_at(ws, p.off_units);
+    hipError_t e = hipSuccess;
+    if (c->dtype != MOE_F32) {                          // only the 16-bit streaming kernel uses the list
+        e = moe::launch_ffn_units(expert_demand, p.C, c->E, p.C, units, s);
+        if (e != hipSuccess) return MOE_ERR_HIP;
+        g.units = units;
+    }
     // task t1: h = phi1(xe W1 + b1)
     g.A = xe; g.a_group_stride = (long long)p.C_pad * H; g.lda = c->H;
     g.a_row_index = slot_token; g.a_index_stride = p.C;
@@ -133,7 +142,7 @@ moe_status run_ffn(const moe_config* c, const Plan& p, void* ws, const void* xe,
     g.C = h; g.c_group_stride = (long long)p.C_pad * I; g.ldc = c->I;
     g.bias = b1; g.bias_group_stride = I;
     g.N = c->I; g.K = c->H; g.act = c->act;
-    hipError_t e = moe::launch_grouped_gemm(g, s);
+    e = moe::launch_grouped_gemm(g, s);
     if (e != hipSuccess) return MOE_ERR_HIP;
     // task t2: y = h W2 + b2
     g.A = h; g.a_group_stride = (long long)p.C_pad * I; g.lda = c->I;

@@ -5,10 +5,12 @@
 // matrix cores.  The design keeps the copy engine busy without a break:
 //
 //   * persistent workgroups, one per CU (the paper's processors, Sec. 3, without a
-//     scheduler: the task list is static once routing is known).  A workgroup walks
-//     its (expert, row tile, column tile) tasks and treats all their K-tiles as one
-//     stream, so the copies of the next task are in flight while the current one
-//     finishes and while its epilogue runs -- no drain between tasks;
+//     scheduler: once routing is known the live tasks are a fixed list, compacted on
+//     the device so that empty experts cost nothing and every XCD gets an equal
+//     share whatever the routing skew).  A workgroup walks its (expert, row tile,
+//     column tile) tasks and treats all their K-tiles as one stream, so the copies
+//     of the next task are in flight while the current one finishes and while its
+//     epilogue runs -- no drain between tasks;
 //   * tile 256 x 256 (8 wavefronts as 2 x 4, 128 rows x 64 columns each, MFMA
 //     32x32x16): an expert with <= 256 live rows reads its weights exactly once;
 //   * K-tile 32.  Weights (from HBM) go through a ring of 4 LDS stages of 16 KB
@@ -112,48 +114,31 @@ struct Task {                                           // wave-uniform descript
 };
 
 template <class S, int ACT>
-__global__ __launch_bounds__(THREADS) void ffn_gemm_stream_kernel(GemmArgs a, int total_ids) {
+__global__ __launch_bounds__(THREADS) void ffn_gemm_stream_kernel(GemmArgs a) {
     typedef uint16_t elem;
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
     const int K = a.K, N = a.N;
     const int ncol = (N + BN - 1) / BN;
     const int nrow = (a.max_rows + BM - 1) / BM;
-    const int per_group = nrow * ncol;
-    const int stride_ids = gridDim.x;
 
-    // Task ids are dealt so that all tiles of an expert run on one XCD at the same time (workgroup ids go
-    // round-robin to the 8 XCDs, each with its own L2).  Returns false for ids that hold no work.
-    auto task_of = [&](int id, Task& t) -> bool {
-        int grp, r;
-        if (a.groups >= kXcds) {
-            const int x = id % kXcds, s = id / kXcds;
-            grp = (s / per_group) * kXcds + x;
-            r = s % per_group;
-        } else {
-            grp = id / per_group;
-            r = id % per_group;
-        }
-        if (grp >= a.groups) return false;
-        t.grp = uniform(grp);
-        t.row0 = uniform((r / ncol) * BM);
-        t.n0 = uniform((r % ncol) * BN);
-        t.rows = uniform(min(a.rows_dev[grp], a.rows_cap));
-        return t.row0 < t.rows;
+    // Work is the compact list of live (expert, row tile) units, each ncol column-tile tasks.  Unit q runs
+    // on XCD q % 8 (workgroup ids go round-robin to the 8 XCDs, each with its own L2), so the column tiles
+    // of a unit run on one XCD at about the same time and share its activation rows through that L2, and
+    // every XCD gets the same number of tasks to within one unit whatever the routing skew.  Inside an XCD
+    // the tasks (unit-major, column tile minor) are dealt round-robin to its workgroups.
+    const int xcd = blockIdx.x % kXcds, wg_local = blockIdx.x / kXcds, wg_stride = gridDim.x / kXcds;
+    const int n_units = uniform(a.units[0]);
+    const int xcd_tasks = n_units > xcd ? ((n_units - xcd + kXcds - 1) / kXcds) * ncol : 0;
+    if (wg_local >= xcd_tasks) return;
+    const int ntasks = (xcd_tasks - wg_local + wg_stride - 1) / wg_stride;
+    auto task_at = [&](int p, Task& t) __attribute__((always_inline)) {          // p < xcd_tasks
+        const int unit = uniform(a.units[1 + (p / ncol) * kXcds + xcd]);
+        t.grp = uniform(unit / nrow);
+        t.row0 = uniform((unit % nrow) * BM);
+        t.n0 = uniform((p % ncol) * BN);
+        t.rows = uniform(min(a.rows_dev[t.grp], a.rows_cap));
     };
-    // first id >= `id` (in steps of the grid size) that holds work, or total_ids
-    auto next_task = [&](int id, Task& t) -> int {
-        for (; id < total_ids; id += stride_ids)
-            if (task_of(id, t)) return id;
-        return total_ids;
-    };
-
-    int ntasks = 0;
-    {
-        Task t;
-        for (int id = blockIdx.x; id < total_ids; id += stride_ids) ntasks += task_of(id, t) ? 1 : 0;
-    }
-    if (ntasks == 0) return;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -190,15 +175,17 @@ __global__ __launch_bounds__(THREADS) void ffn_gemm_stream_kernel(GemmArgs a, in
     const int U = ntasks * nk;                          // K-tiles in this workgroup's whole stream
 
     Task cur, nxt;                                      // task being multiplied; the one after it
-    int nxt_id = next_task(blockIdx.x, cur);
+    int nxt_p = wg_local;                               // position of `nxt` in the XCD's task sequence
+    task_at(nxt_p, cur);
     const unsigned char *a_base, *b_base;               // copy cursors: bases advance along K
     const unsigned char *na_base, *nb_base;             // bases of the task after `cur`
     uint32_t a_off[4], b_off[2], na_off[4], nb_off[2];
     task_bases(cur, a_base, b_base);
     task_offsets(cur, a_off, b_off);
     nxt = cur;
-    nxt_id = next_task(nxt_id + stride_ids, nxt);
-    if (nxt_id < total_ids) {
+    nxt_p += wg_stride;
+    if (nxt_p < xcd_tasks) {
+        task_at(nxt_p, nxt);
         task_bases(nxt, na_base, nb_base);
         task_offsets(nxt, na_off, nb_off);
     } else {
@@ -354,12 +341,11 @@ __global__ __launch_bounds__(THREADS) void ffn_gemm_stream_kernel(GemmArgs a, in
         // K-tiles), so its successor's addresses can replace `nxt`'s.  The loads this needs are waited for
         // here, where every copy in flight is one the next K-tiles need anyway.
         cur = nxt;
-        if (nxt_id < total_ids) {
-            nxt_id = next_task(nxt_id + stride_ids, nxt);
-            if (nxt_id < total_ids) {
-                task_bases(nxt, na_base, nb_base);
-                task_offsets(nxt, na_off, nb_off);
-            }
+        nxt_p += wg_stride;
+        if (nxt_p < xcd_tasks) {
+            task_at(nxt_p, nxt);
+            task_bases(nxt, na_base, nb_base);
+            task_offsets(nxt, na_off, nb_off);
         }
     };
 
@@ -449,6 +435,43 @@ __global__ __launch_bounds__(THREADS) void ffn_gemm_stream_kernel(GemmArgs a, in
     pair_of_tiles(u + 2, std::false_type{}, std::true_type{});       // u == U - 2
 }
 
+// Compact list of the live (group, row tile) units of a grouped GEMM, in group order:
+// units[0] = count, units[1 + q] = g * nrow + row tile.  One workgroup; groups are scanned 1024 at a time.
+__global__ __launch_bounds__(1024) void ffn_units_kernel(const int32_t* __restrict__ rows_dev, int rows_cap, int groups,
+                                                         int nrow, int32_t* __restrict__ units) {
+    __shared__ int wave_total[16];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    int carry = 0;                                      // units of the groups before this pass
+    for (int g0 = 0; g0 < groups; g0 += 1024) {
+        const int g = g0 + tid;
+        int nt = 0;
+        if (g < groups) {
+            const int rows = min(rows_dev[g], rows_cap);
+            nt = rows > 0 ? (rows + BM - 1) / BM : 0;
+        }
+        int incl = nt;                                  // inclusive scan inside the wavefront
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const int up = __shfl_up(incl, d);
+            if (lane >= d) incl += up;
+        }
+        if (lane == 63) wave_total[wave] = incl;
+        __syncthreads();
+        int before = 0, total = 0;
+#pragma unroll
+        for (int w = 0; w < 16; ++w) {
+            const int t = wave_total[w];
+            before += w < wave ? t : 0;
+            total += t;
+        }
+        const int start = carry + before + incl - nt;
+        for (int rt = 0; rt < nt; ++rt) units[1 + start + rt] = g * nrow + rt;
+        carry += total;
+        __syncthreads();
+    }
+    if (tid == 0) units[0] = carry;
+}
+
 int device_cu_count() {
     static int cus = 0;
     if (cus == 0) {
@@ -472,14 +495,14 @@ hipError_t launch_stream_t(const GemmArgs& a, hipStream_t stream) {
         attr_set = true;
     }
     const long long ncol = (a.N + BN - 1) / BN, nrow = (a.max_rows + BM - 1) / BM;
-    const long long groups = a.groups >= kXcds ? (long long)(a.groups + kXcds - 1) / kXcds * kXcds : a.groups;
-    const long long total = groups * nrow * ncol;
-    if (total > 0x7fffffffLL) return hipErrorInvalidValue;
-    // one persistent workgroup per CU; a multiple of the XCD count keeps an expert's tiles on one XCD
+    const long long total = (long long)a.groups * nrow * ncol;           // upper bound of the live tasks
+    if ((long long)a.groups * nrow > 0x7fffffffLL / (ncol > kXcds ? ncol : kXcds)) return hipErrorInvalidValue;
+    // one persistent workgroup per CU, the same number on every XCD
     long long grid = device_cu_count() / kXcds * kXcds;
     if (grid < kXcds) grid = kXcds;
-    if (grid > total) grid = total;
-    hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(THREADS), LDS_BYTES, stream, a, (int)total);
+    const long long need = (total + kXcds - 1) / kXcds * kXcds;
+    if (grid > need) grid = need;
+    hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(THREADS), LDS_BYTES, stream, a);
     return hipGetLastError();
 }
 
@@ -495,8 +518,19 @@ hipError_t launch_stream_act(const GemmArgs& a, hipStream_t stream) {
 
 }  // namespace
 
+size_t ffn_units_ints(int groups, int max_rows) {
+    return 1 + (size_t)groups * (size_t)((max_rows + BM - 1) / BM);
+}
+
+hipError_t launch_ffn_units(const int32_t* rows_dev, int rows_cap, int groups, int max_rows, int32_t* units,
+                            hipStream_t stream) {
+    hipLaunchKernelGGL(ffn_units_kernel, dim3(1), dim3(1024), 0, stream, rows_dev, rows_cap, groups,
+                       (max_rows + BM - 1) / BM, units);
+    return hipGetLastError();
+}
+
 bool stream_gemm_eligible(const GemmArgs& a) {
-    return a.dtype != 0 && !a.b_is_nk && !a.c_f32 && a.rows_dev != nullptr && a.K % (2 * BK) == 0 &&
+    return a.dtype != 0 && !a.b_is_nk && !a.c_f32 && a.rows_dev != nullptr && a.units != nullptr && a.K % (2 * BK) == 0 &&
            a.K >= 6 * BK && a.N % 8 == 0 && a.N >= 256 && a.max_rows > 128 && a.lda % 8 == 0 && a.ldb % 8 == 0 &&
            a.ldc % 8 == 0 &&
            // copies address an operand as a 64-bit base plus 32-bit byte offsets

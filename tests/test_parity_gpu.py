@@ -80,6 +80,37 @@ def test_activations_bf16(oracle, act):
     _run(oracle, w)
 
 
+# ------------------------------------------------------------ shapes that take the weight-streaming FFN kernel
+
+@pytest.mark.parametrize("case", [
+    # several ragged row tiles per expert, fewer experts than XCDs, shortest K the kernel takes, ragged last column tile
+    dict(T=900, H=192, I=448, E=3, k=2, capacity_factor=1.0, dtype="bf16", with_bias=True, act="gelu_erf"),
+    # experts nobody picks between live ones; second column tile only 8 wide (I = 264); second GEMM on the generic kernel
+    dict(T=2000, H=320, I=264, E=11, k=2, capacity_factor=1.25, dtype="f16", with_bias=True, act="relu", empty=(0, 4, 5, 10)),
+    # more experts than XCDs, three row tiles each, both GEMMs streaming
+    dict(T=3000, H=256, I=256, E=16, k=2, capacity_factor=1.5, dtype="f16", with_bias=False, act="gelu_tanh"),
+    # one live expert out of nine: a single unit feeds one XCD only
+    dict(T=300, H=256, I=512, E=9, k=1, capacity_factor=9.0, dtype="bf16", with_bias=True, act="identity",
+         empty=(0, 1, 2, 3, 4, 5, 7, 8)),
+])
+def test_streaming_ffn_shapes(oracle, case):
+    case = dict(case)
+    empty = case.pop("empty", ())
+    w = scaled(WORKLOADS["paper_bf16_e128"], name="stream", seed=21, **case)
+    gb = None
+    if empty:
+        gb = torch.zeros(w.E)
+        gb[list(empty)] = -1.0e4
+    cpu, dev, b, host, rep = _run(oracle, w, gate_bias=gb)
+    for e in empty:
+        assert host["expert_demand"][e] == 0
+    assert b.C > 128                                          # the shape reaches the streaming kernel
+    # the staged path (packed rows) and the fused call (rows gathered through the routing table) agree bit for bit
+    dev2 = dict(dev)
+    b2, host2 = parity.gpu_forward(w, dev2, staged=True)
+    assert torch.equal(b.out, b2.out)
+
+
 # ------------------------------------------------------------ paper-scale configurations, sampled outputs
 
 def _sample_tokens(host, n, seed):
