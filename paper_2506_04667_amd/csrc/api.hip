@@ -85,6 +85,9 @@ char* ws_at(void* ws, size_t off) { return (char*)ws + off; }
 moe_status run_gate(const moe_config* c, const Plan& p, void* ws, const void* x, const void* Wg,
                     const float* gate_bias, float* logits, int32_t* topk_expert, float* topk_weight,
                     hipStream_t s) {
+    if (moe::gate_fused_eligible(c->T, c->H, c->E, c->k, c->dtype))
+        return hip_status(moe::launch_gate_fused(x, Wg, gate_bias, c->T, c->H, c->E, c->k, c->dtype, logits,
+                                                 topk_expert, topk_weight, s));
     void* wgt = ws_at(ws, p.off_wgt);
     hipError_t e = moe::launch_transpose_pad(Wg, wgt, c->H, c->E, p.E_pad, c->dtype, s);
     if (e != hipSuccess) return MOE_ERR_HIP;

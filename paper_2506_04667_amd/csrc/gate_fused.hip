@@ -1,0 +1,263 @@
+// Fused gate for 16-bit storage ("FusedGate" of Alg. 1): one kernel computes the gate
+// logits x Wg (+ bias) on the matrix cores, writes them, and selects each token's top-k
+// experts with their combine weights (Eqs. "combine 1/2": softmax over the k selected
+// logits) -- no transposed copy of Wg, no second pass over the logits in HBM.
+//
+// One workgroup (4 wavefronts) owns 64 tokens and all E <= 128 NB experts.  The token rows
+// stream from HBM exactly once; Wg (H x E, a few hundred KB) is re-read by every workgroup
+// from L2.  Both go straight to LDS (global_load_lds_dwordx4) through a ring of K-tiles of
+// 64, several tiles ahead, with explicit waits.  LDS layouts and swizzles are those of the
+// streaming FFN kernel: token rows 128 B per K-tile, chunk c of row r at c ^ ((r >> 1) & 7);
+// Wg tile [k][n], chunk c of row k at c ^ ((k & 3) << 1), read in MFMA operand order with
+// ds_read_b64_tr_b16.  The MFMAs take the Wg fragment first, so a lane's accumulators hold
+// runs of four consecutive experts of ONE token.
+//
+// Epilogue: logits (+ bias) go to an fp32 LDS tile (it reuses the ring), from there to HBM
+// with full-line stores, and the selection reads the same tile: 16 lanes per token, each
+// holding 8 NB logits in registers; k rounds of "largest remaining logit, smaller expert
+// index on equal values" compared as floats (so -0.0 and +0.0 tie), where "remaining" means
+// strictly after the previous pick in that order.  The rounds run twice: for the softmax
+// denominator, then to write experts and weights.
+#include "common.h"
+#include "kernels.h"
+#include "lds_copy.h"
+
+namespace moe {
+namespace {
+
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+
+constexpr int G_BM = 64, G_BK = 64, G_THREADS = 256;
+constexpr int G_A_STAGE = G_BM * 128;                    // 64 token rows x 64 k
+
+template <int NB>
+struct GateCfg {
+    static constexpr int BN = 128 * NB;
+    static constexpr int PITCH = BN * 2;                 // bytes per k-row of the Wg tile
+    static constexpr int B_STAGE = G_BK * PITCH;
+    static constexpr int STAGE = G_A_STAGE + B_STAGE;    // 24 KB or 40 KB
+    static constexpr int STAGES = NB == 1 ? 6 : 4;
+    static constexpr int LDS_BYTES = STAGES * STAGE;     // 144 KB or 160 KB
+    static constexpr int B_COPIES = B_STAGE / 1024 / 4;  // 1 KB copies per wavefront per K-tile
+    static constexpr int COPIES = 2 + B_COPIES;
+    static constexpr int TN = 2 * NB;                    // 32-expert MFMA tiles per wavefront
+    static constexpr int LP = BN + 4;                    // row pitch (floats) of the logits tile
+    static_assert(G_BM * LP * 4 <= LDS_BYTES, "logits tile must fit in the ring it reuses");
+    static_assert(LDS_BYTES <= 160 * 1024, "LDS budget of a gfx950 CU");
+};
+
+template <class S> struct GateMma;
+template <> struct GateMma<BF16> {
+    static __device__ __forceinline__ f32x16 run(s16x8 a, s16x8 b, f32x16 c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+    }
+};
+template <> struct GateMma<F16> {
+    static __device__ __forceinline__ f32x16 run(s16x8 a, s16x8 b, f32x16 c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+    }
+};
+
+template <class S, int NB>
+__global__ __launch_bounds__(G_THREADS) void gate_fused_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ Wg,
+                                                               const float* __restrict__ gate_bias, int T, int H, int E, int k,
+                                                               float* __restrict__ logits, int32_t* __restrict__ topk_expert,
+                                                               float* __restrict__ topk_weight) {
+    using C = GateCfg<NB>;
+    constexpr int BN = C::BN, PITCH = C::PITCH, STAGE = C::STAGE, D = C::STAGES, TN = C::TN, LP = C::LP;
+    extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = uniform(tid >> 6);
+    const int wm = wave >> 1, wn = wave & 1;            // 2 x 2 wavefronts: 32 tokens x BN / 2 experts each
+    const int l32 = lane & 31, g2 = lane >> 5;
+    const int row0 = blockIdx.x * G_BM;
+
+    // ---- this wavefront's 1 KB copies per K-tile: 2 of token rows (8 rows x 128 B), B_COPIES of Wg ----
+    const unsigned char* a_base = uniform((const unsigned char*)(x + (size_t)row0 * H));
+    const unsigned char* b_base = uniform((const unsigned char*)Wg);
+    uint32_t a_off[2], b_off[C::B_COPIES];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int r = (wave * 2 + j) * 8 + (lane >> 3), p = lane & 7;
+        const int c = p ^ ((r >> 1) & 7);
+        const int rr = min(row0 + r, T - 1) - row0;     // rows beyond T repeat the last token (never stored)
+        a_off[j] = (uint32_t)rr * (uint32_t)(H * 2) + c * 16;
+    }
+    constexpr int CPR = PITCH / 16;                     // 16-byte chunks per k-row
+#pragma unroll
+    for (int j = 0; j < C::B_COPIES; ++j) {
+        const int kk = (wave * C::B_COPIES + j) * (64 / CPR) + lane / CPR, p = lane % CPR;
+        const int c = p ^ ((kk & 3) << 1);
+        const int n = min(c * 8, E - 8);                // columns beyond E repeat the last 8 experts (masked later)
+        b_off[j] = (uint32_t)kk * (uint32_t)(E * 2) + n * 2;
+    }
+    const size_t b_step = (size_t)G_BK * E * 2;
+    const uint32_t lds_base = (uint32_t)(size_t)(__attribute__((address_space(3))) unsigned char*)smem;
+    const int nk = H / G_BK;
+
+    auto issue = [&](int t) __attribute__((always_inline)) {
+        const uint32_t d = lds_base + (t % D) * STAGE;
+#pragma unroll
+        for (int j = 0; j < 2; ++j) copy_to_lds(a_base, a_off[j], d + (wave * 2 + j) * 1024);
+#pragma unroll
+        for (int j = 0; j < C::B_COPIES; ++j)
+            copy_to_lds(b_base, b_off[j], d + G_A_STAGE + (wave * C::B_COPIES + j) * 1024);
+        a_base += 128;
+        b_base += b_step;
+    };
+
+    // ---- per-lane LDS read offsets ----
+    const int a_row = wm * 32 + l32;
+    const int a_sw = (a_row >> 1) & 7;
+    const int L = lane & 15, nb16 = (lane >> 4) & 1;
+    const int bk = g2 * 8 + (L >> 2);                   // k of the first transpose read; the second is k + 4
+    int a_rd[4], b_rd[TN];
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) a_rd[ks] = a_row * 128 + ((((ks << 1) | g2) ^ a_sw) << 4);
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn) {
+        const int chunk = (wn * TN + tn) * 4 + nb16 * 2 + ((L & 3) >> 1);
+        b_rd[tn] = G_A_STAGE + bk * PITCH + ((chunk ^ ((bk & 3) << 1)) << 4) + (L & 1) * 8;
+    }
+
+    f32x16 acc[TN];
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int q = 0; q < 16; ++q) acc[j][q] = 0.0f;
+
+    // ---- main loop: tile u is waited for, tile u + D - 1 requested into the stage tile u - 1 vacated ----
+    for (int t = 0; t < D - 1 && t < nk; ++t) issue(t);
+    for (int u = 0; u < nk; ++u) {
+        // a wavefront's copies complete in issue order: with tiles u .. u+D-2 requested, "tile u has landed"
+        // leaves the COPIES * (D - 2) newest in flight; near the end everything outstanding is waited for
+        if (u + D - 2 < nk) wait_copies_and_barrier<C::COPIES * (D - 2)>();
+        else wait_copies_and_barrier<0>();
+        if (u + D - 1 < nk) issue(u + D - 1);
+        const unsigned char* st = smem + (u % D) * STAGE;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            const u32x4 xf = *(const u32x4*)(st + a_rd[ks]);
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn) {
+                const unsigned char* pw = st + b_rd[tn] + ks * 16 * PITCH;
+                const u32x2 lo = __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)pw));
+                const u32x2 hi = __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(pw + 4 * PITCH)));
+                const u32x4 wf = {lo[0], lo[1], hi[0], hi[1]};
+                acc[tn] = GateMma<S>::run(__builtin_bit_cast(s16x8, wf), __builtin_bit_cast(s16x8, xf), acc[tn]);
+            }
+        }
+    }
+    wait_copies_and_barrier<0>();                       // every wavefront is done with the ring: reuse it
+
+    // ---- logits tile [64 tokens][LP] fp32 in LDS ----
+    // accumulator elements 4 qa .. 4 qa + 3 of tile tn: experts e .. e + 3 of token l32
+    float* lg = (float*)smem;
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+        for (int qa = 0; qa < 4; ++qa) {
+            const int e = (wn * TN + tn) * 32 + qa * 8 + g2 * 4;
+            f32x4 b = {0.0f, 0.0f, 0.0f, 0.0f};
+            if (gate_bias && e < E) b = *(const f32x4*)(gate_bias + e);
+            f32x4 v;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) v[i] = acc[tn][qa * 4 + i] + b[i];
+            *(f32x4*)(lg + (wm * 32 + l32) * LP + e) = v;
+        }
+    __syncthreads();
+
+    // ---- logits to HBM: each wavefront stores its 16 tokens, full rows ----
+    constexpr int LANES_PER_ROW = BN / 4;               // 32 or 64 lanes x 16 B
+    constexpr int ROWS_PER_PASS = 64 / LANES_PER_ROW;
+#pragma unroll
+    for (int i = 0; i < 16 / ROWS_PER_PASS; ++i) {
+        const int r = wave * 16 + i * ROWS_PER_PASS + lane / LANES_PER_ROW, e = (lane % LANES_PER_ROW) * 4;
+        if (row0 + r < T && e < E) *(f32x4*)(logits + (size_t)(row0 + r) * E + e) = *(const f32x4*)(lg + r * LP + e);
+    }
+
+    // ---- selection: 16 lanes per token, 4 tokens per wavefront at a time ----
+    constexpr int VL = BN / 16;                          // logits per lane
+    constexpr int kNone = 0x7fffffff;
+    const int s16 = lane & 15;
+    for (int round = 0; round < 4; ++round) {
+        const int r = wave * 16 + round * 4 + (lane >> 4);
+        const int token = row0 + r;
+        float vals[VL];
+#pragma unroll
+        for (int i = 0; i < VL / 4; ++i) {
+            const f32x4 v = *(const f32x4*)(lg + r * LP + i * 64 + s16 * 4);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) vals[i * 4 + q] = v[q];
+        }
+        float m = 0.0f, sum = 0.0f;
+        for (int pass = 0; pass < 2; ++pass) {
+            float last_v = 0.0f;
+            int last_i = -1;
+            for (int j = 0; j < k; ++j) {
+                float bv = 0.0f;
+                int bi = kNone;
+#pragma unroll
+                for (int i = 0; i < VL; ++i) {
+                    const int e = (i >> 2) * 64 + s16 * 4 + (i & 3);   // ascending in i: equal values keep the earlier index
+                    const float v = vals[i];
+                    const bool avail = (j == 0) || (v < last_v) || (v == last_v && e > last_i);
+                    const bool better = (bi == kNone) || (v > bv);
+                    if (e < E && avail && better) { bv = v; bi = e; }
+                }
+#pragma unroll
+                for (int off = 8; off >= 1; off >>= 1) {
+                    const float ov = __shfl_xor(bv, off);
+                    const int oi = __shfl_xor(bi, off);
+                    if (oi != kNone && (bi == kNone || ov > bv || (ov == bv && oi < bi))) { bv = ov; bi = oi; }
+                }
+                if (pass == 0) {
+                    if (j == 0) m = bv;
+                    sum += expf(bv - m);
+                } else if (s16 == 0 && token < T) {
+                    topk_expert[(size_t)token * k + j] = bi;
+                    topk_weight[(size_t)token * k + j] = expf(bv - m) / sum;
+                }
+                last_v = bv;
+                last_i = bi;
+            }
+        }
+    }
+}
+
+template <class S, int NB>
+hipError_t launch_gate_fused_t(const void* x, const void* Wg, const float* gate_bias, int T, int H, int E, int k,
+                               float* logits, int32_t* topk_expert, float* topk_weight, hipStream_t stream) {
+    auto kernel = gate_fused_kernel<S, NB>;
+    static bool attr_set = false;                       // LDS above 64 KB must be requested once per kernel
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, GateCfg<NB>::LDS_BYTES);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(kernel, dim3((unsigned)((T + G_BM - 1) / G_BM)), dim3(G_THREADS), GateCfg<NB>::LDS_BYTES, stream,
+                       (const uint16_t*)x, (const uint16_t*)Wg, gate_bias, T, H, E, k, logits, topk_expert, topk_weight);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+bool gate_fused_eligible(int T, int H, int E, int k, int dtype) {
+    return dtype != 0 && E % 8 == 0 && E >= 8 && E <= 256 && H % G_BK == 0 && H >= G_BK && k >= 1 && k <= E &&
+           (long long)G_BM * H * 2 < (1ll << 31) && (long long)G_BK * E * 2 < (1ll << 31);
+}
+
+hipError_t launch_gate_fused(const void* x, const void* Wg, const float* gate_bias, int T, int H, int E, int k,
+                             int dtype, float* logits, int32_t* topk_expert, float* topk_weight, hipStream_t stream) {
+    if (E <= 128)
+        return dtype == 1 ? launch_gate_fused_t<BF16, 1>(x, Wg, gate_bias, T, H, E, k, logits, topk_expert, topk_weight, stream)
+                          : launch_gate_fused_t<F16, 1>(x, Wg, gate_bias, T, H, E, k, logits, topk_expert, topk_weight, stream);
+    return dtype == 1 ? launch_gate_fused_t<BF16, 2>(x, Wg, gate_bias, T, H, E, k, logits, topk_expert, topk_weight, stream)
+                      : launch_gate_fused_t<F16, 2>(x, Wg, gate_bias, T, H, E, k, logits, topk_expert, topk_weight, stream);
+}
+
+}  // namespace moe

@@ -46,6 +46,7 @@
 // Requires K % 64 == 0, K >= 192 and N % 8 == 0; other shapes use the generic kernel.
 #include "common.h"
 #include "kernels.h"
+#include "lds_copy.h"
 
 #include <type_traits>
 
@@ -80,28 +81,6 @@ template <> struct Mma16<F16> {
         return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
     }
 };
-
-// Tell the compiler that a value is the same in every lane (it then lives in scalar registers).
-__device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
-__device__ __forceinline__ const unsigned char* uniform(const unsigned char* p) {
-    const uint64_t v = (uint64_t)p;
-    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
-    return (const unsigned char*)(((uint64_t)hi << 32) | lo);
-}
-
-// 64 lanes x 16 bytes from global addresses base + per-lane byte offset to LDS [lds_addr, lds_addr + 1024).
-// A wave-uniform base in scalar registers plus 32-bit lane offsets keeps the copy cursors out of the
-// vector registers, which the accumulators and operand fragments fill almost completely.
-__device__ __forceinline__ void copy_to_lds(const unsigned char* base, uint32_t lane_off, uint32_t lds_addr) {
-    base = uniform(base);
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(lane_off), "s"(base) : "memory");
-}
-
-// own copies older than the newest N have landed; own LDS reads are complete; then meet the other waves
-template <int N>
-__device__ __forceinline__ void wait_copies_and_barrier() {
-    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory");
-}
 
 struct Frags {                                          // MFMA operands of one 16-wide k-step
     u32x4 x[TM];                                        // activations, per row tile: 8 k-values of the lane's row

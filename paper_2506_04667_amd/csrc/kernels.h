@@ -48,6 +48,12 @@ hipError_t launch_grouped_gemm_stream(const GemmArgs& a, hipStream_t stream);
 hipError_t launch_transpose_pad(const void* Wg, void* WgT, int H, int E, int E_pad, int dtype,
                                 hipStream_t stream);
 
+// Fused gate for 16-bit storage: logits = x Wg (+ gate_bias) in fp32, top-k experts and combine weights,
+// one kernel; Wg is read as stored ([H][E]).  gate_fused_eligible tells whether the shape is covered.
+bool gate_fused_eligible(int T, int H, int E, int k, int dtype);
+hipError_t launch_gate_fused(const void* x, const void* Wg, const float* gate_bias, int T, int H, int E, int k,
+                             int dtype, float* logits, int32_t* topk_expert, float* topk_weight, hipStream_t stream);
+
 // Top-k selection and combine weights from fp32 logits.
 hipError_t launch_topk(const float* logits, int T, int E, int k, int32_t* topk_expert,
                        float* topk_weight, hipStream_t stream);

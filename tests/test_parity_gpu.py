@@ -111,6 +111,56 @@ def test_streaming_ffn_shapes(oracle, case):
     assert torch.equal(b.out, b2.out)
 
 
+# ------------------------------------------------------------ shapes that take the fused gate kernel (16-bit)
+
+@pytest.mark.parametrize("T,H,E,k,dtype,bias", [
+    (1000, 192, 24, 3, "bf16", True),                         # ragged last token tile, E far below the tile width
+    (64, 64, 256, 5, "f16", False),                           # one K-tile, widest expert tile
+    (777, 128, 136, 4, "bf16", True),                         # wide tile with a ragged expert tail
+    (130, 256, 8, 8, "f16", True),                            # k = E
+    (4096, 1024, 128, 2, "bf16", False),                      # full-width tile, deep K
+])
+def test_fused_gate_shapes(oracle, T, H, E, k, dtype, bias):
+    w = scaled(WORKLOADS["paper_bf16_e128"], name="gate", T=T, H=H, I=8, E=E, k=k, dtype=dtype, seed=31)
+    print("case", w, flush=True)
+    cpu = make_inputs(w)
+    gb = None
+    if bias:
+        gb = torch.from_numpy(np.random.default_rng(5).standard_normal(E).astype(np.float32))
+    cfg = moe.config_of(w)
+    b = moe.Buffers(cfg)
+    moe.moe_gate(cfg, b.workspace, cpu["x"].cuda(), cpu["Wg"].cuda(), None if gb is None else gb.cuda(),
+                 b.gate_logits, b.topk_expert, b.topk_weight)
+    torch.cuda.synchronize()
+    got = b.gate_logits.cpu().numpy()
+    ref = oracle.gate_logits(cpu["x"], cpu["Wg"], None if gb is None else gb.numpy(), T, H, E, dtype)
+    parity.assert_close(got, ref, parity.TOL[dtype], "gate_logits")
+    te, tw = oracle.topk(got, k)
+    np.testing.assert_array_equal(b.topk_expert.cpu().numpy(), te)
+    np.testing.assert_allclose(b.topk_weight.cpu().numpy(), tw, rtol=1e-5, atol=1e-7)
+
+
+@pytest.mark.parametrize("E,k", [(16, 4), (128, 2), (200, 7)])
+def test_fused_gate_exact_ties(oracle, E, k):
+    # small-integer operands: every logit is an exact small integer, so whole groups of experts tie and the
+    # logits themselves must match the oracle bit for bit
+    rng = np.random.default_rng(E)
+    T, H = 300, 128
+    x = torch.from_numpy(rng.integers(0, 2, size=(T, H)).astype(np.float32)).to(torch.bfloat16)
+    Wg = torch.from_numpy(rng.integers(-1, 2, size=(H, E)).astype(np.float32)).to(torch.bfloat16)
+    Wg[:, 1] = Wg[:, 0]                                       # two experts tie on every token
+    cfg = moe.make_config(T, H, 8, E, k, 1.0, "relu", "bf16")
+    b = moe.Buffers(cfg)
+    moe.moe_gate(cfg, b.workspace, x.cuda(), Wg.cuda(), None, b.gate_logits, b.topk_expert, b.topk_weight)
+    torch.cuda.synchronize()
+    got = b.gate_logits.cpu().numpy()
+    ref = oracle.gate_logits(x, Wg, None, T, H, E, "bf16")
+    np.testing.assert_array_equal(got, ref.astype(np.float32))
+    te, tw = oracle.topk(got, k)
+    np.testing.assert_array_equal(b.topk_expert.cpu().numpy(), te)
+    np.testing.assert_allclose(b.topk_weight.cpu().numpy(), tw, rtol=1e-5, atol=1e-7)
+
+
 # ------------------------------------------------------------ paper-scale configurations, sampled outputs
 
 def _sample_tokens(host, n, seed):
