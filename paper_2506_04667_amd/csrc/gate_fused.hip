@@ -16,8 +16,8 @@
 // with full-line stores, and the selection reads the same tile: 16 lanes per token, each
 // holding 8 NB logits in registers; k rounds of "largest remaining logit, smaller expert
 // index on equal values" compared as floats (so -0.0 and +0.0 tie), where "remaining" means
-// strictly after the previous pick in that order.  The rounds run twice: for the softmax
-// denominator, then to write experts and weights.
+// strictly after the previous pick in that order.  The 16 lanes agree on each pick through
+// DPP exchanges; the unnormalised weights wait in LDS until the softmax denominator is known.
 #include "common.h"
 #include "kernels.h"
 #include "lds_copy.h"
@@ -43,7 +43,7 @@ struct GateCfg {
     static constexpr int COPIES = 2 + B_COPIES;
     static constexpr int TN = 2 * NB;                    // 32-expert MFMA tiles per wavefront
     static constexpr int LP = BN + 4;                    // row pitch (floats) of the logits tile
-    static_assert(G_BM * LP * 4 <= LDS_BYTES, "logits tile must fit in the ring it reuses");
+    static_assert(G_BM * (LP + BN) * 4 <= LDS_BYTES, "logits tile and k <= BN weights per token must fit in the ring they reuse");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS budget of a gfx950 CU");
 };
 
@@ -58,6 +58,15 @@ template <> struct GateMma<F16> {
         return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
     }
 };
+
+// Candidate (value, expert) of the lane selected by a DPP pattern inside a row of 16 lanes; the better of the
+// two by (larger value, then smaller expert index) stays.  "No candidate" is (-inf, INT_MAX) and loses to any.
+template <int CTRL>
+__device__ __forceinline__ void merge_best(float& bv, int& bi) {
+    const float ov = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, bv), CTRL, 0xf, 0xf, true));
+    const int oi = __builtin_amdgcn_update_dpp(0, bi, CTRL, 0xf, 0xf, true);
+    if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+}
 
 template <class S, int NB>
 __global__ __launch_bounds__(G_THREADS) void gate_fused_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ Wg,
@@ -179,53 +188,65 @@ __global__ __launch_bounds__(G_THREADS) void gate_fused_kernel(const uint16_t* _
         if (row0 + r < T && e < E) *(f32x4*)(logits + (size_t)(row0 + r) * E + e) = *(const f32x4*)(lg + r * LP + e);
     }
 
-    // ---- selection: 16 lanes per token, 4 tokens per wavefront at a time ----
+    // ---- selection: 16 lanes per token ----
+    // Round j picks the largest remaining (logit, then smaller index) of the token: every lane proposes the
+    // best of its own VL logits, then the 16 lanes agree through four DPP exchanges (no LDS traffic).  The
+    // unnormalised weights exp(v_j - v_0) wait in LDS until the sum over the k picks is known.
     constexpr int VL = BN / 16;                          // logits per lane
     constexpr int kNone = 0x7fffffff;
+    constexpr int R = 4;                                 // a wavefront's 16 tokens: 4 at a time x 4 independent chains
     const int s16 = lane & 15;
-    for (int round = 0; round < 4; ++round) {
-        const int r = wave * 16 + round * 4 + (lane >> 4);
-        const int token = row0 + r;
-        float vals[VL];
+    float* stash = lg + G_BM * LP;                       // [64 tokens][k]
+    float vals[R][VL];
+    int row[R];
+#pragma unroll
+    for (int c = 0; c < R; ++c) {
+        row[c] = wave * 16 + c * 4 + (lane >> 4);
 #pragma unroll
         for (int i = 0; i < VL / 4; ++i) {
-            const f32x4 v = *(const f32x4*)(lg + r * LP + i * 64 + s16 * 4);
+            const f32x4 v = *(const f32x4*)(lg + row[c] * LP + i * 64 + s16 * 4);
 #pragma unroll
-            for (int q = 0; q < 4; ++q) vals[i * 4 + q] = v[q];
-        }
-        float m = 0.0f, sum = 0.0f;
-        for (int pass = 0; pass < 2; ++pass) {
-            float last_v = 0.0f;
-            int last_i = -1;
-            for (int j = 0; j < k; ++j) {
-                float bv = 0.0f;
-                int bi = kNone;
-#pragma unroll
-                for (int i = 0; i < VL; ++i) {
-                    const int e = (i >> 2) * 64 + s16 * 4 + (i & 3);   // ascending in i: equal values keep the earlier index
-                    const float v = vals[i];
-                    const bool avail = (j == 0) || (v < last_v) || (v == last_v && e > last_i);
-                    const bool better = (bi == kNone) || (v > bv);
-                    if (e < E && avail && better) { bv = v; bi = e; }
-                }
-#pragma unroll
-                for (int off = 8; off >= 1; off >>= 1) {
-                    const float ov = __shfl_xor(bv, off);
-                    const int oi = __shfl_xor(bi, off);
-                    if (oi != kNone && (bi == kNone || ov > bv || (ov == bv && oi < bi))) { bv = ov; bi = oi; }
-                }
-                if (pass == 0) {
-                    if (j == 0) m = bv;
-                    sum += expf(bv - m);
-                } else if (s16 == 0 && token < T) {
-                    topk_expert[(size_t)token * k + j] = bi;
-                    topk_weight[(size_t)token * k + j] = expf(bv - m) / sum;
-                }
-                last_v = bv;
-                last_i = bi;
-            }
+            for (int q = 0; q < 4; ++q) vals[c][i * 4 + q] = v[q];
         }
     }
+    float m[R], sum[R], last_v[R];
+    int last_i[R];
+#pragma unroll
+    for (int c = 0; c < R; ++c) { m[c] = 0.0f; sum[c] = 0.0f; last_v[c] = 0.0f; last_i[c] = -1; }
+    for (int j = 0; j < k; ++j) {
+#pragma unroll
+        for (int c = 0; c < R; ++c) {
+            float bv = -INFINITY;
+            int bi = kNone;
+#pragma unroll
+            for (int i = 0; i < VL; ++i) {
+                const int e = (i >> 2) * 64 + s16 * 4 + (i & 3);   // ascending in i: equal values keep the earlier index
+                const float v = vals[c][i];
+                const bool avail = (j == 0) || (v < last_v[c]) || (v == last_v[c] && e > last_i[c]);
+                const bool better = (bi == kNone) || (v > bv);
+                if (e < E && avail && better) { bv = v; bi = e; }
+            }
+            merge_best<0xB1>(bv, bi);                   // lane ^ 1
+            merge_best<0x4E>(bv, bi);                   // lane ^ 2
+            merge_best<0x141>(bv, bi);                  // mirror inside 8 lanes: the other quad
+            merge_best<0x140>(bv, bi);                  // mirror inside 16 lanes: the other half
+            if (j == 0) m[c] = bv;
+            const float p = expf(bv - m[c]);
+            sum[c] += p;
+            if (s16 == 0 && row0 + row[c] < T) {
+                topk_expert[(size_t)(row0 + row[c]) * k + j] = bi;
+                stash[row[c] * k + j] = p;
+            }
+            last_v[c] = bv;
+            last_i[c] = bi;
+        }
+    }
+    // a wavefront's LDS operations complete in order: lane 0 of a group wrote what the group's lanes read here
+#pragma unroll
+    for (int c = 0; c < R; ++c)
+        if (row0 + row[c] < T)
+            for (int j = s16; j < k; j += 16)
+                topk_weight[(size_t)(row0 + row[c]) * k + j] = stash[row[c] * k + j] / sum[c];
 }
 
 template <class S, int NB>
