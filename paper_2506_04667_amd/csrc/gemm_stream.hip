@@ -300,7 +300,7 @@ __global__ __launch_bounds__(THREADS) void ffn_gemm_stream_kernel(GemmArgs a) {
                             const uint32_t word = b < 2 ? bias_bits[tn][qa][0] : bias_bits[tn][qa][1];
                             bias = bits16_to_float<S>((uint16_t)((b & 1) ? (word >> 16) : (word & 0xffffu)));
                         }
-                        v[b] = apply_act_t<ACT>(acc[tm][tn][qa * 4 + b] + bias);
+                        v[b] = apply_act16_t<ACT>(acc[tm][tn][qa * 4 + b] + bias);
                         acc[tm][tn][qa * 4 + b] = 0.0f;
                     }
                     const int chunk = (tn * 4 + qa) ^ ((l32 >> 1) & 7);
