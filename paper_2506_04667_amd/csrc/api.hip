@@ -5,6 +5,7 @@
 #include "../../include/moe.h"
 
 #include <cmath>
+#include <cstdlib>
 #include <initializer_list>
 
 #include "kernels.h"
@@ -138,24 +139,32 @@ moe_status run_ffn(const moe_config* c, const Plan& p, void* ws, const void* xe,
         g.units = units;
     }
     // task t1: h = phi1(xe W1 + b1)
-    g.A = xe; g.a_group_stride = (long long)p.C_pad * H; g.lda = c->H;
-    g.a_row_index = slot_token; g.a_index_stride = p.C;
-    g.a_rows_total = slot_token ? c->T : p.C_pad;
-    g.B = W1; g.b_group_stride = H * I; g.ldb = c->I;
-    g.C = h; g.c_group_stride = (long long)p.C_pad * I; g.ldc = c->I;
-    g.bias = b1; g.bias_group_stride = I;
-    g.N = c->I; g.K = c->H; g.act = c->act;
-    e = moe::launch_grouped_gemm(g, s);
-    if (e != hipSuccess) return MOE_ERR_HIP;
+    moe::GemmArgs g1 = g;
+    g1.A = xe; g1.a_group_stride = (long long)p.C_pad * H; g1.lda = c->H;
+    g1.a_row_index = slot_token; g1.a_index_stride = p.C;
+    g1.a_rows_total = slot_token ? c->T : p.C_pad;
+    g1.B = W1; g1.b_group_stride = H * I; g1.ldb = c->I;
+    g1.C = h; g1.c_group_stride = (long long)p.C_pad * I; g1.ldc = c->I;
+    g1.bias = b1; g1.bias_group_stride = I;
+    g1.N = c->I; g1.K = c->H; g1.act = c->act;
     // task t2: y = h W2 + b2
-    g.A = h; g.a_group_stride = (long long)p.C_pad * I; g.lda = c->I;
-    g.a_row_index = nullptr; g.a_index_stride = 0;
-    g.a_rows_total = p.C_pad;
-    g.B = W2; g.b_group_stride = I * H; g.ldb = c->H;
-    g.C = y; g.c_group_stride = (long long)p.C_pad * H; g.ldc = c->H;
-    g.bias = b2; g.bias_group_stride = H;
-    g.N = c->H; g.K = c->I; g.act = MOE_ACT_IDENTITY;
-    return hip_status(moe::launch_grouped_gemm(g, s));
+    moe::GemmArgs g2 = g;
+    g2.A = h; g2.a_group_stride = (long long)p.C_pad * I; g2.lda = c->I;
+    g2.a_row_index = nullptr; g2.a_index_stride = 0;
+    g2.a_rows_total = p.C_pad;
+    g2.B = W2; g2.b_group_stride = I * H; g2.ldb = c->H;
+    g2.C = y; g2.c_group_stride = (long long)p.C_pad * H; g2.ldc = c->H;
+    g2.bias = b2; g2.bias_group_stride = H;
+    g2.N = c->H; g2.K = c->I; g2.act = MOE_ACT_IDENTITY;
+    // Optional: one persistent launch for both tasks, t2 tiles following their t1 tiles by dependency (the
+    // tile-level pipelining of the paper's processors, Alg. 2).  Measured slower than two launches on one
+    // MI355X at the paper's shapes, so it is opt-in (environment variable MOE_FFN_FUSED=1).
+    const char* fused = std::getenv("MOE_FFN_FUSED");
+    if (fused && fused[0] == '1' && moe::ffn_fused_eligible(g1, g2))
+        return hip_status(moe::launch_ffn_stream_fused(g1, g2, s));
+    e = moe::launch_grouped_gemm(g1, s);
+    if (e != hipSuccess) return MOE_ERR_HIP;
+    return hip_status(moe::launch_grouped_gemm(g2, s));
 }
 
 moe_status run_combine(const moe_config* c, const Plan& p, const void* y, const int32_t* topk_expert,

@@ -322,7 +322,18 @@ hipError_t launch_cfg(const GemmArgs& a, hipStream_t stream) {
 
 template <class S>
 hipError_t launch_t(const GemmArgs& a, hipStream_t stream) {
-    const bool large = (a.N > 128) && (a.max_rows > 128);
+    // Tile choice from the row bound alone (live row counts are only known on the device): rounds of tasks over
+    // the chip times the time of a round.  A CU runs one 256 x 256 task, or two 128 x 128 tasks that each
+    // take a quarter of the work at about 0.94 of the large tile's efficiency.
+    bool large = (a.N > 128) && (a.max_rows > 128);
+    if (large) {
+        const long long cus = device_cu_count();
+        const long long t_l = (long long)a.groups * ((a.max_rows + 255) / 256) * ((a.N + 255) / 256);
+        const long long t_s = (long long)a.groups * ((a.max_rows + 127) / 128) * ((a.N + 127) / 128);
+        const double time_l = (double)((t_l + cus - 1) / cus);
+        const double time_s = (double)((t_s + 2 * cus - 1) / (2 * cus)) * (2.0 * 0.25 / 0.94);
+        large = time_l <= time_s;
+    }
     if (a.b_is_nk) {
         return large ? launch_cfg<S, true, 2, 4, 4, 2>(a, stream) : launch_cfg<S, true, 2, 2, 2, 2>(a, stream);
     }

@@ -89,35 +89,115 @@ struct Frags {                                          // MFMA operands of one 
 };
 
 struct Task {                                           // wave-uniform description of one output tile
+    int ph;                                             // 0: first GEMM of the kernel's work, 1: the dependent second one
+    int unit;                                           // index in the list of live units
     int grp, row0, n0, rows;
+    int nk;                                             // K-tiles
 };
 
-template <class S, int ACT>
-__global__ __launch_bounds__(THREADS) void ffn_gemm_stream_kernel(GemmArgs a) {
+// One GEMM of the expert FFN: C[g] = act(A[g] B[g] + bias[g]) over the live rows of every group (16-bit storage).
+struct StreamPhase {
+    const void* A; long long a_group_stride; int lda;
+    const int32_t* a_row_index; long long a_index_stride;   // optional gather of the A rows (see GemmArgs)
+    const void* B; long long b_group_stride; int ldb;
+    void* C; long long c_group_stride; int ldc;
+    const void* bias; long long bias_group_stride;
+    int N, K;
+};
+// NPH == 1: the kernel computes ph[0] with activation ACT0.  NPH == 2: also ph[1] (identity), whose A is
+// ph[0]'s C: a ph[1] task of a unit starts once all ph[0] column tiles of that unit have been stored.
+struct StreamArgs {
+    StreamPhase ph[2];
+    const int32_t* rows_dev; int rows_cap; int max_rows;
+    const int32_t* units;                               // [0] = live units, [1 + q] = group * nrow + row tile
+    int32_t* done;                                      // [q] wavefronts that have stored a ph[0] tile of unit q; zero at launch
+    int32_t* fault;                                     // set to 1 if a dependency wait gave up
+    int lag;                                            // units between a unit's ph[0] and ph[1] tasks in an XCD's sequence
+};
+
+constexpr int kSpinLimit = 1 << 21;                     // polls (about 100 ns apart) before a dependency wait gives up
+
+#define PHF(t, f) ((NPH == 2 && (t).ph) ? a.ph[1].f : a.ph[0].f)
+
+template <class S, int ACT0, int NPH>
+__global__ __launch_bounds__(THREADS) void ffn_gemm_stream_kernel(StreamArgs a) {
     typedef uint16_t elem;
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
-    const int K = a.K, N = a.N;
-    const int ncol = (N + BN - 1) / BN;
+    const int ncol0 = (a.ph[0].N + BN - 1) / BN, ncol1 = NPH == 2 ? (a.ph[1].N + BN - 1) / BN : 0;
+    const int nk0 = a.ph[0].K / BK, nk1 = NPH == 2 ? a.ph[1].K / BK : 0;       // K-tiles per task (even, >= 6)
     const int nrow = (a.max_rows + BM - 1) / BM;
 
-    // Work is the compact list of live (expert, row tile) units, each ncol column-tile tasks.  Unit q runs
-    // on XCD q % 8 (workgroup ids go round-robin to the 8 XCDs, each with its own L2), so the column tiles
-    // of a unit run on one XCD at about the same time and share its activation rows through that L2, and
-    // every XCD gets the same number of tasks to within one unit whatever the routing skew.  Inside an XCD
-    // the tasks (unit-major, column tile minor) are dealt round-robin to its workgroups.
+    // Work is the compact list of live (expert, row tile) units, each one task per column tile (and per
+    // phase).  Unit q runs on XCD q % 8 (workgroup ids go round-robin to the 8 XCDs, each with its own L2),
+    // so the column tiles of a unit run on one XCD at about the same time and share its activation rows
+    // through that L2, and every XCD gets the same number of tasks to within one unit whatever the routing
+    // skew.  Inside an XCD the task sequence is dealt round-robin to its workgroups.  With two phases the
+    // sequence of an XCD with ux units is, for step s = 0 .. ux + lag - 1: the ph[0] tasks of unit s (if
+    // s < ux), then the ph[1] tasks of unit s - lag (if s >= lag).  Every task a ph[1] task waits for comes
+    // earlier in the sequence, and each workgroup walks its share in order, so with all workgroups resident
+    // (one per CU, never more workgroups than CUs) the waits cannot deadlock; `lag` is chosen so that the
+    // producers finished rounds earlier and the waits normally do not spin at all.
     const int xcd = blockIdx.x % kXcds, wg_local = blockIdx.x / kXcds, wg_stride = gridDim.x / kXcds;
     const int n_units = uniform(a.units[0]);
-    const int xcd_tasks = n_units > xcd ? ((n_units - xcd + kXcds - 1) / kXcds) * ncol : 0;
+    const int ux = n_units > xcd ? (n_units - xcd + kXcds - 1) / kXcds : 0;
+    const int xcd_tasks = ux * (ncol0 + ncol1);
     if (wg_local >= xcd_tasks) return;
-    const int ntasks = (xcd_tasks - wg_local + wg_stride - 1) / wg_stride;
+    const int lag = a.lag;
+    const int head_units = min(lag, ux), mid_units = max(ux - lag, 0);
+    const int head = head_units * ncol0, mid = mid_units * (ncol0 + ncol1);
+    // position p of the XCD's sequence -> phase, unit index inside the XCD, column tile (arithmetic only)
+    auto decode = [&](int p, int& ph, int& ui, int& ct) __attribute__((always_inline)) {
+        if (NPH == 1 || p < head) {
+            ph = 0; ui = p / ncol0; ct = p % ncol0;
+        } else if (p < head + mid) {
+            const int q = p - head, s = q / (ncol0 + ncol1), r = q % (ncol0 + ncol1);
+            if (r < ncol0) { ph = 0; ui = lag + s; ct = r; }
+            else { ph = 1; ui = s; ct = r - ncol0; }
+        } else {
+            const int q = p - head - mid;
+            ph = 1; ui = mid_units + q / ncol1; ct = q % ncol1;
+        }
+    };
     auto task_at = [&](int p, Task& t) __attribute__((always_inline)) {          // p < xcd_tasks
-        const int unit = uniform(a.units[1 + (p / ncol) * kXcds + xcd]);
+        int ph, ui, ct;
+        decode(p, ph, ui, ct);
+        t.ph = uniform(ph);
+        t.unit = uniform(ui * kXcds + xcd);
+        const int unit = uniform(a.units[1 + t.unit]);
         t.grp = uniform(unit / nrow);
         t.row0 = uniform((unit % nrow) * BM);
-        t.n0 = uniform((p % ncol) * BN);
+        t.n0 = uniform(ct * BN);
         t.rows = uniform(min(a.rows_dev[t.grp], a.rows_cap));
+        t.nk = t.ph ? nk1 : nk0;
     };
+    // A ph[1] task reads what the ph[0] tasks of its unit stored: wait until all of them (8 wavefronts per
+    // column tile) have signalled.  The poll is bounded: if it ever gave up, the fault word says so.
+    // Producer and consumer run on the same XCD and meet in its L2: the producer's stores are acknowledged
+    // by that L2 (vmcnt) before it counts, the counter lives beyond the CU caches (device-scope atomics), and
+    // the consumer has never read those lines before, so no cache write-back or invalidate is needed -- an
+    // agent-scope release/acquire pair would write back and invalidate the whole L2 on every task.
+    auto wait_for_unit = [&](const Task& t) __attribute__((always_inline)) {
+        if (NPH == 2 && t.ph == 1) {
+            const int need = ncol0 * (THREADS / 64);
+            int spins = 0;
+            while (__hip_atomic_load(a.done + t.unit, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < need) {
+                if (++spins > kSpinLimit) {
+                    if (threadIdx.x == 0) __hip_atomic_store(a.fault, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    break;
+                }
+                __builtin_amdgcn_s_sleep(4);
+            }
+            asm volatile("" ::: "memory");
+        }
+    };
+    int U = 0;                                          // K-tiles in this workgroup's whole stream
+    for (int p = wg_local; p < xcd_tasks; p += wg_stride) {
+        int ph, ui, ct;
+        decode(p, ph, ui, ct);
+        U += ph ? nk1 : nk0;
+    }
+    U = uniform(U);
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -128,34 +208,33 @@ __global__ __launch_bounds__(THREADS) void ffn_gemm_stream_kernel(GemmArgs a) {
     // ---- addresses of this wavefront's 1 KB copies, per task: uniform base + per-lane byte offset ----
     // activations: 4 copies of 8 rows x 128 B per K-tile pair; weights: 2 copies of 2 k-rows x 512 B per K-tile
     auto task_bases = [&](const Task& t, const unsigned char*& base_a, const unsigned char*& base_b) __attribute__((always_inline)) {
-        base_a = uniform((const unsigned char*)((const elem*)a.A + (a.a_row_index ? (size_t)0 : (size_t)t.grp * a.a_group_stride)));
-        base_b = uniform((const unsigned char*)((const elem*)a.B + (size_t)t.grp * a.b_group_stride));
+        base_a = uniform((const unsigned char*)((const elem*)PHF(t, A) + (PHF(t, a_row_index) ? (size_t)0 : (size_t)t.grp * PHF(t, a_group_stride))));
+        base_b = uniform((const unsigned char*)((const elem*)PHF(t, B) + (size_t)t.grp * PHF(t, b_group_stride)));
     };
     auto task_offsets = [&](const Task& t, uint32_t (&oa)[4], uint32_t (&ob)[2]) __attribute__((always_inline)) {
+        const int32_t* row_index = PHF(t, a_row_index);
+        const int lda = PHF(t, lda), ldb = PHF(t, ldb), N = PHF(t, N);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int r = (wave * 4 + j) * 8 + (lane >> 3), p = lane & 7;
             const int c = p ^ ((r >> 1) & 7);
             int grow = min(t.row0 + r, t.rows - 1);
-            if (a.a_row_index) grow = a.a_row_index[(size_t)t.grp * a.a_index_stride + grow];
-            oa[j] = (uint32_t)grow * (uint32_t)(a.lda * 2) + c * 16;
+            if (row_index) grow = row_index[(size_t)t.grp * PHF(t, a_index_stride) + grow];
+            oa[j] = (uint32_t)grow * (uint32_t)(lda * 2) + c * 16;
         }
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
             const int k = (wave * 2 + j) * 2 + (lane >> 5), p = lane & 31;
             const int c = p ^ ((k & 3) << 1);
             const int n = min(t.n0 + c * 8, N - 8);
-            ob[j] = (uint32_t)k * (uint32_t)(a.ldb * 2) + n * 2;
+            ob[j] = (uint32_t)k * (uint32_t)(ldb * 2) + n * 2;
         }
     };
-
-    const int nk = K / BK;                              // K-tiles per task (even, >= 6)
-    const int npair = nk / 2;
-    const int U = ntasks * nk;                          // K-tiles in this workgroup's whole stream
 
     Task cur, nxt;                                      // task being multiplied; the one after it
     int nxt_p = wg_local;                               // position of `nxt` in the XCD's task sequence
     task_at(nxt_p, cur);
+    wait_for_unit(cur);
     const unsigned char *a_base, *b_base;               // copy cursors: bases advance along K
     const unsigned char *na_base, *nb_base;             // bases of the task after `cur`
     uint32_t a_off[4], b_off[2], na_off[4], nb_off[2];
@@ -165,6 +244,7 @@ __global__ __launch_bounds__(THREADS) void ffn_gemm_stream_kernel(GemmArgs a) {
     nxt_p += wg_stride;
     if (nxt_p < xcd_tasks) {
         task_at(nxt_p, nxt);
+        wait_for_unit(nxt);
         task_bases(nxt, na_base, nb_base);
         task_offsets(nxt, na_off, nb_off);
     } else {
@@ -174,9 +254,8 @@ __global__ __launch_bounds__(THREADS) void ffn_gemm_stream_kernel(GemmArgs a) {
 #pragma unroll
         for (int j = 0; j < 2; ++j) nb_off[j] = b_off[j];
     }
-    int a_left = npair, b_left = nk;                    // requests left before a cursor moves to the next task
-
-    const size_t b_step = (size_t)BK * a.ldb * 2;
+    int a_left = cur.nk / 2, b_left = cur.nk;           // requests left before a cursor moves to the next task
+    size_t b_step = (size_t)BK * PHF(cur, ldb) * 2;     // bytes between K-tiles of the weights the cursor is in
     const uint32_t lds_base = (uint32_t)(size_t)(__attribute__((address_space(3))) unsigned char*)smem;
     const uint32_t lds_a_wave = lds_base + wave * 4096;
     const uint32_t lds_b_wave = lds_base + B_REGION + wave * 2048;
@@ -187,7 +266,7 @@ __global__ __launch_bounds__(THREADS) void ffn_gemm_stream_kernel(GemmArgs a) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) copy_to_lds(a_base, a_off[j], d + j * 1024);
         if (--a_left == 0) {
-            a_left = npair;
+            a_left = nxt.nk / 2;
             a_base = na_base;
 #pragma unroll
             for (int j = 0; j < 4; ++j) a_off[j] = na_off[j];
@@ -201,7 +280,8 @@ __global__ __launch_bounds__(THREADS) void ffn_gemm_stream_kernel(GemmArgs a) {
         copy_to_lds(b_base, b_off[0], d);
         copy_to_lds(b_base, b_off[1], d + 1024);
         if (--b_left == 0) {
-            b_left = nk;
+            b_left = nxt.nk;
+            b_step = (size_t)BK * PHF(nxt, ldb) * 2;
             b_base = nb_base;
             b_off[0] = nb_off[0]; b_off[1] = nb_off[1];
         } else {
@@ -272,17 +352,20 @@ __global__ __launch_bounds__(THREADS) void ffn_gemm_stream_kernel(GemmArgs a) {
 
     // ---- epilogue of task `cur`: bias, activation, conversion, transposed store; then advance to the next task ----
     unsigned char* epi = smem + EPI_REGION + wave * EPI_BYTES_PER_WAVE;   // [32 rows][64 columns], 128 B pitch
-    auto finish_task = [&]() __attribute__((always_inline)) {
+    auto store_tile = [&](auto act_tag, auto ph_tag) __attribute__((always_inline)) {
+        constexpr int ACT = decltype(act_tag)::value, PH = decltype(ph_tag)::value;
+        const StreamPhase& P = a.ph[PH];
+        const int N = P.N;
         const int col_w = cur.n0 + wn * (TN * 32);      // first column of this wavefront
-        const size_t c_base = (size_t)cur.grp * a.c_group_stride;
+        const size_t c_base = (size_t)cur.grp * P.c_group_stride;
         u32x2 bias_bits[TN][4];
-        if (a.bias) {
+        if (P.bias) {
 #pragma unroll
             for (int tn = 0; tn < TN; ++tn)
 #pragma unroll
                 for (int qa = 0; qa < 4; ++qa) {
                     const int c = min(col_w + tn * 32 + qa * 8 + g2 * 4, N - 4);
-                    bias_bits[tn][qa] = *(const u32x2*)((const elem*)a.bias + (size_t)cur.grp * a.bias_group_stride + c);
+                    bias_bits[tn][qa] = *(const u32x2*)((const elem*)P.bias + (size_t)cur.grp * P.bias_group_stride + c);
                 }
         }
 #pragma unroll
@@ -296,7 +379,7 @@ __global__ __launch_bounds__(THREADS) void ffn_gemm_stream_kernel(GemmArgs a) {
 #pragma unroll
                     for (int b = 0; b < 4; ++b) {
                         float bias = 0.0f;
-                        if (a.bias) {
+                        if (P.bias) {
                             const uint32_t word = b < 2 ? bias_bits[tn][qa][0] : bias_bits[tn][qa][1];
                             bias = bits16_to_float<S>((uint16_t)((b & 1) ? (word >> 16) : (word & 0xffffu)));
                         }
@@ -313,7 +396,19 @@ __global__ __launch_bounds__(THREADS) void ffn_gemm_stream_kernel(GemmArgs a) {
                 const int r_local = i * 8 + (lane >> 3), chunk = lane & 7;
                 const u32x4 v = *(const u32x4*)(epi + r_local * 128 + ((chunk ^ ((r_local >> 1) & 7)) << 4));
                 const int row = cur.row0 + (wm * TM + tm) * 32 + r_local, col = col_w + chunk * 8;
-                if (row < cur.rows && col < N) *(u32x4*)((elem*)a.C + c_base + (size_t)row * a.ldc + col) = v;
+                if (row < cur.rows && col < N) *(u32x4*)((elem*)P.C + c_base + (size_t)row * P.ldc + col) = v;
+            }
+        }
+    };
+    auto finish_task = [&]() __attribute__((always_inline)) {
+        if (NPH == 2 && cur.ph == 1) {
+            store_tile(std::integral_constant<int, 3>{}, std::integral_constant<int, NPH == 2 ? 1 : 0>{});
+        } else {
+            store_tile(std::integral_constant<int, ACT0>{}, std::integral_constant<int, 0>{});
+            if (NPH == 2) {
+                // this wavefront's part of the tile has reached the XCD's L2 before it is counted
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                if (lane == 0) __hip_atomic_fetch_add(a.done + cur.unit, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
         }
         // Both copy cursors have moved on to `nxt` by now (they run at most 4 K-tiles ahead and K >= 6
@@ -323,6 +418,7 @@ __global__ __launch_bounds__(THREADS) void ffn_gemm_stream_kernel(GemmArgs a) {
         nxt_p += wg_stride;
         if (nxt_p < xcd_tasks) {
             task_at(nxt_p, nxt);
+            wait_for_unit(nxt);
             task_bases(nxt, na_base, nb_base);
             task_offsets(nxt, na_off, nb_off);
         }
@@ -402,7 +498,7 @@ __global__ __launch_bounds__(THREADS) void ffn_gemm_stream_kernel(GemmArgs a) {
             __builtin_amdgcn_sched_barrier(0);
         }
         k_done += 2;
-        if (k_done == nk) {
+        if (k_done == cur.nk) {
             k_done = 0;
             finish_task();
             __builtin_amdgcn_sched_barrier(0);
@@ -414,12 +510,17 @@ __global__ __launch_bounds__(THREADS) void ffn_gemm_stream_kernel(GemmArgs a) {
     pair_of_tiles(u + 2, std::false_type{}, std::true_type{});       // u == U - 2
 }
 
-// Compact list of the live (group, row tile) units of a grouped GEMM, in group order:
-// units[0] = count, units[1 + q] = g * nrow + row tile.  One workgroup; groups are scanned 1024 at a time.
+// Compact list of the live (group, row tile) units of a grouped GEMM, in group order, in the scratch block
+// `w` of ffn_units_ints() ints: w[0] = fault word (cleared), w[1] = count, w[2 + q] = g * nrow + row tile,
+// then one completion counter per possible unit (cleared).  One workgroup; groups are scanned 1024 at a time.
 __global__ __launch_bounds__(1024) void ffn_units_kernel(const int32_t* __restrict__ rows_dev, int rows_cap, int groups,
-                                                         int nrow, int32_t* __restrict__ units) {
+                                                         int nrow, int32_t* __restrict__ w) {
     __shared__ int wave_total[16];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int cap = groups * nrow;
+    int32_t* units = w + 2;
+    int32_t* done = w + 2 + cap;
+    for (int i = tid; i < cap; i += 1024) done[i] = 0;
     int carry = 0;                                      // units of the groups before this pass
     for (int g0 = 0; g0 < groups; g0 += 1024) {
         const int g = g0 + tid;
@@ -438,18 +539,76 @@ __global__ __launch_bounds__(1024) void ffn_units_kernel(const int32_t* __restri
         __syncthreads();
         int before = 0, total = 0;
 #pragma unroll
-        for (int w = 0; w < 16; ++w) {
-            const int t = wave_total[w];
-            before += w < wave ? t : 0;
+        for (int wv = 0; wv < 16; ++wv) {
+            const int t = wave_total[wv];
+            before += wv < wave ? t : 0;
             total += t;
         }
         const int start = carry + before + incl - nt;
-        for (int rt = 0; rt < nt; ++rt) units[1 + start + rt] = g * nrow + rt;
+        for (int rt = 0; rt < nt; ++rt) units[start + rt] = g * nrow + rt;
         carry += total;
         __syncthreads();
     }
-    if (tid == 0) units[0] = carry;
+    if (tid == 0) { w[0] = 0; w[1] = carry; }
 }
+
+StreamPhase to_phase(const GemmArgs& g) {
+    StreamPhase p{};
+    p.A = g.A; p.a_group_stride = g.a_group_stride; p.lda = g.lda;
+    p.a_row_index = g.a_row_index; p.a_index_stride = g.a_index_stride;
+    p.B = g.B; p.b_group_stride = g.b_group_stride; p.ldb = g.ldb;
+    p.C = g.C; p.c_group_stride = g.c_group_stride; p.ldc = g.ldc;
+    p.bias = g.bias; p.bias_group_stride = g.bias_group_stride;
+    p.N = g.N; p.K = g.K;
+    return p;
+}
+
+// g2 == nullptr: one GEMM.  Otherwise g2's A is g1's C and both share rows/groups/units.
+template <class S, int ACT0, int NPH>
+hipError_t launch_stream_t(const GemmArgs& g1, const GemmArgs* g2, hipStream_t stream) {
+    auto kernel = ffn_gemm_stream_kernel<S, ACT0, NPH>;
+    static bool attr_set = false;                       // LDS above 64 KB must be requested once per kernel
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const long long nrow = (g1.max_rows + BM - 1) / BM;
+    const long long ncol = (g1.N + BN - 1) / BN + (g2 ? (g2->N + BN - 1) / BN : 0);
+    const long long total = (long long)g1.groups * nrow * ncol;          // upper bound of the live tasks
+    if ((long long)g1.groups * nrow > 0x7fffffffLL / (ncol > kXcds ? ncol : kXcds)) return hipErrorInvalidValue;
+    // one persistent workgroup per CU, the same number on every XCD, never more workgroups than CUs
+    long long grid = device_cu_count() / kXcds * kXcds;
+    if (grid < kXcds) return hipErrorInvalidValue;
+    const long long need = (total + kXcds - 1) / kXcds * kXcds;
+    if (grid > need) grid = need;
+    StreamArgs a{};
+    a.ph[0] = to_phase(g1);
+    if (g2) a.ph[1] = to_phase(*g2);
+    a.rows_dev = g1.rows_dev; a.rows_cap = g1.rows_cap; a.max_rows = g1.max_rows;
+    int32_t* w = const_cast<int32_t*>(g1.units);
+    a.fault = w; a.units = w + 1; a.done = w + 2 + (long long)g1.groups * nrow;
+    // a unit's second-GEMM tasks come `lag` units after its first-GEMM tasks: about four rounds of the XCD's
+    // workgroups, so that the tiles they wait for were stored rounds ago
+    const long long wg_per_xcd = grid / kXcds;
+    a.lag = (int)((4 * wg_per_xcd + ncol - 1) / ncol);
+    if (a.lag < 1) a.lag = 1;
+    hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(THREADS), LDS_BYTES, stream, a);
+    return hipGetLastError();
+}
+
+template <class S, int NPH>
+hipError_t launch_stream_act(const GemmArgs& g1, const GemmArgs* g2, hipStream_t stream) {
+    switch (g1.act) {
+        case 0: return launch_stream_t<S, 0, NPH>(g1, g2, stream);
+        case 1: return launch_stream_t<S, 1, NPH>(g1, g2, stream);
+        case 2: return launch_stream_t<S, 2, NPH>(g1, g2, stream);
+        default: return launch_stream_t<S, 3, NPH>(g1, g2, stream);
+    }
+}
+
+}  // namespace
 
 int device_cu_count() {
     static int cus = 0;
@@ -463,42 +622,8 @@ int device_cu_count() {
     return cus;
 }
 
-template <class S, int ACT>
-hipError_t launch_stream_t(const GemmArgs& a, hipStream_t stream) {
-    auto kernel = ffn_gemm_stream_kernel<S, ACT>;
-    static bool attr_set = false;                       // LDS above 64 KB must be requested once per kernel
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
-    const long long ncol = (a.N + BN - 1) / BN, nrow = (a.max_rows + BM - 1) / BM;
-    const long long total = (long long)a.groups * nrow * ncol;           // upper bound of the live tasks
-    if ((long long)a.groups * nrow > 0x7fffffffLL / (ncol > kXcds ? ncol : kXcds)) return hipErrorInvalidValue;
-    // one persistent workgroup per CU, the same number on every XCD
-    long long grid = device_cu_count() / kXcds * kXcds;
-    if (grid < kXcds) grid = kXcds;
-    const long long need = (total + kXcds - 1) / kXcds * kXcds;
-    if (grid > need) grid = need;
-    hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(THREADS), LDS_BYTES, stream, a);
-    return hipGetLastError();
-}
-
-template <class S>
-hipError_t launch_stream_act(const GemmArgs& a, hipStream_t stream) {
-    switch (a.act) {
-        case 0: return launch_stream_t<S, 0>(a, stream);
-        case 1: return launch_stream_t<S, 1>(a, stream);
-        case 2: return launch_stream_t<S, 2>(a, stream);
-        default: return launch_stream_t<S, 3>(a, stream);
-    }
-}
-
-}  // namespace
-
 size_t ffn_units_ints(int groups, int max_rows) {
-    return 1 + (size_t)groups * (size_t)((max_rows + BM - 1) / BM);
+    return 2 + 2 * (size_t)groups * (size_t)((max_rows + BM - 1) / BM);
 }
 
 hipError_t launch_ffn_units(const int32_t* rows_dev, int rows_cap, int groups, int max_rows, int32_t* units,
@@ -517,7 +642,17 @@ bool stream_gemm_eligible(const GemmArgs& a) {
 }
 
 hipError_t launch_grouped_gemm_stream(const GemmArgs& a, hipStream_t stream) {
-    return a.dtype == 1 ? launch_stream_act<BF16>(a, stream) : launch_stream_act<F16>(a, stream);
+    return a.dtype == 1 ? launch_stream_act<BF16, 1>(a, nullptr, stream) : launch_stream_act<F16, 1>(a, nullptr, stream);
+}
+
+bool ffn_fused_eligible(const GemmArgs& g1, const GemmArgs& g2) {
+    return stream_gemm_eligible(g1) && stream_gemm_eligible(g2) && g2.act == 3 && g2.a_row_index == nullptr &&
+           g1.units == g2.units && g1.rows_dev == g2.rows_dev && g1.rows_cap == g2.rows_cap &&
+           g1.groups == g2.groups && g1.max_rows == g2.max_rows && g1.dtype == g2.dtype;
+}
+
+hipError_t launch_ffn_stream_fused(const GemmArgs& g1, const GemmArgs& g2, hipStream_t stream) {
+    return g1.dtype == 1 ? launch_stream_act<BF16, 2>(g1, &g2, stream) : launch_stream_act<F16, 2>(g1, &g2, stream);
 }
 
 }  // namespace moe

@@ -22,9 +22,9 @@ struct GemmArgs {
     void* C; long long c_group_stride; int ldc;
     const void* bias; long long bias_group_stride;          // nullptr = none
     const int32_t* rows_dev; int rows_fixed; int rows_cap;
-    // optional compact list of live (group, row tile) units written by launch_ffn_units for the same
-    // rows_dev / rows_cap / groups / max_rows; the weight-streaming kernel needs it
-    const int32_t* units;
+    // optional scratch block written by launch_ffn_units for the same rows_dev / rows_cap / groups / max_rows
+    // (list of live units and completion counters); the weight-streaming kernels need it
+    int32_t* units;
     int groups; int max_rows;                               // grid extent in rows
     int N; int K;
     int act;                                                // moe_act, applied after the bias
@@ -34,15 +34,23 @@ struct GemmArgs {
 };
 hipError_t launch_grouped_gemm(const GemmArgs& a, hipStream_t stream);
 
+// compute units of the current device (256 on MI355X)
+int device_cu_count();
+
 // Weight-streaming variant for the 16-bit expert FFN tasks (direct-to-LDS, deep prefetch);
 // launch_grouped_gemm routes eligible shapes to it.
 bool stream_gemm_eligible(const GemmArgs& a);
-// units[0] = number of live units, units[1 + q] = g * ceil(max_rows / 256) + row tile, in order of g;
-// `units` holds ffn_units_ints(groups, max_rows) ints.
+hipError_t launch_grouped_gemm_stream(const GemmArgs& a, hipStream_t stream);
+// Scratch block of the streaming kernels, written by launch_ffn_units for the same rows_dev / rows_cap / groups /
+// max_rows: a fault word, the number of live (group, row tile of 256) units, their list in order of group, and
+// one completion counter per unit.  ffn_units_ints() ints; GemmArgs::units points at the block.
 size_t ffn_units_ints(int groups, int max_rows);
 hipError_t launch_ffn_units(const int32_t* rows_dev, int rows_cap, int groups, int max_rows, int32_t* units,
                             hipStream_t stream);
-hipError_t launch_grouped_gemm_stream(const GemmArgs& a, hipStream_t stream);
+// Both FFN GEMMs in one persistent launch: a unit's second-GEMM tasks start when all its first-GEMM tiles are
+// stored (g2.A is g1.C).  Eligible when both GEMMs are and they share rows, groups and units.
+bool ffn_fused_eligible(const GemmArgs& g1, const GemmArgs& g2);
+hipError_t launch_ffn_stream_fused(const GemmArgs& g1, const GemmArgs& g2, hipStream_t stream);
 
 // WgT[n][h] = Wg[h][n] for n < E, zero rows for E <= n < E_pad.
 hipError_t launch_transpose_pad(const void* Wg, void* WgT, int H, int E, int E_pad, int dtype,

@@ -111,6 +111,29 @@ def test_streaming_ffn_shapes(oracle, case):
     assert torch.equal(b.out, b2.out)
 
 
+def test_single_launch_ffn_opt_in(oracle, monkeypatch):
+    # both FFN GEMMs in one persistent launch with tile-level dependencies (opt-in): same arithmetic in the same
+    # order as the two-launch path, so the outputs must agree bit for bit, and with the oracle within the bar
+    cases = [scaled(WORKLOADS["paper_bf16_e128"], name="fused_ffn", seed=23, T=3000, H=256, I=256, E=16, k=2,
+                    capacity_factor=1.5, dtype="f16", with_bias=True, act="gelu_erf"),
+             scaled(WORKLOADS["paper_bf16_e128"], name="fused_ffn_few_units", seed=24, T=700, H=512, I=256, E=3, k=1,
+                    capacity_factor=1.2, dtype="bf16", act="relu"),
+             WORKLOADS["paper_bf16_e128"]]
+    for w in cases:
+        print("case", w, flush=True)
+        cpu = make_inputs(w)
+        dev = parity.to_device(cpu)
+        monkeypatch.delenv("MOE_FFN_FUSED", raising=False)
+        b0, host0 = parity.gpu_forward(w, dev)
+        monkeypatch.setenv("MOE_FFN_FUSED", "1")
+        b1, host1 = parity.gpu_forward(w, dev)
+        b2, host2 = parity.gpu_forward(w, dev)                # again: the completion counters are cleared per call
+        monkeypatch.delenv("MOE_FFN_FUSED", raising=False)
+        assert torch.equal(b0.out, b1.out) and torch.equal(b0.out, b2.out)
+        tokens = None if w.T <= 4096 else _sample_tokens(host1, 32, 7)
+        print("  ", parity.check_layer(oracle, w, cpu, b1, host1, tokens=tokens), flush=True)
+
+
 # ------------------------------------------------------------ shapes that take the fused gate kernel (16-bit)
 
 @pytest.mark.parametrize("T,H,E,k,dtype,bias", [
