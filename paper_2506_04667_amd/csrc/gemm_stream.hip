@@ -159,16 +159,29 @@ __global__ __launch_bounds__(THREADS) void ffn_gemm_stream_kernel(StreamArgs a) 
             ph = 1; ui = mid_units + q / ncol1; ct = q % ncol1;
         }
     };
-    auto task_at = [&](int p, Task& t) __attribute__((always_inline)) {          // p < xcd_tasks
+    // The unit and the live row count of this workgroup's tasks are fetched 64 tasks at a time, one task per
+    // lane, so that moving on to the next task costs two lane reads, not two dependent trips to memory.
+    int info_unit = 0, info_rows = 0;                   // of this workgroup's task number j0 + lane
+    auto load_task_info = [&](int j0) __attribute__((always_inline)) {
+        const int p = wg_local + (j0 + (int)(threadIdx.x & 63)) * wg_stride;
+        if (p < xcd_tasks) {
+            int ph, ui, ct;
+            decode(p, ph, ui, ct);
+            info_unit = a.units[1 + ui * kXcds + xcd];
+            info_rows = min(a.rows_dev[info_unit / nrow], a.rows_cap);
+        }
+    };
+    // task number j of this workgroup, at position p = wg_local + j * wg_stride < xcd_tasks
+    auto task_at = [&](int j, int p, Task& t) __attribute__((always_inline)) {
         int ph, ui, ct;
         decode(p, ph, ui, ct);
         t.ph = uniform(ph);
         t.unit = uniform(ui * kXcds + xcd);
-        const int unit = uniform(a.units[1 + t.unit]);
+        const int unit = __builtin_amdgcn_readlane(info_unit, j & 63);
         t.grp = uniform(unit / nrow);
         t.row0 = uniform((unit % nrow) * BM);
         t.n0 = uniform(ct * BN);
-        t.rows = uniform(min(a.rows_dev[t.grp], a.rows_cap));
+        t.rows = __builtin_amdgcn_readlane(info_rows, j & 63);
         t.nk = t.ph ? nk1 : nk0;
     };
     // A ph[1] task reads what the ph[0] tasks of its unit stored: wait until all of them (8 wavefronts per
@@ -232,8 +245,9 @@ __global__ __launch_bounds__(THREADS) void ffn_gemm_stream_kernel(StreamArgs a) 
     };
 
     Task cur, nxt;                                      // task being multiplied; the one after it
-    int nxt_p = wg_local;                               // position of `nxt` in the XCD's task sequence
-    task_at(nxt_p, cur);
+    int nxt_j = 0, nxt_p = wg_local;                    // number and position of `nxt` in the XCD's task sequence
+    load_task_info(0);
+    task_at(nxt_j, nxt_p, cur);
     wait_for_unit(cur);
     const unsigned char *a_base, *b_base;               // copy cursors: bases advance along K
     const unsigned char *na_base, *nb_base;             // bases of the task after `cur`
@@ -241,9 +255,10 @@ __global__ __launch_bounds__(THREADS) void ffn_gemm_stream_kernel(StreamArgs a) 
     task_bases(cur, a_base, b_base);
     task_offsets(cur, a_off, b_off);
     nxt = cur;
+    ++nxt_j;
     nxt_p += wg_stride;
     if (nxt_p < xcd_tasks) {
-        task_at(nxt_p, nxt);
+        task_at(nxt_j, nxt_p, nxt);
         wait_for_unit(nxt);
         task_bases(nxt, na_base, nb_base);
         task_offsets(nxt, na_off, nb_off);
@@ -401,6 +416,19 @@ __global__ __launch_bounds__(THREADS) void ffn_gemm_stream_kernel(StreamArgs a) 
         }
     };
     auto finish_task = [&]() __attribute__((always_inline)) {
+        // Both copy cursors have moved on to `nxt` by now (they run at most 4 K-tiles ahead and K >= 6
+        // K-tiles), so the addresses of its successor can replace `nxt`'s.  The loads they need (the gather
+        // table) are requested first and used after the tile is stored.
+        Task after = nxt;
+        ++nxt_j;
+        nxt_p += wg_stride;
+        if (nxt_p < xcd_tasks) {
+            if ((nxt_j & 63) == 0) load_task_info(nxt_j);
+            task_at(nxt_j, nxt_p, after);
+            wait_for_unit(after);
+            task_bases(after, na_base, nb_base);
+            task_offsets(after, na_off, nb_off);
+        }
         if (NPH == 2 && cur.ph == 1) {
             store_tile(std::integral_constant<int, 3>{}, std::integral_constant<int, NPH == 2 ? 1 : 0>{});
         } else {
@@ -411,17 +439,8 @@ __global__ __launch_bounds__(THREADS) void ffn_gemm_stream_kernel(StreamArgs a) 
                 if (lane == 0) __hip_atomic_fetch_add(a.done + cur.unit, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
         }
-        // Both copy cursors have moved on to `nxt` by now (they run at most 4 K-tiles ahead and K >= 6
-        // K-tiles), so its successor's addresses can replace `nxt`'s.  The loads this needs are waited for
-        // here, where every copy in flight is one the next K-tiles need anyway.
         cur = nxt;
-        nxt_p += wg_stride;
-        if (nxt_p < xcd_tasks) {
-            task_at(nxt_p, nxt);
-            wait_for_unit(nxt);
-            task_bases(nxt, na_base, nb_base);
-            task_offsets(nxt, na_off, nb_off);
-        }
+        nxt = after;
     };
 
     // ---- main loop over the stream of K-tiles u = 0 .. U-1 ----
