@@ -152,6 +152,16 @@ def main():
     roofline = roof_hbm if binding_is_hbm else roof_mfma
     other = roof_mfma if binding_is_hbm else roof_hbm
 
+    # achieved HBM rate of the bandwidth-bound stages: algorithmic bytes / stage time
+    C = b.C
+    stage_bytes = {
+        "gate": T * H * el + H * E * el + T * E * 4 + T * k * 8,
+        # the staged dispatch call packs xe as well (moe_forward gathers inside the first GEMM instead)
+        "dispatch": T * k * 4 + (T * k + 2 * E * C + E) * 4 + T * H * el + R * H * el,
+        "combine": R * H * el + T * k * 12 + T * H * el,
+    }
+    stage_gbs = {n: round(v / (stage_ms[n] * 1e-3) / 1e9, 1) for n, v in stage_bytes.items()}
+
     cpu_baseline = None
     if args.cpu_baseline_tokens > 0:
         from oracle import load_oracle
@@ -181,6 +191,7 @@ def main():
         "expert_demand": {"min": int(demand.min()), "median": int(demand.median()), "max": int(demand.max()),
                           "empty": E - live},
         "stage_ms": {n: round(v, 4) for n, v in stage_ms.items()},
+        "stage_hbm_gbs": stage_gbs,
         "ffn_tflops": round(4.0 * R * H * I / (ffn_ms * 1e-3) / 1e12, 1),
         "ffn_mfma_frac": round(4.0 * R * H * I / (ffn_ms * 1e-3) / 1e12 / PEAK["mfma_tflops"][w.dtype], 4),
         "roofline": roofline,
