@@ -67,7 +67,7 @@ moe_status make_plan(const moe_config* c, Plan* p) {
     p->off_logits = take(T * E * 4);
     p->off_slot_token = take(E * (size_t)p->C * 4);
     p->off_slot_weight = take(E * (size_t)p->C * 4);
-    p->off_counts = take((size_t)moe::route_chunks((long long)T * c->k) * E * 4);
+    p->off_counts = take((size_t)moe::route_chunks(c->T) * E * 4);
     p->off_units = take(moe::ffn_units_ints(c->E, p->C) * 4);
     p->off_h = take(rows * I * el);
     p->off_y = take(rows * H * el);
@@ -85,10 +85,16 @@ char* ws_at(void* ws, size_t off) { return (char*)ws + off; }
 
 moe_status run_gate(const moe_config* c, const Plan& p, void* ws, const void* x, const void* Wg,
                     const float* gate_bias, float* logits, int32_t* topk_expert, float* topk_weight,
-                    hipStream_t s) {
-    if (moe::gate_fused_eligible(c->T, c->H, c->E, c->k, c->dtype))
+                    bool* route_counts_written, hipStream_t s) {
+    // route_counts_written != nullptr: the caller goes on to the slot assignment; the fused gate then writes
+    // the per-chunk expert counts into the workspace and says so
+    if (route_counts_written) *route_counts_written = false;
+    if (moe::gate_fused_eligible(c->T, c->H, c->E, c->k, c->dtype)) {
+        int32_t* counts = route_counts_written ? (int32_t*)ws_at(ws, p.off_counts) : nullptr;
+        if (route_counts_written) *route_counts_written = true;
         return hip_status(moe::launch_gate_fused(x, Wg, gate_bias, c->T, c->H, c->E, c->k, c->dtype, logits,
-                                                 topk_expert, topk_weight, s));
+                                                 topk_expert, topk_weight, counts, s));
+    }
     void* wgt = ws_at(ws, p.off_wgt);
     hipError_t e = moe::launch_transpose_pad(Wg, wgt, c->H, c->E, p.E_pad, c->dtype, s);
     if (e != hipSuccess) return MOE_ERR_HIP;
@@ -110,10 +116,11 @@ moe_status run_gate(const moe_config* c, const Plan& p, void* ws, const void* x,
 moe_status run_dispatch(const moe_config* c, const Plan& p, void* ws, const void* x,
                         const int32_t* topk_expert, const float* topk_weight, int32_t* slot,
                         int32_t* expert_demand, int32_t* slot_token, float* slot_weight, void* xe,
-                        hipStream_t s) {
+                        bool counts_ready, bool build_units, hipStream_t s) {
     hipError_t e = moe::launch_route(topk_expert, topk_weight, c->T, c->E, c->k, p.C,
-                                     (int32_t*)ws_at(ws, p.off_counts), slot, expert_demand, slot_token,
-                                     slot_weight, s);
+                                     (int32_t*)ws_at(ws, p.off_counts), counts_ready, slot, expert_demand,
+                                     slot_token, slot_weight,
+                                     build_units ? (int32_t*)ws_at(ws, p.off_units) : nullptr, s);
     if (e != hipSuccess) return MOE_ERR_HIP;
     if (!xe) return MOE_OK;
     return hip_status(moe::launch_pack(x, topk_expert, slot, c->T, c->H, c->k, c->E, p.C, p.C_pad, c->dtype, xe, s));
@@ -123,7 +130,7 @@ moe_status run_dispatch(const moe_config* c, const Plan& p, void* ws, const void
 // first GEMM gathers through slot_token[E, C] (no packed copy).
 moe_status run_ffn(const moe_config* c, const Plan& p, void* ws, const void* xe, const int32_t* slot_token,
                    const int32_t* expert_demand, const void* W1, const void* b1, const void* W2,
-                   const void* b2, void* y, hipStream_t s) {
+                   const void* b2, void* y, bool units_ready, hipStream_t s) {
     void* h = ws_at(ws, p.off_h);
     const long long H = c->H, I = c->I;
     moe::GemmArgs g{};
@@ -133,9 +140,11 @@ moe_status run_ffn(const moe_config* c, const Plan& p, void* ws, const void* xe,
     // both tasks walk the same live (expert, row tile) units
     int32_t* units = (int32_t*)ws_at(ws, p.off_units);
     hipError_t e = hipSuccess;
-    if (c->dtype != MOE_F32) {                          // only the 16-bit streaming kernel uses the list
-        e = moe::launch_ffn_units(expert_demand, p.C, c->E, p.C, units, s);
-        if (e != hipSuccess) return MOE_ERR_HIP;
+    if (c->dtype != MOE_F32) {                          // only the 16-bit streaming kernels use the list
+        if (!units_ready) {
+            e = moe::launch_ffn_units(expert_demand, p.C, c->E, p.C, units, s);
+            if (e != hipSuccess) return MOE_ERR_HIP;
+        }
         g.units = units;
     }
     // task t1: h = phi1(xe W1 + b1)
@@ -238,13 +247,16 @@ moe_status moe_forward(const moe_config* cfg, void* workspace, size_t workspace_
     int32_t* slot_token = (int32_t*)ws_at(workspace, p.off_slot_token);
     float* slot_weight = (float*)ws_at(workspace, p.off_slot_weight);
     void* y = ws_at(workspace, p.off_y);
-    st = run_gate(cfg, p, workspace, x, Wg, gate_bias, logits, topk_expert, topk_weight, s);
+    bool counts_ready = false;
+    st = run_gate(cfg, p, workspace, x, Wg, gate_bias, logits, topk_expert, topk_weight, &counts_ready, s);
     if (st != MOE_OK) return st;
     // Dispatch builds the routing table only; the first FFN GEMM gathers its rows from x through
     // slot_token, so the packed copy xe is never materialised on this path.
-    st = run_dispatch(cfg, p, workspace, x, topk_expert, topk_weight, slot, expert_demand, slot_token, slot_weight, nullptr, s);
+    const bool units_here = cfg->dtype != MOE_F32;      // the scatter launch also lists the live FFN units
+    st = run_dispatch(cfg, p, workspace, x, topk_expert, topk_weight, slot, expert_demand, slot_token, slot_weight, nullptr,
+                      counts_ready, units_here, s);
     if (st != MOE_OK) return st;
-    st = run_ffn(cfg, p, workspace, x, slot_token, expert_demand, W1, b1, W2, b2, y, s);
+    st = run_ffn(cfg, p, workspace, x, slot_token, expert_demand, W1, b1, W2, b2, y, units_here, s);
     if (st != MOE_OK) return st;
     return run_combine(cfg, p, y, topk_expert, topk_weight, slot, out, s);
 }
@@ -258,7 +270,7 @@ moe_status moe_gate(const moe_config* cfg, void* workspace, size_t workspace_byt
     if (bad_required({workspace, x, Wg, gate_logits, topk_expert, topk_weight}) || bad_optional({gate_bias}))
         return MOE_ERR_INVALID_ARG;
     if (workspace_bytes < p.total) return MOE_ERR_WORKSPACE_TOO_SMALL;
-    return run_gate(cfg, p, workspace, x, Wg, gate_bias, gate_logits, topk_expert, topk_weight, (hipStream_t)stream);
+    return run_gate(cfg, p, workspace, x, Wg, gate_bias, gate_logits, topk_expert, topk_weight, nullptr, (hipStream_t)stream);
 }
 
 moe_status moe_route(const moe_config* cfg, const float* gate_logits, int32_t* topk_expert,
@@ -280,7 +292,8 @@ moe_status moe_dispatch(const moe_config* cfg, void* workspace, size_t workspace
         bad_optional({x, xe}) || (xe && !x))
         return MOE_ERR_INVALID_ARG;
     if (workspace_bytes < p.total) return MOE_ERR_WORKSPACE_TOO_SMALL;
-    return run_dispatch(cfg, p, workspace, x, topk_expert, topk_weight, slot, expert_demand, slot_token, slot_weight, xe, (hipStream_t)stream);
+    return run_dispatch(cfg, p, workspace, x, topk_expert, topk_weight, slot, expert_demand, slot_token, slot_weight, xe,
+                        false, false, (hipStream_t)stream);
 }
 
 moe_status moe_expert_ffn(const moe_config* cfg, void* workspace, size_t workspace_bytes, const void* xe,
@@ -291,7 +304,7 @@ moe_status moe_expert_ffn(const moe_config* cfg, void* workspace, size_t workspa
     if (st != MOE_OK) return st;
     if (bad_required({workspace, xe, expert_demand, W1, W2, y}) || bad_optional({b1, b2})) return MOE_ERR_INVALID_ARG;
     if (workspace_bytes < p.total) return MOE_ERR_WORKSPACE_TOO_SMALL;
-    return run_ffn(cfg, p, workspace, xe, nullptr, expert_demand, W1, b1, W2, b2, y, (hipStream_t)stream);
+    return run_ffn(cfg, p, workspace, xe, nullptr, expert_demand, W1, b1, W2, b2, y, false, (hipStream_t)stream);
 }
 
 moe_status moe_combine(const moe_config* cfg, const void* y, const int32_t* topk_expert,

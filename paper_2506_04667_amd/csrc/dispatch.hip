@@ -5,48 +5,55 @@
 // cells, capacity aligned to the row tile as in Sec. 3.2.1).
 //
 // Slot assignment is integer work and fully deterministic: the (token, choice)
-// pairs, in token-major order, are cut into chunks of kChunk pairs;
-//   1. count:   one workgroup per chunk histograms its pairs by expert (LDS integer atomics);
+// pairs, in token-major order, are cut into chunks of 64 tokens (64 k pairs);
+//   1. count:   one workgroup per chunk histograms its pairs by expert (LDS integer atomics).
+//               The fused gate kernel, whose workgroups own the same 64 tokens, writes these
+//               counts itself (the routing table as a by-product of the gate, Alg. 1), and the
+//               launch is skipped;
 //   2. scan:    one wavefront per expert turns the counts into exclusive chunk bases
-//               and the expert's total demand;
+//               and the expert's total demand; the launch also empties the routing table;
 //   3. scatter: one wavefront per chunk walks its pairs 64 at a time; a lane's
 //               slot is base + (pairs of the same expert in earlier steps) +
-//               (lower lanes naming the same expert in this step).
+//               (lower lanes naming the same expert in this step).  One more workgroup of
+//               this launch builds the FFN kernels' list of live (expert, row tile) units.
 #include "common.h"
 #include "kernels.h"
+#include "ffn_units.h"
 
 namespace moe {
 namespace {
 
-constexpr int kChunk = 256;
+constexpr int kChunkTokens = 64;                        // tokens per chunk = tokens per fused-gate workgroup
 
-// One workgroup per chunk of kChunk pairs: per-expert counts in an LDS histogram (integer atomics, so
-// the result does not depend on their order); also clears the routing table.
-__global__ __launch_bounds__(kChunk) void route_count_kernel(const int32_t* __restrict__ topk_expert, long long P,
-                                                             int E, int32_t* __restrict__ counts,
-                                                             int32_t* __restrict__ slot_token,
-                                                             float* __restrict__ slot_weight, long long EC) {
+// One workgroup per chunk: per-expert counts in an LDS histogram (integer atomics, so the result does not
+// depend on their order).
+__global__ __launch_bounds__(256) void route_count_kernel(const int32_t* __restrict__ topk_expert, long long P,
+                                                          int chunk_pairs, int E, int32_t* __restrict__ counts) {
     extern __shared__ int32_t hist[];                // [E]
-    const long long gid = blockIdx.x * (long long)blockDim.x + threadIdx.x;
-    const long long stride = (long long)gridDim.x * blockDim.x;
-    for (long long q = gid; q < EC; q += stride) {   // empty routing table
-        slot_token[q] = -1;
-        slot_weight[q] = 0.0f;
-    }
-    for (int e = threadIdx.x; e < E; e += kChunk) hist[e] = 0;
+    for (int e = threadIdx.x; e < E; e += 256) hist[e] = 0;
     __syncthreads();
-    const long long p = (long long)blockIdx.x * kChunk + threadIdx.x;
-    if (p < P) {
+    const long long p0 = (long long)blockIdx.x * chunk_pairs;
+    const long long p1 = p0 + chunk_pairs < P ? p0 + chunk_pairs : P;
+    for (long long p = p0 + threadIdx.x; p < p1; p += 256) {
         const int e = topk_expert[p];
         if (e >= 0 && e < E) atomicAdd(&hist[e], 1);
     }
     __syncthreads();
-    for (int e = threadIdx.x; e < E; e += kChunk) counts[(size_t)blockIdx.x * E + e] = hist[e];
+    for (int e = threadIdx.x; e < E; e += 256) counts[(size_t)blockIdx.x * E + e] = hist[e];
 }
 
-// One wavefront per expert: exclusive scan of its per-chunk counts, 64 chunks at a time.
+// One wavefront per expert: exclusive scan of its per-chunk counts, 64 chunks at a time.  The launch also
+// empties the routing table (slot_token = -1, slot_weight = 0).
 __global__ __launch_bounds__(256) void route_scan_kernel(int32_t* __restrict__ counts, int n_chunks, int E,
-                                                         int32_t* __restrict__ expert_demand) {
+                                                         int32_t* __restrict__ expert_demand,
+                                                         int32_t* __restrict__ slot_token,
+                                                         float* __restrict__ slot_weight, long long EC) {
+    const long long gid = blockIdx.x * (long long)blockDim.x + threadIdx.x;
+    const long long stride = (long long)gridDim.x * blockDim.x;
+    for (long long q = gid; q < EC; q += stride) {
+        slot_token[q] = -1;
+        slot_weight[q] = 0.0f;
+    }
     const int e = blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
     const int lane = threadIdx.x % kWave;
     if (e >= E) return;
@@ -68,17 +75,25 @@ __global__ __launch_bounds__(256) void route_scan_kernel(int32_t* __restrict__ c
 
 __global__ __launch_bounds__(64) void route_scatter_kernel(const int32_t* __restrict__ topk_expert,
                                                            const float* __restrict__ topk_weight, long long P,
-                                                           int E, int k, int C, const int32_t* __restrict__ base,
+                                                           int chunk_pairs, int n_chunks, int E, int k, int C,
+                                                           const int32_t* __restrict__ base,
                                                            int32_t* __restrict__ slot,
                                                            int32_t* __restrict__ slot_token,
-                                                           float* __restrict__ slot_weight) {
+                                                           float* __restrict__ slot_weight,
+                                                           const int32_t* __restrict__ expert_demand,
+                                                           int32_t* __restrict__ ffn_units) {
     extern __shared__ int32_t run[];                 // [E] slots handed out so far, per expert
+    __shared__ int wave_total[16];
+    if ((int)blockIdx.x == n_chunks) {               // the extra workgroup: list of live FFN units
+        build_ffn_units(expert_demand, C, E, (C + kUnitRows - 1) / kUnitRows, ffn_units, wave_total, 64);
+        return;
+    }
     const int c = blockIdx.x, lane = threadIdx.x;
     for (int e = lane; e < E; e += kWave) run[e] = base[(size_t)c * E + e];
     __syncthreads();
     const int nbits = E > 1 ? 32 - __clz(E - 1) : 0;
-    const long long p_end = ((long long)c + 1) * kChunk < P ? ((long long)c + 1) * kChunk : P;
-    for (long long p0 = (long long)c * kChunk; p0 < p_end; p0 += kWave) {
+    const long long p_end = ((long long)c + 1) * chunk_pairs < P ? ((long long)c + 1) * chunk_pairs : P;
+    for (long long p0 = (long long)c * chunk_pairs; p0 < p_end; p0 += kWave) {
         const long long p = p0 + lane;
         int e = p < p_end ? topk_expert[p] : -1;
         const bool valid = (e >= 0 && e < E);
@@ -127,20 +142,24 @@ __global__ __launch_bounds__(256) void pack_kernel(const u32x4* __restrict__ x, 
 
 }  // namespace
 
-int route_chunks(long long pairs) { return (int)((pairs + kChunk - 1) / kChunk); }
+int route_chunk_tokens() { return kChunkTokens; }
+int route_chunks(int T) { return (T + kChunkTokens - 1) / kChunkTokens; }
 
 hipError_t launch_route(const int32_t* topk_expert, const float* topk_weight, int T, int E, int k, int C,
-                        int32_t* counts, int32_t* slot, int32_t* expert_demand, int32_t* slot_token,
-                        float* slot_weight, hipStream_t stream) {
+                        int32_t* counts, bool counts_ready, int32_t* slot, int32_t* expert_demand,
+                        int32_t* slot_token, float* slot_weight, int32_t* ffn_units, hipStream_t stream) {
     const long long P = (long long)T * k;
-    const int n_chunks = route_chunks(P);
+    const int n_chunks = route_chunks(T);
+    const int chunk_pairs = kChunkTokens * k;
     const long long EC = (long long)E * C;
-    hipLaunchKernelGGL(route_count_kernel, dim3(n_chunks), dim3(kChunk), (size_t)E * sizeof(int32_t), stream,
-                       topk_expert, P, E, counts, slot_token, slot_weight, EC);
+    if (!counts_ready)
+        hipLaunchKernelGGL(route_count_kernel, dim3(n_chunks), dim3(256), (size_t)E * sizeof(int32_t), stream,
+                           topk_expert, P, chunk_pairs, E, counts);
     hipLaunchKernelGGL(route_scan_kernel, dim3((E + 3) / 4), dim3(256), 0, stream, counts, n_chunks, E,
-                       expert_demand);
-    hipLaunchKernelGGL(route_scatter_kernel, dim3(n_chunks), dim3(64), (size_t)E * sizeof(int32_t), stream,
-                       topk_expert, topk_weight, P, E, k, C, counts, slot, slot_token, slot_weight);
+                       expert_demand, slot_token, slot_weight, EC);
+    hipLaunchKernelGGL(route_scatter_kernel, dim3(n_chunks + (ffn_units ? 1 : 0)), dim3(64),
+                       (size_t)E * sizeof(int32_t), stream, topk_expert, topk_weight, P, chunk_pairs, n_chunks, E, k,
+                       C, counts, slot, slot_token, slot_weight, expert_demand, ffn_units);
     return hipGetLastError();
 }
 

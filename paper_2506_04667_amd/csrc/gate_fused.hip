@@ -43,7 +43,8 @@ struct GateCfg {
     static constexpr int COPIES = 2 + B_COPIES;
     static constexpr int TN = 2 * NB;                    // 32-expert MFMA tiles per wavefront
     static constexpr int LP = BN + 4;                    // row pitch (floats) of the logits tile
-    static_assert(G_BM * (LP + BN) * 4 <= LDS_BYTES, "logits tile and k <= BN weights per token must fit in the ring they reuse");
+    static_assert(G_BM * (LP + BN) * 4 + BN * 4 <= LDS_BYTES,
+                  "logits tile, k <= BN weights per token and the expert histogram must fit in the ring they reuse");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS budget of a gfx950 CU");
 };
 
@@ -72,7 +73,8 @@ template <class S, int NB>
 __global__ __launch_bounds__(G_THREADS) void gate_fused_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ Wg,
                                                                const float* __restrict__ gate_bias, int T, int H, int E, int k,
                                                                float* __restrict__ logits, int32_t* __restrict__ topk_expert,
-                                                               float* __restrict__ topk_weight) {
+                                                               float* __restrict__ topk_weight,
+                                                               int32_t* __restrict__ route_counts) {
     using C = GateCfg<NB>;
     constexpr int BN = C::BN, PITCH = C::PITCH, STAGE = C::STAGE, D = C::STAGES, TN = C::TN, LP = C::LP;
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
@@ -197,6 +199,11 @@ __global__ __launch_bounds__(G_THREADS) void gate_fused_kernel(const uint16_t* _
     constexpr int R = 4;                                 // a wavefront's 16 tokens: 4 at a time x 4 independent chains
     const int s16 = lane & 15;
     float* stash = lg + G_BM * LP;                       // [64 tokens][k]
+    int* hist = (int*)(lg + G_BM * (LP + BN));           // [E] picks per expert among this workgroup's tokens
+    if (route_counts) {
+        for (int e = tid; e < E; e += G_THREADS) hist[e] = 0;
+        __syncthreads();
+    }
     float vals[R][VL];
     int row[R];
 #pragma unroll
@@ -236,6 +243,7 @@ __global__ __launch_bounds__(G_THREADS) void gate_fused_kernel(const uint16_t* _
             if (s16 == 0 && row0 + row[c] < T) {
                 topk_expert[(size_t)(row0 + row[c]) * k + j] = bi;
                 stash[row[c] * k + j] = p;
+                if (route_counts && bi < E) atomicAdd(&hist[bi], 1);   // integer: the order of the additions does not matter
             }
             last_v[c] = bv;
             last_i[c] = bi;
@@ -247,11 +255,17 @@ __global__ __launch_bounds__(G_THREADS) void gate_fused_kernel(const uint16_t* _
         if (row0 + row[c] < T)
             for (int j = s16; j < k; j += 16)
                 topk_weight[(size_t)(row0 + row[c]) * k + j] = stash[row[c] * k + j] / sum[c];
+    // first step of the slot assignment: this workgroup's tokens are one chunk of the token-order scan
+    if (route_counts) {
+        __syncthreads();
+        for (int e = tid; e < E; e += G_THREADS) route_counts[(size_t)blockIdx.x * E + e] = hist[e];
+    }
 }
 
 template <class S, int NB>
 hipError_t launch_gate_fused_t(const void* x, const void* Wg, const float* gate_bias, int T, int H, int E, int k,
-                               float* logits, int32_t* topk_expert, float* topk_weight, hipStream_t stream) {
+                               float* logits, int32_t* topk_expert, float* topk_weight, int32_t* route_counts,
+                               hipStream_t stream) {
     auto kernel = gate_fused_kernel<S, NB>;
     static bool attr_set = false;                       // LDS above 64 KB must be requested once per kernel
     if (!attr_set) {
@@ -261,7 +275,8 @@ hipError_t launch_gate_fused_t(const void* x, const void* Wg, const float* gate_
         attr_set = true;
     }
     hipLaunchKernelGGL(kernel, dim3((unsigned)((T + G_BM - 1) / G_BM)), dim3(G_THREADS), GateCfg<NB>::LDS_BYTES, stream,
-                       (const uint16_t*)x, (const uint16_t*)Wg, gate_bias, T, H, E, k, logits, topk_expert, topk_weight);
+                       (const uint16_t*)x, (const uint16_t*)Wg, gate_bias, T, H, E, k, logits, topk_expert, topk_weight,
+                       route_counts);
     return hipGetLastError();
 }
 
@@ -273,12 +288,14 @@ bool gate_fused_eligible(int T, int H, int E, int k, int dtype) {
 }
 
 hipError_t launch_gate_fused(const void* x, const void* Wg, const float* gate_bias, int T, int H, int E, int k,
-                             int dtype, float* logits, int32_t* topk_expert, float* topk_weight, hipStream_t stream) {
+                             int dtype, float* logits, int32_t* topk_expert, float* topk_weight,
+                             int32_t* route_counts, hipStream_t stream) {
+    static_assert(G_BM == 64, "a workgroup's tokens are one chunk of the routing scan");
     if (E <= 128)
-        return dtype == 1 ? launch_gate_fused_t<BF16, 1>(x, Wg, gate_bias, T, H, E, k, logits, topk_expert, topk_weight, stream)
-                          : launch_gate_fused_t<F16, 1>(x, Wg, gate_bias, T, H, E, k, logits, topk_expert, topk_weight, stream);
-    return dtype == 1 ? launch_gate_fused_t<BF16, 2>(x, Wg, gate_bias, T, H, E, k, logits, topk_expert, topk_weight, stream)
-                      : launch_gate_fused_t<F16, 2>(x, Wg, gate_bias, T, H, E, k, logits, topk_expert, topk_weight, stream);
+        return dtype == 1 ? launch_gate_fused_t<BF16, 1>(x, Wg, gate_bias, T, H, E, k, logits, topk_expert, topk_weight, route_counts, stream)
+                          : launch_gate_fused_t<F16, 1>(x, Wg, gate_bias, T, H, E, k, logits, topk_expert, topk_weight, route_counts, stream);
+    return dtype == 1 ? launch_gate_fused_t<BF16, 2>(x, Wg, gate_bias, T, H, E, k, logits, topk_expert, topk_weight, route_counts, stream)
+                      : launch_gate_fused_t<F16, 2>(x, Wg, gate_bias, T, H, E, k, logits, topk_expert, topk_weight, route_counts, stream);
 }
 
 }  // namespace moe

@@ -47,6 +47,7 @@
 #include "common.h"
 #include "kernels.h"
 #include "lds_copy.h"
+#include "ffn_units.h"
 
 #include <type_traits>
 
@@ -68,6 +69,7 @@ constexpr int B_REGION = A_STAGES * A_STAGE;            // weights ring starts a
 constexpr int EPI_REGION = B_REGION + B_STAGES * B_STAGE;
 constexpr int EPI_BYTES_PER_WAVE = 32 * 128;            // 32 rows x 64 columns x 2 B
 constexpr int LDS_BYTES = EPI_REGION + 8 * EPI_BYTES_PER_WAVE;
+static_assert(BM == kUnitRows, "the unit list is cut in row tiles of this kernel");
 static_assert(LDS_BYTES <= 160 * 1024, "LDS budget of a gfx950 CU");
 
 template <class S> struct Mma16;
@@ -529,46 +531,10 @@ __global__ __launch_bounds__(THREADS) void ffn_gemm_stream_kernel(StreamArgs a) 
     pair_of_tiles(u + 2, std::false_type{}, std::true_type{});       // u == U - 2
 }
 
-// Compact list of the live (group, row tile) units of a grouped GEMM, in group order, in the scratch block
-// `w` of ffn_units_ints() ints: w[0] = fault word (cleared), w[1] = count, w[2 + q] = g * nrow + row tile,
-// then one completion counter per possible unit (cleared).  One workgroup; groups are scanned 1024 at a time.
 __global__ __launch_bounds__(1024) void ffn_units_kernel(const int32_t* __restrict__ rows_dev, int rows_cap, int groups,
                                                          int nrow, int32_t* __restrict__ w) {
     __shared__ int wave_total[16];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int cap = groups * nrow;
-    int32_t* units = w + 2;
-    int32_t* done = w + 2 + cap;
-    for (int i = tid; i < cap; i += 1024) done[i] = 0;
-    int carry = 0;                                      // units of the groups before this pass
-    for (int g0 = 0; g0 < groups; g0 += 1024) {
-        const int g = g0 + tid;
-        int nt = 0;
-        if (g < groups) {
-            const int rows = min(rows_dev[g], rows_cap);
-            nt = rows > 0 ? (rows + BM - 1) / BM : 0;
-        }
-        int incl = nt;                                  // inclusive scan inside the wavefront
-#pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {
-            const int up = __shfl_up(incl, d);
-            if (lane >= d) incl += up;
-        }
-        if (lane == 63) wave_total[wave] = incl;
-        __syncthreads();
-        int before = 0, total = 0;
-#pragma unroll
-        for (int wv = 0; wv < 16; ++wv) {
-            const int t = wave_total[wv];
-            before += wv < wave ? t : 0;
-            total += t;
-        }
-        const int start = carry + before + incl - nt;
-        for (int rt = 0; rt < nt; ++rt) units[start + rt] = g * nrow + rt;
-        carry += total;
-        __syncthreads();
-    }
-    if (tid == 0) { w[0] = 0; w[1] = carry; }
+    build_ffn_units(rows_dev, rows_cap, groups, nrow, w, wave_total, 1024);
 }
 
 StreamPhase to_phase(const GemmArgs& g) {

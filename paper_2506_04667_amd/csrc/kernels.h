@@ -59,18 +59,25 @@ hipError_t launch_transpose_pad(const void* Wg, void* WgT, int H, int E, int E_p
 // Fused gate for 16-bit storage: logits = x Wg (+ gate_bias) in fp32, top-k experts and combine weights,
 // one kernel; Wg is read as stored ([H][E]).  gate_fused_eligible tells whether the shape is covered.
 bool gate_fused_eligible(int T, int H, int E, int k, int dtype);
+// route_counts (optional): [ceil(T / 64)][E] picks per expert among each workgroup's 64 tokens, the first step
+// of the slot assignment (launch_route with counts_ready).
 hipError_t launch_gate_fused(const void* x, const void* Wg, const float* gate_bias, int T, int H, int E, int k,
-                             int dtype, float* logits, int32_t* topk_expert, float* topk_weight, hipStream_t stream);
+                             int dtype, float* logits, int32_t* topk_expert, float* topk_weight,
+                             int32_t* route_counts, hipStream_t stream);
 
 // Top-k selection and combine weights from fp32 logits.
 hipError_t launch_topk(const float* logits, int T, int E, int k, int32_t* topk_expert,
                        float* topk_weight, hipStream_t stream);
 
-// Token-order slot assignment.  `counts` is scratch of route_chunks(P) * E ints.
-int route_chunks(long long pairs);
-hipError_t launch_route(const int32_t* topk_expert, const float* topk_weight, int T, int E, int k,
-                        int C, int32_t* counts, int32_t* slot, int32_t* expert_demand,
-                        int32_t* slot_token, float* slot_weight, hipStream_t stream);
+// Token-order slot assignment.  The pairs are cut into chunks of route_chunk_tokens() tokens; `counts` is
+// scratch of route_chunks(T) * E ints.  With counts_ready the per-chunk expert counts are already there (the
+// fused gate wrote them).  With ffn_units != nullptr the last launch also builds the FFN kernels' unit list
+// for rows_cap = max_rows = C (see launch_ffn_units).
+int route_chunk_tokens();
+int route_chunks(int T);
+hipError_t launch_route(const int32_t* topk_expert, const float* topk_weight, int T, int E, int k, int C,
+                        int32_t* counts, bool counts_ready, int32_t* slot, int32_t* expert_demand,
+                        int32_t* slot_token, float* slot_weight, int32_t* ffn_units, hipStream_t stream);
 
 // xe[e][slot][:] = x[token][:] for every kept (token, choice).
 hipError_t launch_pack(const void* x, const int32_t* topk_expert, const int32_t* slot, int T, int H,
