@@ -28,7 +28,7 @@ namespace {
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
-constexpr int G_BM = 64, G_BK = 64, G_THREADS = 256;
+constexpr int G_BM = 64, G_BK = 64, G_THREADS = 512, G_WAVES = G_THREADS / 64;
 constexpr int G_A_STAGE = G_BM * 128;                    // 64 token rows x 64 k
 
 template <int NB>
@@ -39,8 +39,8 @@ struct GateCfg {
     static constexpr int STAGE = G_A_STAGE + B_STAGE;    // 24 KB or 40 KB
     static constexpr int STAGES = NB == 1 ? 6 : 4;
     static constexpr int LDS_BYTES = STAGES * STAGE;     // 144 KB or 160 KB
-    static constexpr int B_COPIES = B_STAGE / 1024 / 4;  // 1 KB copies per wavefront per K-tile
-    static constexpr int COPIES = 2 + B_COPIES;
+    static constexpr int B_COPIES = B_STAGE / 1024 / G_WAVES;  // 1 KB copies per wavefront per K-tile
+    static constexpr int COPIES = 1 + B_COPIES;
     static constexpr int TN = 2 * NB;                    // 32-expert MFMA tiles per wavefront
     static constexpr int LP = BN + 4;                    // row pitch (floats) of the logits tile
     static_assert(G_BM * (LP + BN) * 4 + BN * 4 <= LDS_BYTES,
@@ -82,20 +82,22 @@ __global__ __launch_bounds__(G_THREADS) void gate_fused_kernel(const uint16_t* _
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = uniform(tid >> 6);
-    const int wm = wave >> 1, wn = wave & 1;            // 2 x 2 wavefronts: 32 tokens x BN / 2 experts each
+    // two groups of 2 x 2 wavefronts (32 tokens x BN / 2 experts each); group kg multiplies k-steps 2 kg and
+    // 2 kg + 1 of every K-tile, and the two partial sums meet in LDS at the end: two wavefronts per SIMD hide
+    // each other's LDS latency and barrier waits without reading any operand twice more
+    const int kg = wave >> 2, wm = (wave >> 1) & 1, wn = wave & 1;
     const int l32 = lane & 31, g2 = lane >> 5;
     const int row0 = blockIdx.x * G_BM;
 
-    // ---- this wavefront's 1 KB copies per K-tile: 2 of token rows (8 rows x 128 B), B_COPIES of Wg ----
+    // ---- this wavefront's 1 KB copies per K-tile: 1 of token rows (8 rows x 128 B), B_COPIES of Wg ----
     const unsigned char* a_base = uniform((const unsigned char*)(x + (size_t)row0 * H));
     const unsigned char* b_base = uniform((const unsigned char*)Wg);
-    uint32_t a_off[2], b_off[C::B_COPIES];
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        const int r = (wave * 2 + j) * 8 + (lane >> 3), p = lane & 7;
+    uint32_t a_off, b_off[C::B_COPIES];
+    {
+        const int r = wave * 8 + (lane >> 3), p = lane & 7;
         const int c = p ^ ((r >> 1) & 7);
         const int rr = min(row0 + r, T - 1) - row0;     // rows beyond T repeat the last token (never stored)
-        a_off[j] = (uint32_t)rr * (uint32_t)(H * 2) + c * 16;
+        a_off = (uint32_t)rr * (uint32_t)(H * 2) + c * 16;
     }
     constexpr int CPR = PITCH / 16;                     // 16-byte chunks per k-row
 #pragma unroll
@@ -111,8 +113,7 @@ __global__ __launch_bounds__(G_THREADS) void gate_fused_kernel(const uint16_t* _
 
     auto issue = [&](int t) __attribute__((always_inline)) {
         const uint32_t d = lds_base + (t % D) * STAGE;
-#pragma unroll
-        for (int j = 0; j < 2; ++j) copy_to_lds(a_base, a_off[j], d + (wave * 2 + j) * 1024);
+        copy_to_lds(a_base, a_off, d + wave * 1024);
 #pragma unroll
         for (int j = 0; j < C::B_COPIES; ++j)
             copy_to_lds(b_base, b_off[j], d + G_A_STAGE + (wave * C::B_COPIES + j) * 1024);
@@ -125,13 +126,13 @@ __global__ __launch_bounds__(G_THREADS) void gate_fused_kernel(const uint16_t* _
     const int a_sw = (a_row >> 1) & 7;
     const int L = lane & 15, nb16 = (lane >> 4) & 1;
     const int bk = g2 * 8 + (L >> 2);                   // k of the first transpose read; the second is k + 4
-    int a_rd[4], b_rd[TN];
+    int a_rd[2], b_rd[TN];                              // this group's two k-steps: 2 kg, 2 kg + 1
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) a_rd[ks] = a_row * 128 + ((((ks << 1) | g2) ^ a_sw) << 4);
+    for (int i = 0; i < 2; ++i) a_rd[i] = a_row * 128 + (((((2 * kg + i) << 1) | g2) ^ a_sw) << 4);
 #pragma unroll
     for (int tn = 0; tn < TN; ++tn) {
         const int chunk = (wn * TN + tn) * 4 + nb16 * 2 + ((L & 3) >> 1);
-        b_rd[tn] = G_A_STAGE + bk * PITCH + ((chunk ^ ((bk & 3) << 1)) << 4) + (L & 1) * 8;
+        b_rd[tn] = G_A_STAGE + (2 * kg * 16 + bk) * PITCH + ((chunk ^ ((bk & 3) << 1)) << 4) + (L & 1) * 8;
     }
 
     f32x16 acc[TN];
@@ -150,7 +151,7 @@ __global__ __launch_bounds__(G_THREADS) void gate_fused_kernel(const uint16_t* _
         if (u + D - 1 < nk) issue(u + D - 1);
         const unsigned char* st = smem + (u % D) * STAGE;
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
+        for (int ks = 0; ks < 2; ++ks) {
             const u32x4 xf = *(const u32x4*)(st + a_rd[ks]);
 #pragma unroll
             for (int tn = 0; tn < TN; ++tn) {
@@ -164,29 +165,42 @@ __global__ __launch_bounds__(G_THREADS) void gate_fused_kernel(const uint16_t* _
     }
     wait_copies_and_barrier<0>();                       // every wavefront is done with the ring: reuse it
 
-    // ---- logits tile [64 tokens][LP] fp32 in LDS ----
+    // ---- logits tile [64 tokens][LP] fp32 in LDS: group 1 parks its partial sums, group 0 adds its own and
+    // the bias ----
     // accumulator elements 4 qa .. 4 qa + 3 of tile tn: experts e .. e + 3 of token l32
     float* lg = (float*)smem;
 #pragma unroll
-    for (int tn = 0; tn < TN; ++tn)
+    for (int pass = 1; pass >= 0; --pass) {
+        if (kg == pass) {
 #pragma unroll
-        for (int qa = 0; qa < 4; ++qa) {
-            const int e = (wn * TN + tn) * 32 + qa * 8 + g2 * 4;
-            f32x4 b = {0.0f, 0.0f, 0.0f, 0.0f};
-            if (gate_bias && e < E) b = *(const f32x4*)(gate_bias + e);
-            f32x4 v;
+            for (int tn = 0; tn < TN; ++tn)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) v[i] = acc[tn][qa * 4 + i] + b[i];
-            *(f32x4*)(lg + (wm * 32 + l32) * LP + e) = v;
+                for (int qa = 0; qa < 4; ++qa) {
+                    const int e = (wn * TN + tn) * 32 + qa * 8 + g2 * 4;
+                    float* cell = lg + (wm * 32 + l32) * LP + e;
+                    f32x4 v;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) v[i] = acc[tn][qa * 4 + i];
+                    if (pass == 0) {
+                        f32x4 b = {0.0f, 0.0f, 0.0f, 0.0f};
+                        if (gate_bias && e < E) b = *(const f32x4*)(gate_bias + e);
+                        const f32x4 other = *(const f32x4*)cell;
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) v[i] = (v[i] + other[i]) + b[i];
+                    }
+                    *(f32x4*)cell = v;
+                }
         }
-    __syncthreads();
+        __syncthreads();
+    }
 
-    // ---- logits to HBM: each wavefront stores its 16 tokens, full rows ----
+    // ---- logits to HBM: each wavefront stores its 8 tokens, full rows ----
+    constexpr int TOK = G_BM / G_WAVES;                 // tokens per wavefront from here on
     constexpr int LANES_PER_ROW = BN / 4;               // 32 or 64 lanes x 16 B
     constexpr int ROWS_PER_PASS = 64 / LANES_PER_ROW;
 #pragma unroll
-    for (int i = 0; i < 16 / ROWS_PER_PASS; ++i) {
-        const int r = wave * 16 + i * ROWS_PER_PASS + lane / LANES_PER_ROW, e = (lane % LANES_PER_ROW) * 4;
+    for (int i = 0; i < TOK / ROWS_PER_PASS; ++i) {
+        const int r = wave * TOK + i * ROWS_PER_PASS + lane / LANES_PER_ROW, e = (lane % LANES_PER_ROW) * 4;
         if (row0 + r < T && e < E) *(f32x4*)(logits + (size_t)(row0 + r) * E + e) = *(const f32x4*)(lg + r * LP + e);
     }
 
@@ -196,7 +210,7 @@ __global__ __launch_bounds__(G_THREADS) void gate_fused_kernel(const uint16_t* _
     // unnormalised weights exp(v_j - v_0) wait in LDS until the sum over the k picks is known.
     constexpr int VL = BN / 16;                          // logits per lane
     constexpr int kNone = 0x7fffffff;
-    constexpr int R = 4;                                 // a wavefront's 16 tokens: 4 at a time x 4 independent chains
+    constexpr int R = TOK / 4;                           // a wavefront's tokens: 4 at a time x R independent chains
     const int s16 = lane & 15;
     float* stash = lg + G_BM * LP;                       // [64 tokens][k]
     int* hist = (int*)(lg + G_BM * (LP + BN));           // [E] picks per expert among this workgroup's tokens
@@ -208,7 +222,7 @@ __global__ __launch_bounds__(G_THREADS) void gate_fused_kernel(const uint16_t* _
     int row[R];
 #pragma unroll
     for (int c = 0; c < R; ++c) {
-        row[c] = wave * 16 + c * 4 + (lane >> 4);
+        row[c] = wave * TOK + c * 4 + (lane >> 4);
 #pragma unroll
         for (int i = 0; i < VL / 4; ++i) {
             const f32x4 v = *(const f32x4*)(lg + row[c] * LP + i * 64 + s16 * 4);
