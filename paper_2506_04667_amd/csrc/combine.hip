@@ -19,24 +19,46 @@ __global__ __launch_bounds__(256) void combine_kernel(const void* __restrict__ y
         float acc[VEC];
 #pragma unroll
         for (int i = 0; i < VEC; ++i) acc[i] = 0.0f;
-        for (int j = 0; j < k; ++j) {
-            const int s = slot[(size_t)t * k + j];
-            if (s < 0 || s >= C) continue;
-            const int e = topk_expert[(size_t)t * k + j];
-            if (e < 0 || e >= E) continue;
-            const float w = topk_weight[(size_t)t * k + j];
-            const u32x4 v = ((const u32x4*)y)[((size_t)e * C_pad + s) * row_chunks + c];
-            if constexpr (S::kBytes == 4) {
+        // choices four at a time: first their routing entries, then all their row chunks in flight together,
+        // then the sums in ascending choice order
+        for (int j0 = 0; j0 < k; j0 += 4) {
+            float w[4];
+            size_t row[4];
+            bool live[4];
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const uint32_t u = v[i];   // copy out first: bit_cast of a vector element reads lane 0
-                    acc[i] = fmaf(w, __builtin_bit_cast(float, u), acc[i]);
+            for (int q = 0; q < 4; ++q) {
+                const int j = j0 + q;
+                live[q] = false;
+                w[q] = 0.0f;
+                row[q] = 0;
+                if (j < k) {
+                    const int s = slot[(size_t)t * k + j];
+                    const int e = topk_expert[(size_t)t * k + j];
+                    w[q] = topk_weight[(size_t)t * k + j];
+                    live[q] = s >= 0 && s < C && e >= 0 && e < E;
+                    if (live[q]) row[q] = (size_t)e * C_pad + s;
                 }
-            } else {
+            }
+            u32x4 v[4];
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    acc[2 * i] = fmaf(w, bits16_to_float<S>((uint16_t)(v[i] & 0xffffu)), acc[2 * i]);
-                    acc[2 * i + 1] = fmaf(w, bits16_to_float<S>((uint16_t)(v[i] >> 16)), acc[2 * i + 1]);
+            for (int q = 0; q < 4; ++q)
+                if (live[q]) v[q] = ((const u32x4*)y)[row[q] * row_chunks + c];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                if (!live[q]) continue;
+                if constexpr (S::kBytes == 4) {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const uint32_t u = v[q][i];   // copy out first: bit_cast of a vector element reads lane 0
+                        acc[i] = fmaf(w[q], __builtin_bit_cast(float, u), acc[i]);
+                    }
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const uint32_t u = v[q][i];
+                        acc[2 * i] = fmaf(w[q], bits16_to_float<S>((uint16_t)(u & 0xffffu)), acc[2 * i]);
+                        acc[2 * i + 1] = fmaf(w[q], bits16_to_float<S>((uint16_t)(u >> 16)), acc[2 * i + 1]);
+                    }
                 }
             }
         }
