@@ -12,7 +12,7 @@
 //     of the next task are in flight while the current one finishes and while its
 //     epilogue runs -- no drain between tasks;
 //   * tile 256 x 256 (8 wavefronts as 2 x 4, 128 rows x 64 columns each, MFMA
-//     32x32x16): an expert with <= 256 live rows reads its weights exactly once;
+//     16x16x32): an expert with <= 256 live rows reads its weights exactly once;
 //   * K-tile 32.  Weights (from HBM) go through a ring of 4 LDS stages of 16 KB
 //     (32 x 256), requested 3 K-tiles ahead; activations (re-read from L2 by the 8
 //     column tiles of an expert) go through 2 stages of 32 KB that hold two K-tiles
@@ -21,16 +21,18 @@
 //     issued from inline asm and waited for with explicit s_waitcnt vmcnt(n) +
 //     s_barrier: a compiler-visible LDS-DMA makes every later LDS read wait for all
 //     outstanding copies;
-//   * MFMA operand fragments are double-buffered in registers at k-step (16)
-//     granularity: while the MFMAs of one k-step run, the LDS reads of the next are
-//     in flight, across K-tile and task boundaries too.
+//   * MFMA operand fragments are double-buffered in registers at half-K-tile
+//     granularity: while 16 MFMAs run, the LDS reads of the next 16 are in flight,
+//     across K-tile and task boundaries too.
 //
 // A direct copy writes 64 lanes x 16 B to 1024 contiguous LDS bytes (lane i at
 // base + 16 i), while each lane picks its own global address; the XOR swizzles below
 // are therefore applied on the global side (which 16-byte chunk a lane fetches).
 //   A stage: row pitch 128 B; chunk c of row r lives at c ^ ((r >> 1) & 7).
-//   B stage: [k][n], row pitch 512 B; chunk c of row k lives at c ^ ((k & 3) << 1);
-//            read back in MFMA operand order with ds_read_b64_tr_b16.
+//   B stage: [k][n], row pitch 512 B; chunk c of row k lives at
+//            c ^ (((k & 3) << 1) | (((k >> 3) & 1) << 3)); read back in MFMA operand
+//            order with ds_read_b64_tr_b16 (the four 16-lane groups of a wavefront
+//            read the four k-octets of a K-tile).
 // Rows at or beyond the live row count are fetched from the last live row (their
 // products land in output rows that are never stored); columns beyond N likewise.
 // Because every lane supplies its own global address, the activation rows can be
@@ -59,7 +61,7 @@ typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
 constexpr int kXcds = 8;
 constexpr int BM = 256, BN = 256, BK = 32, THREADS = 512;
-constexpr int TM = 4, TN = 2, WN = 4;                   // 32x32 MFMA tiles per wavefront; wavefronts along N
+constexpr int TM = 8, TN = 4, WN = 4;                   // 16x16 MFMA tiles per wavefront (128 x 64); wavefronts along N
 constexpr int A_STAGE = BM * 128;                       // 256 rows x 64 k (two K-tiles)
 constexpr int A_STAGES = 2;
 constexpr int B_STAGE = BK * BN * 2;                    // 32 k x 256 columns
@@ -72,23 +74,26 @@ constexpr int LDS_BYTES = EPI_REGION + 8 * EPI_BYTES_PER_WAVE;
 static_assert(BM == kUnitRows, "the unit list is cut in row tiles of this kernel");
 static_assert(LDS_BYTES <= 160 * 1024, "LDS budget of a gfx950 CU");
 
+// v_mfma_f32_16x16x32: a lane holds, of each operand, 8 consecutive k (k = 8 (lane / 16) ..) of row/column
+// lane % 16, and of the result rows 4 (lane / 16) .. + 3 of column lane % 16.  Under sustained load with real
+// operand values this shape draws less power per flop than 32x32x16 (measured: it sustains a 15-40 % higher
+// rate in a register loop), and power is what bounds this kernel beyond its data path.
 template <class S> struct Mma16;
 template <> struct Mma16<BF16> {
-    static __device__ __forceinline__ f32x16 run(s16x8 a, s16x8 b, f32x16 c) {
-        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+    static __device__ __forceinline__ f32x4 run(s16x8 a, s16x8 b, f32x4 c) {
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
     }
 };
 template <> struct Mma16<F16> {
-    static __device__ __forceinline__ f32x16 run(s16x8 a, s16x8 b, f32x16 c) {
-        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+    static __device__ __forceinline__ f32x4 run(s16x8 a, s16x8 b, f32x4 c) {
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
     }
 };
 
-struct Frags {                                          // MFMA operands of one 16-wide k-step
-    u32x4 x[TM];                                        // activations, per row tile: 8 k-values of the lane's row
-    u32x4 w[TN];                                        // weights, per column tile: 8 k-values of the lane's column
-                                                        // (dwords 0-1 and 2-3 come from two transpose reads)
-};
+// MFMA operands of one K-tile (32 wide), double-buffered in registers: the weights of the wavefront's four
+// column tiles (two transpose reads each), and the activations of four of its eight row tiles at a time.
+struct WFrags { u32x4 w[TN]; };
+struct XFrags { u32x4 x[4]; };
 
 struct Task {                                           // wave-uniform description of one output tile
     int ph;                                             // 0: first GEMM of the kernel's work, 1: the dependent second one
@@ -218,7 +223,6 @@ __global__ __launch_bounds__(THREADS) void ffn_gemm_stream_kernel(StreamArgs a) 
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WN, wn = wave % WN;
-    const int l32 = lane & 31, g2 = lane >> 5;
 
     // ---- addresses of this wavefront's 1 KB copies, per task: uniform base + per-lane byte offset ----
     // activations: 4 copies of 8 rows x 128 B per K-tile pair; weights: 2 copies of 2 k-rows x 512 B per K-tile
@@ -240,7 +244,7 @@ __global__ __launch_bounds__(THREADS) void ffn_gemm_stream_kernel(StreamArgs a) 
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
             const int k = (wave * 2 + j) * 2 + (lane >> 5), p = lane & 31;
-            const int c = p ^ ((k & 3) << 1);
+            const int c = p ^ (((k & 3) << 1) | (((k >> 3) & 1) << 3));
             const int n = min(t.n0 + c * 8, N - 8);
             ob[j] = (uint32_t)k * (uint32_t)(ldb * 2) + n * 2;
         }
@@ -307,64 +311,45 @@ __global__ __launch_bounds__(THREADS) void ffn_gemm_stream_kernel(StreamArgs a) 
         b_issue_stage = b_issue_stage + 1 == B_STAGES ? 0 : b_issue_stage + 1;
     };
 
-    f32x16 acc[TM][TN];
+    f32x4 acc[TM][TN];                                  // [row tile of 16][column tile of 16]
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
 #pragma unroll
-            for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.0f;
+            for (int q = 0; q < 4; ++q) acc[i][j][q] = 0.0f;
 
     // ---- per-lane LDS read offsets ----
-    const int a_row = wm * TM * 32 + l32;
-    const int a_sw = (a_row >> 1) & 7;                  // same for every 32-row MFMA tile of this lane
-    const int L = lane & 15, nb16 = (lane >> 4) & 1;
-    const int bk = g2 * 8 + (L >> 2);                   // k of the first transpose read; second is k + 4
-    int a_rd[2][2], b_rd[TN];                           // [half of the 64-wide stage][k-step]
+    const int r16 = lane & 15, kq = lane >> 4;          // row/column inside a 16-wide MFMA tile; k-octet of the lane
+    const int a_row = wm * TM * 16 + r16;
+    const int a_sw = (a_row >> 1) & 7;                  // same for every 16-row tile of this lane
+    const int bk = kq * 8 + (r16 >> 2);                 // k of the first transpose read; the second is k + 4
+    const int b_sw = ((bk & 3) << 1) | (((bk >> 3) & 1) << 3);
+    int a_rd[2], b_rd[TN];                              // [half of the 64-wide activation stage]
 #pragma unroll
-    for (int h = 0; h < 2; ++h)
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks) a_rd[h][ks] = a_row * 128 + ((((h << 2) | (ks << 1) | g2) ^ a_sw) << 4);
+    for (int h = 0; h < 2; ++h) a_rd[h] = a_row * 128 + ((((h << 2) | kq) ^ a_sw) << 4);
 #pragma unroll
     for (int tn = 0; tn < TN; ++tn) {
-        const int chunk = (wn * TN + tn) * 4 + nb16 * 2 + ((L & 3) >> 1);
-        b_rd[tn] = B_REGION + bk * B_ROW_BYTES + ((chunk ^ ((bk & 3) << 1)) << 4) + (L & 1) * 8;
+        const int chunk = (wn * TN + tn) * 2 + ((r16 & 3) >> 1);
+        b_rd[tn] = B_REGION + bk * B_ROW_BYTES + ((chunk ^ b_sw) << 4) + (r16 & 1) * 8;
     }
 
-    // Read i (0..7) of the operands of k-step ks of the K-tile in activation stage sa (half h) and weight
-    // stage sb: the first column tile's weights, the row tiles' activations, the second column tile's weights.
-    auto read_frag = [&](int i, int sa, int h, int sb, Frags& f, int ks) __attribute__((always_inline)) {
-        const unsigned char* pw = smem + sb * B_STAGE + ks * 16 * B_ROW_BYTES;
-        const unsigned char* pa = smem + sa * A_STAGE + a_rd[h][ks];
-        switch (i) {
-            case 0: case 1: case 3: case 4: {
-                const int tn = i >= 3, half = (i == 1 || i == 4);
-                const u32x2 t = __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                                                              (lds_s16x4*)(pw + b_rd[tn] + half * 4 * B_ROW_BYTES)));
-                f.w[tn][2 * half] = t[0];
-                f.w[tn][2 * half + 1] = t[1];
-                break;
-            }
-            case 2: f.x[0] = *(const u32x4*)(pa); break;
-            case 5: f.x[1] = *(const u32x4*)(pa + 1 * 32 * 128); break;
-            case 6: f.x[2] = *(const u32x4*)(pa + 2 * 32 * 128); break;
-            default: f.x[3] = *(const u32x4*)(pa + 3 * 32 * 128); break;
-        }
+    // activations of row tiles 4 g .. 4 g + 3, K-tile in activation stage sa, half h: read i of 4
+    auto read_x = [&](int i, int g, int sa, int h, XFrags& f) __attribute__((always_inline)) {
+        f.x[i] = *(const u32x4*)(smem + sa * A_STAGE + a_rd[h] + (g * 4 + i) * 16 * 128);
     };
-    // MFMA i (0..7) of a k-step: row tile i / 2, column tile i % 2
-    auto mma_one = [&](int i, const Frags& f) __attribute__((always_inline)) {
-        const int tm = i >> 1, tn = i & 1;
-        acc[tm][tn] = Mma16<S>::run(__builtin_bit_cast(s16x8, f.w[tn]), __builtin_bit_cast(s16x8, f.x[tm]), acc[tm][tn]);
+    // weights of the K-tile in weight stage sb: read i of 8 (column tile i / 2, k 0-3 or 4-7 of the lane's octet)
+    auto read_w = [&](int i, int sb, WFrags& f) __attribute__((always_inline)) {
+        const int tn = i >> 1, half = i & 1;
+        const u32x2 t = __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                                                      (lds_s16x4*)(smem + sb * B_STAGE + b_rd[tn] + half * 4 * B_ROW_BYTES)));
+        f.w[tn][2 * half] = t[0];
+        f.w[tn][2 * half + 1] = t[1];
     };
-    // One k-step with the operand reads of the next one slotted between its MFMAs, so that issuing them
-    // costs no matrix-pipe time.  The order is pinned: the scheduler may not move anything across a fence.
-    auto step_same_tile = [&](const Frags& cur_f, Frags& nxt_f, int sa, int h, int sb, int ks) __attribute__((always_inline)) {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            mma_one(i, cur_f);
-            read_frag(i, sa, h, sb, nxt_f, ks);
-            __builtin_amdgcn_sched_barrier(0);
-        }
+    // MFMA i (0..15) of half g of a K-tile: row tile 4 g + i / 4, column tile i % 4
+    auto mma_one = [&](int i, int g, const WFrags& wf, const XFrags& xf) __attribute__((always_inline)) {
+        const int tm = g * 4 + (i >> 2), tn = i & 3;
+        acc[tm][tn] = Mma16<S>::run(__builtin_bit_cast(s16x8, wf.w[tn]), __builtin_bit_cast(s16x8, xf.x[i >> 2]), acc[tm][tn]);
     };
 
     // ---- epilogue of task `cur`: bias, activation, conversion, transposed store; then advance to the next task ----
@@ -373,46 +358,46 @@ __global__ __launch_bounds__(THREADS) void ffn_gemm_stream_kernel(StreamArgs a) 
         constexpr int ACT = decltype(act_tag)::value, PH = decltype(ph_tag)::value;
         const StreamPhase& P = a.ph[PH];
         const int N = P.N;
-        const int col_w = cur.n0 + wn * (TN * 32);      // first column of this wavefront
+        const int col_w = cur.n0 + wn * (TN * 16);      // first column of this wavefront
         const size_t c_base = (size_t)cur.grp * P.c_group_stride;
-        u32x2 bias_bits[TN][4];
+        // accumulator elements 0 .. 3 of tile (tm, tn): columns c .. c + 3 (c = 16 tn + 4 kq) of token row r16
+        u32x2 bias_bits[TN];
         if (P.bias) {
 #pragma unroll
-            for (int tn = 0; tn < TN; ++tn)
-#pragma unroll
-                for (int qa = 0; qa < 4; ++qa) {
-                    const int c = min(col_w + tn * 32 + qa * 8 + g2 * 4, N - 4);
-                    bias_bits[tn][qa] = *(const u32x2*)((const elem*)P.bias + (size_t)cur.grp * P.bias_group_stride + c);
-                }
+            for (int tn = 0; tn < TN; ++tn) {
+                const int c = min(col_w + tn * 16 + kq * 4, N - 4);
+                bias_bits[tn] = *(const u32x2*)((const elem*)P.bias + (size_t)cur.grp * P.bias_group_stride + c);
+            }
         }
 #pragma unroll
-        for (int tm = 0; tm < TM; ++tm) {
-            // accumulator elements 4 qa .. 4 qa + 3 of tile (tm, tn): columns c .. c + 3 of token row l32
+        for (int pass = 0; pass < TM / 2; ++pass) {      // 32 rows (two row tiles) at a time
 #pragma unroll
-            for (int tn = 0; tn < TN; ++tn)
+            for (int rh = 0; rh < 2; ++rh) {
+                const int tm = pass * 2 + rh, rl = rh * 16 + r16;
 #pragma unroll
-                for (int qa = 0; qa < 4; ++qa) {
+                for (int tn = 0; tn < TN; ++tn) {
                     float v[4];
 #pragma unroll
                     for (int b = 0; b < 4; ++b) {
                         float bias = 0.0f;
                         if (P.bias) {
-                            const uint32_t word = b < 2 ? bias_bits[tn][qa][0] : bias_bits[tn][qa][1];
+                            const uint32_t word = b < 2 ? bias_bits[tn][0] : bias_bits[tn][1];
                             bias = bits16_to_float<S>((uint16_t)((b & 1) ? (word >> 16) : (word & 0xffffu)));
                         }
-                        v[b] = apply_act16_t<ACT>(acc[tm][tn][qa * 4 + b] + bias);
-                        acc[tm][tn][qa * 4 + b] = 0.0f;
+                        v[b] = apply_act16_t<ACT>(acc[tm][tn][b] + bias);
+                        acc[tm][tn][b] = 0.0f;
                     }
-                    const int chunk = (tn * 4 + qa) ^ ((l32 >> 1) & 7);
-                    *(u32x2*)(epi + l32 * 128 + (chunk << 4) + g2 * 8) = u32x2{pack2<S>(v[0], v[1]), pack2<S>(v[2], v[3])};
+                    const int chunk = (tn * 2 + (kq >> 1)) ^ ((rl >> 1) & 7);
+                    *(u32x2*)(epi + rl * 128 + (chunk << 4) + (kq & 1) * 8) = u32x2{pack2<S>(v[0], v[1]), pack2<S>(v[2], v[3])};
                 }
+            }
             // a wavefront's LDS operations complete in order: the reads below see the writes above, and the
             // writes of the next pass come after these reads
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const int r_local = i * 8 + (lane >> 3), chunk = lane & 7;
                 const u32x4 v = *(const u32x4*)(epi + r_local * 128 + ((chunk ^ ((r_local >> 1) & 7)) << 4));
-                const int row = cur.row0 + (wm * TM + tm) * 32 + r_local, col = col_w + chunk * 8;
+                const int row = cur.row0 + wm * (TM * 16) + pass * 32 + r_local, col = col_w + chunk * 8;
                 if (row < cur.rows && col < N) *(u32x4*)((elem*)P.C + c_base + (size_t)row * P.ldc + col) = v;
             }
         }
@@ -446,11 +431,14 @@ __global__ __launch_bounds__(THREADS) void ffn_gemm_stream_kernel(StreamArgs a) 
     };
 
     // ---- main loop over the stream of K-tiles u = 0 .. U-1 ----
-    // K-tile u: weights in stage u % 4, activations in stage (u / 2) % 2, half u % 2; consumed as two
-    // 16-wide k-steps.  The operands of the next k-step are read from LDS while the MFMAs of the current one
-    // run.  Between the two k-steps of tile u the wave waits for tile u+1, then requests weights tile u+4
-    // (into the stage tile u vacated) and, after an odd u, the activation pair (u+3)/2 (into the stage the
-    // pair u/2 vacated).  Copies of one wave complete in issue order, which in steady state reads
+    // K-tile u: weights in stage u % 4, activations in stage (u / 2) % 2, half u % 2; one 32-wide MFMA step
+    // per 16 x 16 tile, done as two halves of 16 MFMAs (row tiles 0-3, then 4-7).  Operands are read from
+    // LDS one step ahead, slotted between the MFMAs: during the first half the activations of the second
+    // half; during the second half the weights and first-half activations of tile u+1.  Early in the second
+    // half of tile u the wave waits for tile u+1, then requests weights tile u+4 (into the stage tile u
+    // vacated) and, after an odd u, the activation pair (u+3)/2 (into the stage the pair u/2 vacated: every
+    // wavefront holds the rest of that pair in registers by then).  Copies of one wave complete in issue
+    // order, which in steady state reads
     //   ... B | A B | B | A B | B | A B ...      (A = 4 copies, B = 2 copies; one group per K-tile)
     // so "tile u+1 has landed" is vmcnt(8) before an odd tile (only its weights are new: the newer copies
     // are B A B) and vmcnt(4) before an even tile (its activation pair is new: the newer copies are B B).
@@ -463,11 +451,35 @@ __global__ __launch_bounds__(THREADS) void ffn_gemm_stream_kernel(StreamArgs a) 
     issue_a();
     issue_b();
     wait_copies_and_barrier<4>();                       // A0 and B0 (and more) have landed
-    Frags f0, f1;
+    WFrags w0, w1;                                      // weights of the even / odd tile of a pair
+    XFrags x0, x1;                                      // activations of row tiles 0-3 / 4-7
 #pragma unroll
-    for (int i = 0; i < 8; ++i) read_frag(i, 0, 0, 0, f0, 0);
+    for (int i = 0; i < 8; ++i) read_w(i, 0, w0);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) read_x(i, 0, 0, 0, x0);
     int sb = 0;                                         // weight stage of tile u
     int k_done = 0;                                     // K-tiles of `cur` multiplied so far
+
+    // First half of a K-tile (weights wf, activations x0), reading the second half's activations into x1.
+    auto first_half = [&](const WFrags& wf, int sa, int h) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            mma_one(i, 0, wf, x0);
+            if ((i & 3) == 0) read_x(i >> 2, 1, sa, h, x1);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+    // Second half of a K-tile after its first four MFMAs: twelve MFMAs with the twelve reads of the next
+    // tile's operands (weights in stage sb_n -> wn_f, activations of its first half -> x0) between them.
+    auto second_half_tail = [&](const WFrags& wf, WFrags& wn_f, int sb_n, int sa_n, int h_n) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 4; i < 16; ++i) {
+            mma_one(i, 1, wf, x1);
+            if (i < 12) read_w(i - 4, sb_n, wn_f);
+            else read_x(i - 12, 0, sa_n, h_n, x0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
 
     // One pair of K-tiles (u even, u + 1).  STEADY: u <= U - 6, so every request below exists and the wait
     // counts above hold; otherwise nothing more is requested and the waits are for everything in flight.
@@ -475,47 +487,33 @@ __global__ __launch_bounds__(THREADS) void ffn_gemm_stream_kernel(StreamArgs a) 
     auto pair_of_tiles = [&](int u, auto steady_tag, auto last_tag) __attribute__((always_inline)) {
         constexpr bool STEADY = decltype(steady_tag)::value, LAST = decltype(last_tag)::value;
         const int sa = (u >> 1) & 1;
-        // ---- even tile u: first k-step, reading its second ----
-        step_same_tile(f0, f1, sa, 0, sb, 1);
-        // second k-step: half of its MFMAs cover the wait for tile u+1, whose first k-step is then read
+        // ---- even tile u ----
+        first_half(w0, sa, 0);
         const int sb1 = (sb + 1) & (B_STAGES - 1);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) mma_one(i, f1);
+        for (int i = 0; i < 4; ++i) mma_one(i, 1, w0, x1);   // these cover the wait for tile u+1
         __builtin_amdgcn_sched_barrier(0);
         wait_copies_and_barrier<STEADY ? 8 : 0>();
         if (STEADY) issue_b();
         __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int i = 4; i < 8; ++i) {
-            mma_one(i, f1);
-            read_frag(2 * (i - 4), sa, 1, sb1, f0, 0);
-            read_frag(2 * (i - 4) + 1, sa, 1, sb1, f0, 0);
-            __builtin_amdgcn_sched_barrier(0);
-        }
+        second_half_tail(w0, w1, sb1, sa, 1);
         // ---- odd tile u + 1 ----
-        step_same_tile(f0, f1, sa, 1, sb1, 1);
+        first_half(w1, sa, 1);
         sb = (sb1 + 1) & (B_STAGES - 1);
         if (!LAST) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) mma_one(i, f1);
+            for (int i = 0; i < 4; ++i) mma_one(i, 1, w1, x1);
             __builtin_amdgcn_sched_barrier(0);
             wait_copies_and_barrier<STEADY ? 4 : 0>();
-            // every wave holds the rest of the pair in registers: its activation stage can be refilled
             if (STEADY) {
                 issue_a();
                 issue_b();
             }
             __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int i = 4; i < 8; ++i) {
-                mma_one(i, f1);
-                read_frag(2 * (i - 4), sa ^ 1, 0, sb, f0, 0);
-                read_frag(2 * (i - 4) + 1, sa ^ 1, 0, sb, f0, 0);
-                __builtin_amdgcn_sched_barrier(0);
-            }
+            second_half_tail(w1, w0, sb, sa ^ 1, 0);
         } else {
 #pragma unroll
-            for (int i = 0; i < 8; ++i) mma_one(i, f1);
+            for (int i = 0; i < 16; ++i) mma_one(i, 1, w1, x1);
             __builtin_amdgcn_sched_barrier(0);
         }
         k_done += 2;
