@@ -8,7 +8,7 @@
 // from L2.  Both go straight to LDS (global_load_lds_dwordx4) through a ring of K-tiles of
 // 64, several tiles ahead, with explicit waits.  LDS layouts and swizzles are those of the
 // streaming FFN kernel: token rows 128 B per K-tile, chunk c of row r at c ^ ((r >> 1) & 7);
-// Wg tile [k][n], chunk c of row k at c ^ ((k & 3) << 1), read in MFMA operand order with
+// Wg tile [k][n], chunk c of row k at c ^ ((k & 3) << 2), read in MFMA operand order with
 // ds_read_b64_tr_b16.  The MFMAs take the Wg fragment first, so a lane's accumulators hold
 // runs of four consecutive experts of ONE token.
 //
@@ -103,7 +103,7 @@ __global__ __launch_bounds__(G_THREADS) void gate_fused_kernel(const uint16_t* _
 #pragma unroll
     for (int j = 0; j < C::B_COPIES; ++j) {
         const int kk = (wave * C::B_COPIES + j) * (64 / CPR) + lane / CPR, p = lane % CPR;
-        const int c = p ^ ((kk & 3) << 1);
+        const int c = p ^ ((kk & 3) << 2);
         const int n = min(c * 8, E - 8);                // columns beyond E repeat the last 8 experts (masked later)
         b_off[j] = (uint32_t)kk * (uint32_t)(E * 2) + n * 2;
     }
@@ -132,7 +132,7 @@ __global__ __launch_bounds__(G_THREADS) void gate_fused_kernel(const uint16_t* _
 #pragma unroll
     for (int tn = 0; tn < TN; ++tn) {
         const int chunk = (wn * TN + tn) * 4 + nb16 * 2 + ((L & 3) >> 1);
-        b_rd[tn] = G_A_STAGE + (2 * kg * 16 + bk) * PITCH + ((chunk ^ ((bk & 3) << 1)) << 4) + (L & 1) * 8;
+        b_rd[tn] = G_A_STAGE + (2 * kg * 16 + bk) * PITCH + ((chunk ^ ((bk & 3) << 2)) << 4) + (L & 1) * 8;
     }
 
     f32x16 acc[TN];

@@ -21,7 +21,7 @@
 // banks of 4 bytes):
 //   A (and an [n][k] B):  row pitch 128 B, chunk c of row r lives at c ^ ((r >> 1) & 7)
 //                         -> 16-byte operand reads of 16 consecutive rows hit 16 distinct chunks.
-//   [k][n] B, 16-bit:     chunk c of row k lives at c ^ ((k & 3) << 1); the MFMA B operand
+//   [k][n] B, 16-bit:     chunk c of row k lives at c ^ ((k & 3) << 2); the MFMA B operand
 //                         (k contiguous per lane) is produced by the LDS transpose read
 //                         ds_read_b64_tr_b16: within 16 lanes, lane i receives, as element j,
 //                         element (i % 4) of the 8-byte row addressed by lane 4 j + i / 4.
@@ -79,7 +79,7 @@ __device__ __forceinline__ int a_off(int r, int c) { return r * 128 + ((c ^ ((r 
 // byte offset of 16-byte chunk c of row k in a [k][n] B tile
 template <bool k16>
 __device__ __forceinline__ int b_off(int k, int c, int row_bytes) {
-    return k * row_bytes + ((c ^ (k16 ? ((k & 3) << 1) : (((k >> 2) & 1) << 3))) << 4);
+    return k * row_bytes + ((c ^ (k16 ? ((k & 3) << 2) : (((k >> 2) & 1) << 3))) << 4);
 }
 
 template <class S, bool NT, int WM, int WN, int TM, int TN>
