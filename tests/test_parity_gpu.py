@@ -163,6 +163,22 @@ def test_fused_gate_shapes(oracle, T, H, E, k, dtype, bias):
     np.testing.assert_allclose(b.topk_weight.cpu().numpy(), tw, rtol=1e-5, atol=1e-7)
 
 
+@pytest.mark.parametrize("case", [
+    dict(T=1000, H=256, I=256, E=24, k=3, capacity_factor=1.0, dtype="bf16", act="relu"),       # ragged last chunk of 64 tokens
+    dict(T=700, H=128, I=264, E=136, k=4, capacity_factor=0.5, dtype="f16", act="gelu_tanh"),   # wide expert tile, many drops
+    dict(T=63, H=64, I=64, E=8, k=8, capacity_factor=1.0, dtype="bf16", act="identity"),        # a single partial chunk, k = E
+])
+def test_fused_gate_feeds_the_routing_scan(oracle, case):
+    # moe_forward: the fused gate kernel writes the per-chunk expert counts that the slot assignment starts from;
+    # the staged calls count with the stand-alone kernel instead.  Both must give the oracle's routing.
+    w = scaled(WORKLOADS["paper_bf16_e128"], name="gate_counts", seed=33, **case)
+    cpu, dev, b, host, rep = _run(oracle, w)
+    b2, host2 = parity.gpu_forward(w, dev, staged=True)
+    for n in host:
+        np.testing.assert_array_equal(host[n], host2[n], err_msg=n)
+    assert torch.equal(b.out, b2.out)
+
+
 @pytest.mark.parametrize("E,k", [(16, 4), (128, 2), (200, 7)])
 def test_fused_gate_exact_ties(oracle, E, k):
     # small-integer operands: every logit is an exact small integer, so whole groups of experts tie and the
