@@ -1,12 +1,13 @@
-// Fused gate for 16-bit storage ("FusedGate" of Alg. 1): one kernel computes the gate
+// Fused gate ("FusedGate" of Alg. 1), all storage types: one kernel computes the gate
 // logits x Wg (+ bias) on the matrix cores, writes them, and selects each token's top-k
 // experts with their combine weights (Eqs. "combine 1/2": softmax over the k selected
 // logits) -- no transposed copy of Wg, no second pass over the logits in HBM.
 //
-// One workgroup (4 wavefronts) owns 64 tokens and all E <= 128 NB experts.  The token rows
+// One workgroup (8 wavefronts) owns 64 tokens and all E <= 256 experts.  The token rows
 // stream from HBM exactly once; Wg (H x E, a few hundred KB) is re-read by every workgroup
 // from L2.  Both go straight to LDS (global_load_lds_dwordx4) through a ring of K-tiles of
-// 64, several tiles ahead, with explicit waits.  LDS layouts and swizzles are those of the
+// 128 bytes per row (64 elements, or 32 in fp32), several tiles ahead, with explicit waits.
+// In 16-bit storage the LDS layouts and swizzles are those of the
 // streaming FFN kernel: token rows 128 B per K-tile, chunk c of row r at c ^ ((r >> 1) & 7);
 // Wg tile [k][n], chunk c of row k at c ^ ((k & 3) << 2), read in MFMA operand order with
 // ds_read_b64_tr_b16.  The MFMAs take the Wg fragment first, so a lane's accumulators hold
@@ -14,7 +15,7 @@
 //
 // Epilogue: logits (+ bias) go to an fp32 LDS tile (it reuses the ring), from there to HBM
 // with full-line stores, and the selection reads the same tile: 16 lanes per token, each
-// holding 8 NB logits in registers; k rounds of "largest remaining logit, smaller expert
+// holding a sixteenth of the row in registers; k rounds of "largest remaining logit, smaller expert
 // index on equal values" compared as floats (so -0.0 and +0.0 tie), where "remaining" means
 // strictly after the previous pick in that order.  The 16 lanes agree on each pick through
 // DPP exchanges; the unnormalised weights wait in LDS until the softmax denominator is known.
@@ -28,21 +29,26 @@ namespace {
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
-constexpr int G_BM = 64, G_BK = 64, G_THREADS = 512, G_WAVES = G_THREADS / 64;
-constexpr int G_A_STAGE = G_BM * 128;                    // 64 token rows x 64 k
+constexpr int G_BM = 64, G_THREADS = 512, G_WAVES = G_THREADS / 64;
+constexpr int G_A_STAGE = G_BM * 128;                    // 64 token rows x 128 bytes of k
 
-template <int NB>
+// S: storage type; BN: experts covered (64 for fp32 only, 128, 256).  A K-tile is 128 bytes of k per token
+// row: 64 elements in 16-bit storage, 32 in fp32.
+template <class S, int BN_>
 struct GateCfg {
-    static constexpr int BN = 128 * NB;
-    static constexpr int PITCH = BN * 2;                 // bytes per k-row of the Wg tile
-    static constexpr int B_STAGE = G_BK * PITCH;
-    static constexpr int STAGE = G_A_STAGE + B_STAGE;    // 24 KB or 40 KB
-    static constexpr int STAGES = NB == 1 ? 6 : 4;
-    static constexpr int LDS_BYTES = STAGES * STAGE;     // 144 KB or 160 KB
+    static constexpr int BN = BN_;
+    static constexpr int EL = S::kBytes, VEC = 16 / EL;  // bytes per element; elements per 16-byte chunk
+    static constexpr int KT = 128 / EL;                  // k per K-tile
+    static constexpr int PITCH = BN * EL;                // bytes per k-row of the Wg tile
+    static constexpr int B_STAGE = KT * PITCH;
+    static constexpr int STAGE = G_A_STAGE + B_STAGE;    // 16, 24 or 40 KB
+    static constexpr int STAGES = B_STAGE > 16384 ? 4 : 6;
+    static constexpr int LDS_BYTES = STAGES * STAGE;     // at most 160 KB
     static constexpr int B_COPIES = B_STAGE / 1024 / G_WAVES;  // 1 KB copies per wavefront per K-tile
     static constexpr int COPIES = 1 + B_COPIES;
-    static constexpr int TN = 2 * NB;                    // 32-expert MFMA tiles per wavefront
+    static constexpr int TN = BN / 64;                   // 32-expert MFMA tiles per wavefront
     static constexpr int LP = BN + 4;                    // row pitch (floats) of the logits tile
+    static_assert(PITCH >= 256, "the swizzles of the Wg tile move chunks by up to 12 or 8 places");
     static_assert(G_BM * (LP + BN) * 4 + BN * 4 <= LDS_BYTES,
                   "logits tile, k <= BN weights per token and the expert histogram must fit in the ring they reuse");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS budget of a gfx950 CU");
@@ -69,14 +75,16 @@ __device__ __forceinline__ void merge_best(float& bv, int& bi) {
     if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
 }
 
-template <class S, int NB>
-__global__ __launch_bounds__(G_THREADS) void gate_fused_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ Wg,
+template <class S, int BN_>
+__global__ __launch_bounds__(G_THREADS) void gate_fused_kernel(const unsigned char* __restrict__ x, const unsigned char* __restrict__ Wg,
                                                                const float* __restrict__ gate_bias, int T, int H, int E, int k,
                                                                float* __restrict__ logits, int32_t* __restrict__ topk_expert,
                                                                float* __restrict__ topk_weight,
                                                                int32_t* __restrict__ route_counts) {
-    using C = GateCfg<NB>;
+    using C = GateCfg<S, BN_>;
     constexpr int BN = C::BN, PITCH = C::PITCH, STAGE = C::STAGE, D = C::STAGES, TN = C::TN, LP = C::LP;
+    constexpr int EL = C::EL, VEC = C::VEC, KT = C::KT;
+    constexpr bool k16 = EL == 2;
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
     const int tid = threadIdx.x;
@@ -90,26 +98,26 @@ __global__ __launch_bounds__(G_THREADS) void gate_fused_kernel(const uint16_t* _
     const int row0 = blockIdx.x * G_BM;
 
     // ---- this wavefront's 1 KB copies per K-tile: 1 of token rows (8 rows x 128 B), B_COPIES of Wg ----
-    const unsigned char* a_base = uniform((const unsigned char*)(x + (size_t)row0 * H));
-    const unsigned char* b_base = uniform((const unsigned char*)Wg);
+    const unsigned char* a_base = uniform(x + (size_t)row0 * H * EL);
+    const unsigned char* b_base = uniform(Wg);
     uint32_t a_off, b_off[C::B_COPIES];
     {
         const int r = wave * 8 + (lane >> 3), p = lane & 7;
         const int c = p ^ ((r >> 1) & 7);
         const int rr = min(row0 + r, T - 1) - row0;     // rows beyond T repeat the last token (never stored)
-        a_off = (uint32_t)rr * (uint32_t)(H * 2) + c * 16;
+        a_off = (uint32_t)rr * (uint32_t)(H * EL) + c * 16;
     }
     constexpr int CPR = PITCH / 16;                     // 16-byte chunks per k-row
 #pragma unroll
     for (int j = 0; j < C::B_COPIES; ++j) {
         const int kk = (wave * C::B_COPIES + j) * (64 / CPR) + lane / CPR, p = lane % CPR;
-        const int c = p ^ ((kk & 3) << 2);
-        const int n = min(c * 8, E - 8);                // columns beyond E repeat the last 8 experts (masked later)
-        b_off[j] = (uint32_t)kk * (uint32_t)(E * 2) + n * 2;
+        const int c = p ^ (k16 ? ((kk & 3) << 2) : (((kk >> 2) & 1) << 3));
+        const int n = min(c * VEC, E - VEC);            // columns beyond E repeat the last experts (masked later)
+        b_off[j] = (uint32_t)kk * (uint32_t)(E * EL) + n * EL;
     }
-    const size_t b_step = (size_t)G_BK * E * 2;
+    const size_t b_step = (size_t)KT * E * EL;
     const uint32_t lds_base = (uint32_t)(size_t)(__attribute__((address_space(3))) unsigned char*)smem;
-    const int nk = H / G_BK;
+    const int nk = H / KT;
 
     auto issue = [&](int t) __attribute__((always_inline)) {
         const uint32_t d = lds_base + (t % D) * STAGE;
@@ -131,8 +139,16 @@ __global__ __launch_bounds__(G_THREADS) void gate_fused_kernel(const uint16_t* _
     for (int i = 0; i < 2; ++i) a_rd[i] = a_row * 128 + (((((2 * kg + i) << 1) | g2) ^ a_sw) << 4);
 #pragma unroll
     for (int tn = 0; tn < TN; ++tn) {
-        const int chunk = (wn * TN + tn) * 4 + nb16 * 2 + ((L & 3) >> 1);
-        b_rd[tn] = G_A_STAGE + (2 * kg * 16 + bk) * PITCH + ((chunk ^ ((bk & 3) << 2)) << 4) + (L & 1) * 8;
+        if (k16) {
+            const int chunk = (wn * TN + tn) * 4 + nb16 * 2 + ((L & 3) >> 1);
+            b_rd[tn] = G_A_STAGE + (2 * kg * 16 + bk) * PITCH + ((chunk ^ ((bk & 3) << 2)) << 4) + (L & 1) * 8;
+        } else {
+            // fp32: a k-step is 8 wide; the lane's 16-byte activation chunk holds k = 8 ks + 4 g2 + 0..3, and the
+            // matching weights are four 4-byte reads at those k, column n (v_mfma_f32_32x32x2 takes one k per
+            // half-wavefront; which k of the tile that is does not matter as long as both operands agree)
+            const int n = (wn * TN + tn) * 32 + l32;
+            b_rd[tn] = G_A_STAGE + (2 * kg * 8 + 4 * g2) * PITCH + (((n >> 2) ^ (g2 << 3)) << 4) + (n & 3) * 4;
+        }
     }
 
     f32x16 acc[TN];
@@ -152,14 +168,28 @@ __global__ __launch_bounds__(G_THREADS) void gate_fused_kernel(const uint16_t* _
         const unsigned char* st = smem + (u % D) * STAGE;
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks) {
-            const u32x4 xf = *(const u32x4*)(st + a_rd[ks]);
+            if constexpr (k16) {
+                const u32x4 xf = *(const u32x4*)(st + a_rd[ks]);
 #pragma unroll
-            for (int tn = 0; tn < TN; ++tn) {
-                const unsigned char* pw = st + b_rd[tn] + ks * 16 * PITCH;
-                const u32x2 lo = __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)pw));
-                const u32x2 hi = __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(pw + 4 * PITCH)));
-                const u32x4 wf = {lo[0], lo[1], hi[0], hi[1]};
-                acc[tn] = GateMma<S>::run(__builtin_bit_cast(s16x8, wf), __builtin_bit_cast(s16x8, xf), acc[tn]);
+                for (int tn = 0; tn < TN; ++tn) {
+                    const unsigned char* pw = st + b_rd[tn] + ks * 16 * PITCH;
+                    const u32x2 lo = __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)pw));
+                    const u32x2 hi = __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(pw + 4 * PITCH)));
+                    const u32x4 wf = {lo[0], lo[1], hi[0], hi[1]};
+                    acc[tn] = GateMma<S>::run(__builtin_bit_cast(s16x8, wf), __builtin_bit_cast(s16x8, xf), acc[tn]);
+                }
+            } else {
+                const f32x4 xf = *(const f32x4*)(st + a_rd[ks]);
+                float wv[TN][4];
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) wv[tn][j] = *(const float*)(st + b_rd[tn] + (ks * 8 + j) * PITCH);
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+#pragma unroll
+                    for (int tn = 0; tn < TN; ++tn)
+                        acc[tn] = __builtin_amdgcn_mfma_f32_32x32x2f32(wv[tn][j], xf[j], acc[tn], 0, 0, 0);
             }
         }
     }
@@ -276,40 +306,53 @@ __global__ __launch_bounds__(G_THREADS) void gate_fused_kernel(const uint16_t* _
     }
 }
 
-template <class S, int NB>
+template <class S, int BN>
 hipError_t launch_gate_fused_t(const void* x, const void* Wg, const float* gate_bias, int T, int H, int E, int k,
                                float* logits, int32_t* topk_expert, float* topk_weight, int32_t* route_counts,
                                hipStream_t stream) {
-    auto kernel = gate_fused_kernel<S, NB>;
+    auto kernel = gate_fused_kernel<S, BN>;
+    constexpr int lds_bytes = GateCfg<S, BN>::LDS_BYTES;
     static bool attr_set = false;                       // LDS above 64 KB must be requested once per kernel
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, GateCfg<NB>::LDS_BYTES);
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL(kernel, dim3((unsigned)((T + G_BM - 1) / G_BM)), dim3(G_THREADS), GateCfg<NB>::LDS_BYTES, stream,
-                       (const uint16_t*)x, (const uint16_t*)Wg, gate_bias, T, H, E, k, logits, topk_expert, topk_weight,
-                       route_counts);
+    hipLaunchKernelGGL(kernel, dim3((unsigned)((T + G_BM - 1) / G_BM)), dim3(G_THREADS), lds_bytes, stream,
+                       (const unsigned char*)x, (const unsigned char*)Wg, gate_bias, T, H, E, k, logits, topk_expert,
+                       topk_weight, route_counts);
     return hipGetLastError();
+}
+
+template <class S>
+hipError_t launch_gate_fused_s(const void* x, const void* Wg, const float* gate_bias, int T, int H, int E, int k,
+                               float* logits, int32_t* topk_expert, float* topk_weight, int32_t* route_counts,
+                               hipStream_t stream) {
+    if (S::kBytes == 4 && E <= 64)
+        return launch_gate_fused_t<F32, 64>(x, Wg, gate_bias, T, H, E, k, logits, topk_expert, topk_weight, route_counts, stream);
+    if (E <= 128)
+        return launch_gate_fused_t<S, 128>(x, Wg, gate_bias, T, H, E, k, logits, topk_expert, topk_weight, route_counts, stream);
+    return launch_gate_fused_t<S, 256>(x, Wg, gate_bias, T, H, E, k, logits, topk_expert, topk_weight, route_counts, stream);
 }
 
 }  // namespace
 
 bool gate_fused_eligible(int T, int H, int E, int k, int dtype) {
-    return dtype != 0 && E % 8 == 0 && E >= 8 && E <= 256 && H % G_BK == 0 && H >= G_BK && k >= 1 && k <= E &&
-           (long long)G_BM * H * 2 < (1ll << 31) && (long long)G_BK * E * 2 < (1ll << 31);
+    const int el = dtype == 0 ? 4 : 2, vec = 16 / el, kt = 128 / el;
+    return E % vec == 0 && E >= vec && E <= 256 && H % kt == 0 && H >= kt && k >= 1 && k <= E &&
+           (long long)G_BM * H * el < (1ll << 31) && (long long)kt * E * el < (1ll << 31);
 }
 
 hipError_t launch_gate_fused(const void* x, const void* Wg, const float* gate_bias, int T, int H, int E, int k,
                              int dtype, float* logits, int32_t* topk_expert, float* topk_weight,
                              int32_t* route_counts, hipStream_t stream) {
     static_assert(G_BM == 64, "a workgroup's tokens are one chunk of the routing scan");
-    if (E <= 128)
-        return dtype == 1 ? launch_gate_fused_t<BF16, 1>(x, Wg, gate_bias, T, H, E, k, logits, topk_expert, topk_weight, route_counts, stream)
-                          : launch_gate_fused_t<F16, 1>(x, Wg, gate_bias, T, H, E, k, logits, topk_expert, topk_weight, route_counts, stream);
-    return dtype == 1 ? launch_gate_fused_t<BF16, 2>(x, Wg, gate_bias, T, H, E, k, logits, topk_expert, topk_weight, route_counts, stream)
-                      : launch_gate_fused_t<F16, 2>(x, Wg, gate_bias, T, H, E, k, logits, topk_expert, topk_weight, route_counts, stream);
+    switch (dtype) {
+        case 0: return launch_gate_fused_s<F32>(x, Wg, gate_bias, T, H, E, k, logits, topk_expert, topk_weight, route_counts, stream);
+        case 1: return launch_gate_fused_s<BF16>(x, Wg, gate_bias, T, H, E, k, logits, topk_expert, topk_weight, route_counts, stream);
+        default: return launch_gate_fused_s<F16>(x, Wg, gate_bias, T, H, E, k, logits, topk_expert, topk_weight, route_counts, stream);
+    }
 }
 
 }  // namespace moe

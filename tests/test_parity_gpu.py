@@ -134,7 +134,7 @@ def test_single_launch_ffn_opt_in(oracle, monkeypatch):
         print("  ", parity.check_layer(oracle, w, cpu, b1, host1, tokens=tokens), flush=True)
 
 
-# ------------------------------------------------------------ shapes that take the fused gate kernel (16-bit)
+# ------------------------------------------------------------ shapes that take the fused gate kernel
 
 @pytest.mark.parametrize("T,H,E,k,dtype,bias", [
     (1000, 192, 24, 3, "bf16", True),                         # ragged last token tile, E far below the tile width
@@ -142,6 +142,11 @@ def test_single_launch_ffn_opt_in(oracle, monkeypatch):
     (777, 128, 136, 4, "bf16", True),                         # wide tile with a ragged expert tail
     (130, 256, 8, 8, "f16", True),                            # k = E
     (4096, 1024, 128, 2, "bf16", False),                      # full-width tile, deep K
+    (1000, 96, 12, 3, "f32", True),                           # fp32: narrowest tile (E <= 64), ragged everything
+    (2048, 1024, 16, 2, "f32", False),                        # fp32, the small benchmark configuration's gate
+    (500, 128, 64, 2, "f32", True),                           # fp32, E = 64 exactly
+    (300, 64, 200, 5, "f32", False),                          # fp32, widest tile with a ragged expert tail
+    (700, 2048, 128, 4, "f32", True),                         # fp32, deep K
 ])
 def test_fused_gate_shapes(oracle, T, H, E, k, dtype, bias):
     w = scaled(WORKLOADS["paper_bf16_e128"], name="gate", T=T, H=H, I=8, E=E, k=k, dtype=dtype, seed=31)
@@ -179,21 +184,22 @@ def test_fused_gate_feeds_the_routing_scan(oracle, case):
     assert torch.equal(b.out, b2.out)
 
 
-@pytest.mark.parametrize("E,k", [(16, 4), (128, 2), (200, 7)])
-def test_fused_gate_exact_ties(oracle, E, k):
+@pytest.mark.parametrize("E,k,dtype", [(16, 4, "bf16"), (128, 2, "bf16"), (200, 7, "bf16"), (40, 3, "f32"), (256, 6, "f32")])
+def test_fused_gate_exact_ties(oracle, E, k, dtype):
     # small-integer operands: every logit is an exact small integer, so whole groups of experts tie and the
     # logits themselves must match the oracle bit for bit
     rng = np.random.default_rng(E)
     T, H = 300, 128
-    x = torch.from_numpy(rng.integers(0, 2, size=(T, H)).astype(np.float32)).to(torch.bfloat16)
-    Wg = torch.from_numpy(rng.integers(-1, 2, size=(H, E)).astype(np.float32)).to(torch.bfloat16)
+    td = torch.bfloat16 if dtype == "bf16" else torch.float32
+    x = torch.from_numpy(rng.integers(0, 2, size=(T, H)).astype(np.float32)).to(td)
+    Wg = torch.from_numpy(rng.integers(-1, 2, size=(H, E)).astype(np.float32)).to(td)
     Wg[:, 1] = Wg[:, 0]                                       # two experts tie on every token
-    cfg = moe.make_config(T, H, 8, E, k, 1.0, "relu", "bf16")
+    cfg = moe.make_config(T, H, 8, E, k, 1.0, "relu", dtype)
     b = moe.Buffers(cfg)
     moe.moe_gate(cfg, b.workspace, x.cuda(), Wg.cuda(), None, b.gate_logits, b.topk_expert, b.topk_weight)
     torch.cuda.synchronize()
     got = b.gate_logits.cpu().numpy()
-    ref = oracle.gate_logits(x, Wg, None, T, H, E, "bf16")
+    ref = oracle.gate_logits(x, Wg, None, T, H, E, dtype)
     np.testing.assert_array_equal(got, ref.astype(np.float32))
     te, tw = oracle.topk(got, k)
     np.testing.assert_array_equal(b.topk_expert.cpu().numpy(), te)
