@@ -41,6 +41,10 @@ def parse_args():
     ap.add_argument("--workload", default="paper_bf16_e128")
     ap.add_argument("--cpu-baseline-tokens", type=int, default=16384,
                     help="tokens in the oracle's timed sample (0 = skip the cpu_baseline leg)")
+    ap.add_argument("--tokens", type=int, default=0, help="override T of the workload (sweeps; not the headline run)")
+    ap.add_argument("--experts", type=int, default=0, help="override E of the workload")
+    ap.add_argument("--act", default="", help="override the activation (relu, gelu_tanh, gelu_erf, identity)")
+    ap.add_argument("--with-bias", action="store_true", help="give the experts bias vectors b1, b2")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch one plain 1 GiB device copy (reference for hardware counters)")
     return ap.parse_args()
@@ -68,6 +72,13 @@ def main():
     from paper_2506_04667_amd.inputs import WORKLOADS, make_inputs, scaled
 
     w = WORKLOADS[args.workload]
+    over = {}
+    if args.tokens > 0: over["T"] = args.tokens
+    if args.experts > 0: over["E"] = args.experts
+    if args.act: over["act"] = args.act
+    if args.with_bias: over["with_bias"] = True
+    if over:
+        w = scaled(w, name=w.name + "+" + ",".join("%s=%s" % kv for kv in sorted(over.items())), **over)
     moe.load()
     torch.cuda.set_device(0)
     t0 = time.time()

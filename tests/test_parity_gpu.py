@@ -104,7 +104,7 @@ def test_streaming_ffn_shapes(oracle, case):
     cpu, dev, b, host, rep = _run(oracle, w, gate_bias=gb)
     for e in empty:
         assert host["expert_demand"][e] == 0
-    assert b.C > 128                                          # the shape reaches the streaming kernel
+    assert b.C > 32                                           # the shape reaches the streaming kernel
     # the staged path (packed rows) and the fused call (rows gathered through the routing table) agree bit for bit
     dev2 = dict(dev)
     b2, host2 = parity.gpu_forward(w, dev2, staged=True)
