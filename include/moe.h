@@ -12,14 +12,18 @@
  * Conventions for every entry point
  *   - All tensor pointers are DEVICE pointers owned by the caller, row-major,
  *     contiguous, 16-byte aligned.  `cfg` is a HOST pointer.  The library
- *     allocates nothing, keeps no global state, and touches only the caller's
- *     buffers and workspace.
+ *     allocates nothing and touches only the caller's buffers and workspace;
+ *     between calls it keeps nothing but per-process facts (the device's CU
+ *     count, and that a kernel's LDS limit has been raised: the first launch
+ *     of each kernel sets that function attribute, so run one call before
+ *     capturing calls into a HIP graph).
  *   - All work is enqueued on `stream` (a hipStream_t passed as void*; NULL is
  *     the default stream).  No host synchronisation, no device-to-host copy:
  *     ragged per-expert sizes stay on the device.
- *   - Errors are return codes; nothing is thrown.  On any error nothing has been
- *     enqueued.  Inputs are assumed finite; NaN/Inf logits give unspecified
- *     routing.
+ *   - Errors are return codes; nothing is thrown.  Arguments are checked before
+ *     anything is enqueued; MOE_ERR_HIP (a launch failed) can leave earlier
+ *     stages of the call enqueued.  Inputs are assumed finite; NaN/Inf logits
+ *     give unspecified routing.
  *   - Identical inputs give bit-identical outputs, run to run (no floating-point
  *     atomics, token-order slot assignment).
  *   - Storage dtype `cfg->dtype` applies to x, Wg, W1, W2, b1, b2, xe, y and
@@ -139,7 +143,11 @@ moe_status moe_dispatch(const moe_config* cfg, void* workspace, size_t workspace
  * expert e and each row r < min(expert_demand[e], C):
  *   y[e,r,:] = phi(xe[e,r,:] W1[e] + b1[e]) W2[e] + b2[e].
  * Only ceil(rows/bM) row tiles per expert are computed; rows beyond are left
- * untouched.  The intermediate h[E,C_pad,I] lives in the workspace. */
+ * untouched.  The intermediate h[E,C_pad,I] lives in the workspace.
+ * With the environment variable MOE_FFN_FUSED=1 (read at each call) eligible
+ * 16-bit shapes run both tasks in one persistent launch, a t2 tile starting
+ * when the t1 tiles it reads are stored (Alg. 2's tile-level dependency);
+ * the results are identical, the two-launch default is faster on one GPU. */
 moe_status moe_expert_ffn(const moe_config* cfg, void* workspace, size_t workspace_bytes,
                           const void* xe, const int32_t* expert_demand,
                           const void* W1, const void* b1, const void* W2, const void* b2,
