@@ -308,8 +308,8 @@ __global__ __launch_bounds__(THREADS) void ffn_gemm_stream_kernel(StreamArgs a) 
     };
     auto issue_b = [&]() __attribute__((always_inline)) {                              // next K-tile of the weights
         const uint32_t d = lds_b_wave + b_issue_stage * B_STAGE;
-        copy_to_lds(b_base, b_off[0], d);
-        copy_to_lds(b_base, b_off[1], d + 1024);
+        copy_to_lds_stream(b_base, b_off[0], d);
+        copy_to_lds_stream(b_base, b_off[1], d + 1024);
         if (--b_left == 0) {
             b_left = nxt.nk;
             b_step = (size_t)BK * PHF(nxt, ldb) * 2;
