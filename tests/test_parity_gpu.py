@@ -313,6 +313,53 @@ def test_capacity_override_paper_layout_reading(oracle):
     assert b.C == 64 and rep["dropped"] >= 512
 
 
+def test_forward_replays_from_a_hip_graph(oracle):
+    # moe_forward allocates nothing, synchronises nothing and clears its scratch with kernels, so a caller may
+    # capture it; every replay (with eager work and synchronisation in between, and new inputs in the same
+    # buffers) must reproduce the eager result bit for bit
+    w = scaled(WORKLOADS["paper_bf16_e128"], name="graph", seed=41, T=1500, H=256, I=512, E=16, k=2,
+               capacity_factor=1.0, with_bias=True)
+    cpu = make_inputs(w)
+    dev = parity.to_device(cpu)
+    cfg = moe.config_of(w)
+    b = moe.Buffers(cfg)
+
+    def run():
+        moe.moe_forward(cfg, b.workspace, dev["x"], dev["Wg"], dev["gate_bias"], dev["W1"], dev["b1"], dev["W2"],
+                        dev["b2"], b.out, b.gate_logits, b.topk_expert, b.topk_weight, b.slot, b.expert_demand)
+
+    run()                                                     # first call outside capture: kernel attributes get set
+    torch.cuda.synchronize()
+    eager = b.out.clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            run()
+    torch.cuda.current_stream().wait_stream(side)
+    x0 = dev["x"].clone()
+    for rep in range(4):
+        if rep == 2:                                          # other inputs in the same buffer, then back
+            dev["x"].copy_(x0.flip(0))
+            run()
+            torch.cuda.synchronize()
+            eager_flipped = b.out.clone()
+        b.out.zero_()
+        b.workspace.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(b.out, eager_flipped if rep >= 2 else eager), rep
+        _ = (dev["W1"][0, :8, :8].float() @ dev["W1"][0, :8, :8].float().t()).sum().item()   # unrelated eager work
+    dev["x"].copy_(x0)
+    host = {"gate_logits": b.gate_logits.cpu().numpy(), "topk_expert": b.topk_expert.cpu().numpy(),
+            "topk_weight": b.topk_weight.cpu().numpy(), "slot": b.slot.cpu().numpy(),
+            "expert_demand": b.expert_demand.cpu().numpy()}
+    cpu_flipped = dict(cpu)
+    cpu_flipped["x"] = cpu["x"].flip(0).contiguous()
+    print("  ", parity.check_layer(oracle, w, cpu_flipped, b, host), flush=True)
+
+
 def test_error_codes_on_device_calls():
     cfg = moe.make_config(128, 64, 128, 4, 1, 2.0, "relu", "f32")
     b = moe.Buffers(cfg)
