@@ -45,6 +45,8 @@ def parse_args():
     ap.add_argument("--experts", type=int, default=0, help="override E of the workload")
     ap.add_argument("--act", default="", help="override the activation (relu, gelu_tanh, gelu_erf, identity)")
     ap.add_argument("--with-bias", action="store_true", help="give the experts bias vectors b1, b2")
+    ap.add_argument("--graph", action="store_true",
+                    help="replay the step from a captured HIP graph in the timed loop (the same kernels, one launch call)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch one plain 1 GiB device copy (reference for hardware counters)")
     return ap.parse_args()
@@ -100,12 +102,24 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    run_step = step
+    if args.graph:
+        step()                                                   # kernel attributes are set on first use, outside capture
+        torch.cuda.synchronize()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                step()
+        torch.cuda.current_stream().wait_stream(side)
+        run_step = graph.replay
     for _ in range(args.warmup):
-        step()
+        run_step()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        step()
+        run_step()
     torch.cuda.synchronize()
     ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
 
@@ -194,7 +208,7 @@ def main():
         "metric": "MoE fwd latency (ms) + expert-FFN TFLOPS & % MFMA peak, T=16K E=128 k=2",
         "value": round(ms_per_step, 4), "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
-        "dtype": w.dtype, "data": "synthetic",
+        "dtype": w.dtype, "data": "synthetic", "launch": "hip_graph_replay" if args.graph else "stream",
         "config": {"workload": w.name, "T": T, "H": H, "I": I, "E": E, "k": k,
                    "capacity_factor": w.capacity_factor, "act": w.act, "capacity": b.C},
         "tokens_per_s": round(T / (ms_per_step * 1e-3), 1),
