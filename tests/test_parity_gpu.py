@@ -172,6 +172,9 @@ def test_fused_gate_shapes(oracle, T, H, E, k, dtype, bias):
     dict(T=1000, H=256, I=256, E=24, k=3, capacity_factor=1.0, dtype="bf16", act="relu"),       # ragged last chunk of 64 tokens
     dict(T=700, H=128, I=264, E=136, k=4, capacity_factor=0.5, dtype="f16", act="gelu_tanh"),   # wide expert tile, many drops
     dict(T=63, H=64, I=64, E=8, k=8, capacity_factor=1.0, dtype="bf16", act="identity"),        # a single partial chunk, k = E
+    dict(T=5000, H=256, I=512, E=256, k=2, capacity_factor=1.5, dtype="bf16", act="gelu_erf",
+         with_bias=True),                                                                         # 256 experts, ~40 rows each: streaming FFN with one sparse row tile per expert
+    dict(T=2500, H=192, I=256, E=40, k=1, capacity_factor=1.0, dtype="f16", act="relu"),        # top-1, C = 63
 ])
 def test_fused_gate_feeds_the_routing_scan(oracle, case):
     # moe_forward: the fused gate kernel writes the per-chunk expert counts that the slot assignment starts from;
