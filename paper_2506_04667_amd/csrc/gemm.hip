@@ -264,12 +264,11 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_kernel(GemmArgs a) 
     __syncthreads();
     for (int t = 0; t < nk; ++t) {
         const int cur = t & 1;
-        compute(cur, 0, 2);
         if (t + 1 < nk) {
             store_lds(cur ^ 1);                          // K-tile t+1; that stage was last read before the previous barrier
-            if (t + 2 < nk) load_global((t + 2) * BK);
+            if (t + 2 < nk) load_global((t + 2) * BK);   // a whole K-tile of MFMAs to arrive
         }
-        compute(cur, 2, 4);
+        compute(cur, 0, 4);
         __syncthreads();
     }
 
