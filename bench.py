@@ -27,6 +27,8 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
+MEASURED_STREAM_GBS = 6100.0
+
 PEAK = {  # MI355X published peaks
     "hbm_gbs": 8000.0,
     "mfma_tflops": {"bf16": 2500.0, "f16": 2500.0, "f32": 157.3},
@@ -168,7 +170,9 @@ def main():
     roof_hbm = {"bound": "hbm", "achieved": round(ach_gbs, 1), "peak": PEAK["hbm_gbs"], "unit": "GB/s",
                 "frac": round(ach_gbs / PEAK["hbm_gbs"], 4), "traffic": traffic,
                 "kernel": kernel_name, "launch_ms": round(launch_ms, 4),
-                "algorithmic_bytes_per_launch": bytes_per_launch}
+                "algorithmic_bytes_per_launch": bytes_per_launch,
+                # context: the best streaming-read rate a plain copy kernel reaches on this chip (measured, GB/s)
+                "measured_stream_peak": MEASURED_STREAM_GBS, "frac_of_measured": round(ach_gbs / MEASURED_STREAM_GBS, 4)}
     roof_mfma = {"bound": "mfma", "achieved": round(ach_tf, 1), "peak": PEAK["mfma_tflops"][w.dtype],
                  "unit": "TFLOP/s", "frac": round(ach_tf / PEAK["mfma_tflops"][w.dtype], 4), "traffic": traffic,
                  "kernel": kernel_name, "launch_ms": round(launch_ms, 4),
