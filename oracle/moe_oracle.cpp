@@ -266,6 +266,29 @@ void oracle_slots(const int32_t* topk_expert, const float* topk_weight, int32_t 
     if (expert_demand) for (int e = 0; e < E; ++e) expert_demand[e] = cnt[e];
 }
 
+void oracle_slots_choice_major(const int32_t* topk_expert, const float* topk_weight, int32_t T,
+                               int32_t E, int32_t k, int32_t C, int32_t* slot,
+                               int32_t* expert_demand, int32_t* slot_token, float* slot_weight) {
+    std::vector<int32_t> cnt(E, 0);
+    if (slot_token) for (int64_t q = 0; q < (int64_t)E * C; ++q) slot_token[q] = -1;
+    if (slot_weight) for (int64_t q = 0; q < (int64_t)E * C; ++q) slot_weight[q] = 0.0f;
+    for (int j = 0; j < k; ++j) {                      // every token's j-th choice before any (j+1)-th choice
+        for (int i = 0; i < T; ++i) {
+            const int64_t p = (int64_t)i * k + j;
+            const int e = topk_expert[p];
+            const int s = cnt[e]++;
+            if (s < C) {
+                if (slot) slot[p] = s;
+                if (slot_token) slot_token[(int64_t)e * C + s] = i;
+                if (slot_weight) slot_weight[(int64_t)e * C + s] = topk_weight[p];
+            } else if (slot) {
+                slot[p] = -1;
+            }
+        }
+    }
+    if (expert_demand) for (int e = 0; e < E; ++e) expert_demand[e] = cnt[e];
+}
+
 void oracle_ffn_rows(const void* x, const void* W1, const void* b1, const void* W2,
                      const void* b2, const int32_t* pair_token, const int32_t* pair_expert,
                      int32_t n, int32_t H, int32_t I, int32_t act, int32_t dtype, double* y) {

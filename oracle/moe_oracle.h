@@ -98,6 +98,14 @@ void oracle_slots(const int32_t* topk_expert, const float* topk_weight,
                   int32_t* expert_demand /* [E], pre-capacity counts */,
                   int32_t* slot_token /* [E,C] */, float* slot_weight /* [E,C] */);
 
+/* O5 under the other drop priority the paper leaves open (it does not say who loses a slot when an
+ * expert overflows): choice rank first, then token order -- every token's first choice is served
+ * before any second choice.  Same outputs as oracle_slots; with k = 1 the two coincide. */
+void oracle_slots_choice_major(const int32_t* topk_expert, const float* topk_weight,
+                               int32_t T, int32_t E, int32_t k, int32_t C,
+                               int32_t* slot, int32_t* expert_demand,
+                               int32_t* slot_token, float* slot_weight);
+
 /* O6 for n given (token, expert) pairs: y[p,:] in double. */
 void oracle_ffn_rows(const void* x, const void* W1, const void* b1,
                      const void* W2, const void* b2,

@@ -78,6 +78,8 @@ class Oracle:
         L.oracle_topk.argtypes = [vp, i32, i32, i32, vp, vp]
         L.oracle_slots.restype = None
         L.oracle_slots.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, vp, vp]
+        L.oracle_slots_choice_major.restype = None
+        L.oracle_slots_choice_major.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, vp, vp]
         L.oracle_ffn_rows.restype = None
         L.oracle_ffn_rows.argtypes = [vp] * 7 + [i32] * 5 + [vp]
         L.oracle_ffn_combine.restype = None
@@ -132,15 +134,15 @@ class Oracle:
         self.lib.oracle_topk(_ptr(logits), T, E, k, _ptr(te), _ptr(tw))
         return te, tw
 
-    def slots(self, topk_expert, topk_weight, E, C):
+    def slots(self, topk_expert, topk_weight, E, C, choice_major=False):
         te, tw = _i32(topk_expert), _f32(topk_weight)
         T, k = te.shape
         slot = np.empty((T, k), dtype=np.int32)
         demand = np.empty((E,), dtype=np.int32)
         slot_token = np.empty((E, C), dtype=np.int32)
         slot_weight = np.empty((E, C), dtype=np.float32)
-        self.lib.oracle_slots(_ptr(te), _ptr(tw), T, E, k, C, _ptr(slot), _ptr(demand),
-                              _ptr(slot_token), _ptr(slot_weight))
+        fn = self.lib.oracle_slots_choice_major if choice_major else self.lib.oracle_slots
+        fn(_ptr(te), _ptr(tw), T, E, k, C, _ptr(slot), _ptr(demand), _ptr(slot_token), _ptr(slot_weight))
         return slot, demand, slot_token, slot_weight
 
     def ffn_rows(self, x, W1, b1, W2, b2, pair_token, pair_expert, H, I, act, dtype):

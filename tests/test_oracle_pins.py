@@ -210,6 +210,46 @@ def test_slots_brute_force_on_tiny_inputs(oracle):
                         assert slot[i, j] == c and slot_weight[e, c] == tw[i, j]
 
 
+def _brute_force_slots_choice_major(te, C):
+    """The same count with the pairs ordered by (choice rank, token)."""
+    T, k = te.shape
+    flat = [(i, j, int(te[i, j])) for j in range(k) for i in range(T)]
+    slot = np.full((T, k), -1, np.int32)
+    for n, (i, j, e) in enumerate(flat):
+        earlier = sum(1 for (_, _, e2) in flat[:n] if e2 == e)
+        if earlier < C:
+            slot[i, j] = earlier
+    return slot
+
+
+def test_choice_major_slots_brute_force_and_properties(oracle):
+    rng = np.random.default_rng(17)
+    for T, E in [(1, 1), (3, 2), (8, 4), (6, 3)]:
+        for k in range(1, E + 1):
+            logits = rng.integers(-3, 4, size=(T, E)).astype(np.float32)
+            te, tw = oracle.topk(logits, k)
+            for C in range(1, T * k + 2):
+                slot, demand, slot_token, slot_weight = oracle.slots(te, tw, E, C, choice_major=True)
+                np.testing.assert_array_equal(slot, _brute_force_slots_choice_major(te, C))
+                np.testing.assert_array_equal(demand, np.bincount(te.ravel(), minlength=E))
+                ref = oracle.slots(te, tw, E, C)
+                if k == 1:                                       # one choice per token: the two priorities coincide
+                    for a, b in zip((slot, demand, slot_token, slot_weight), ref):
+                        np.testing.assert_array_equal(a, b)
+                # a first choice loses only to earlier tokens' first choices, whatever the later ranks do
+                first = te[:, 0]
+                for i in range(T):
+                    earlier = int((first[:i] == first[i]).sum())
+                    assert slot[i, 0] == (earlier if earlier < C else -1)
+                for e in range(E):
+                    n_e = min(int(demand[e]), C)
+                    assert (slot_token[e, n_e:] == -1).all() and (slot_weight[e, n_e:] == 0).all()
+                    for c in range(n_e):
+                        i = slot_token[e, c]
+                        j = list(te[i]).index(e)
+                        assert slot[i, j] == c and slot_weight[e, c] == tw[i, j]
+
+
 def test_slot_invariants_at_moderate_size(oracle):
     rng = np.random.default_rng(8)
     T, E, k = 3000, 24, 3
