@@ -56,6 +56,12 @@ typedef enum {
     MOE_ACT_IDENTITY = 3
 } moe_act;
 
+/* Who keeps a slot when more than C pairs name an expert (the paper leaves it open): */
+typedef enum {
+    MOE_DROP_TOKEN_MAJOR = 0,         /* pairs ordered by token, then choice rank (the default) */
+    MOE_DROP_CHOICE_MAJOR = 1         /* every token's j-th choice before any (j+1)-th choice */
+} moe_drop_policy;
+
 #define MOE_MAX_EXPERTS 8192
 
 typedef struct {
@@ -68,6 +74,7 @@ typedef struct {
     int32_t capacity_override;        /* > 0: slots per expert given directly */
     int32_t dtype;                    /* moe_dtype */
     int32_t act;                      /* moe_act: phi_1 of the first FFN task */
+    int32_t drop_policy;              /* moe_drop_policy */
 } moe_config;
 
 const char* moe_status_string(moe_status s);
@@ -99,6 +106,7 @@ moe_status moe_workspace_bytes(const moe_config* cfg, size_t* bytes);
  *        topk_weight[T,k] fp32 softmax over the k selected logits (Eq. combine 1/2)
  *        slot[T,k]             slot of (token, choice) in its expert's buffer, -1 = dropped;
  *                              slots are handed out in token order, then choice order
+ *                              (or choice rank first: cfg->drop_policy)
  *        expert_demand[E]      pairs that named each expert, before the capacity cut
  * All outputs except gate_logits are required.  On this path the packed copy xe
  * is not materialised: the first FFN task reads its rows from x through the

@@ -23,7 +23,8 @@ EXPORTS = ["moe_status_string", "moe_row_tile", "moe_capacity", "moe_workspace_b
 class MoeConfig(ctypes.Structure):
     _fields_ = [("T", ctypes.c_int32), ("H", ctypes.c_int32), ("I", ctypes.c_int32),
                 ("E", ctypes.c_int32), ("k", ctypes.c_int32), ("capacity_factor", ctypes.c_float),
-                ("capacity_override", ctypes.c_int32), ("dtype", ctypes.c_int32), ("act", ctypes.c_int32)]
+                ("capacity_override", ctypes.c_int32), ("dtype", ctypes.c_int32), ("act", ctypes.c_int32),
+                ("drop_policy", ctypes.c_int32)]
 
 
 class MoeError(RuntimeError):
@@ -72,14 +73,18 @@ def load(path=None):
     return lib
 
 
-def make_config(T, H, I, E, k, capacity_factor, act, dtype, capacity_override=0):
-    return MoeConfig(T, H, I, E, k, float(capacity_factor), int(capacity_override), DTYPE[dtype], ACT[act])
+DROP_POLICY = {"token_major": 0, "choice_major": 1}
+
+
+def make_config(T, H, I, E, k, capacity_factor, act, dtype, capacity_override=0, drop_policy="token_major"):
+    return MoeConfig(T, H, I, E, k, float(capacity_factor), int(capacity_override), DTYPE[dtype], ACT[act],
+                     DROP_POLICY[drop_policy])
 
 
 def config_of(w):
     """moe_config of a workload description (anything with T, H, I, E, k, capacity_factor, act, dtype)."""
     return make_config(w.T, w.H, w.I, w.E, w.k, w.capacity_factor, w.act, w.dtype,
-                       getattr(w, "capacity_override", 0))
+                       getattr(w, "capacity_override", 0), getattr(w, "drop_policy", "token_major"))
 
 
 def _p(t):

@@ -33,6 +33,7 @@ moe_status check_config(const moe_config* c) {
     if (c->act < MOE_ACT_RELU || c->act > MOE_ACT_IDENTITY) return MOE_ERR_UNSUPPORTED;
     if (c->H % 8 != 0 || c->I % 8 != 0) return MOE_ERR_UNSUPPORTED;
     if (c->E > MOE_MAX_EXPERTS) return MOE_ERR_UNSUPPORTED;
+    if (c->drop_policy < MOE_DROP_TOKEN_MAJOR || c->drop_policy > MOE_DROP_CHOICE_MAJOR) return MOE_ERR_UNSUPPORTED;
     return MOE_OK;
 }
 
@@ -117,8 +118,10 @@ moe_status run_dispatch(const moe_config* c, const Plan& p, void* ws, const void
                         const int32_t* topk_expert, const float* topk_weight, int32_t* slot,
                         int32_t* expert_demand, int32_t* slot_token, float* slot_weight, void* xe,
                         bool counts_ready, bool build_units, hipStream_t s) {
-    hipError_t e = moe::launch_route(topk_expert, topk_weight, c->T, c->E, c->k, p.C,
-                                     (int32_t*)ws_at(ws, p.off_counts), counts_ready, slot, expert_demand,
+    // the fused gate counts per chunk of 64 tokens, which is a chunk of the pair order only under token-major priority
+    const bool choice_major = c->drop_policy == MOE_DROP_CHOICE_MAJOR;
+    hipError_t e = moe::launch_route(topk_expert, topk_weight, c->T, c->E, c->k, p.C, choice_major,
+                                     (int32_t*)ws_at(ws, p.off_counts), counts_ready && !choice_major, slot, expert_demand,
                                      slot_token, slot_weight,
                                      build_units ? (int32_t*)ws_at(ws, p.off_units) : nullptr, s);
     if (e != hipSuccess) return MOE_ERR_HIP;

@@ -25,17 +25,24 @@ namespace {
 
 constexpr int kChunkTokens = 64;                        // tokens per chunk = tokens per fused-gate workgroup
 
+// Position q in the order in which pairs claim slots -> index of the pair in the [T, k] tables.
+// Token-major: the tables' own order.  Choice-major: q = j * T + token.
+__device__ __forceinline__ long long pair_index(long long q, int T, int k, bool choice_major) {
+    return choice_major ? (q % T) * k + q / T : q;
+}
+
 // One workgroup per chunk: per-expert counts in an LDS histogram (integer atomics, so the result does not
 // depend on their order).
 __global__ __launch_bounds__(256) void route_count_kernel(const int32_t* __restrict__ topk_expert, long long P,
-                                                          int chunk_pairs, int E, int32_t* __restrict__ counts) {
+                                                          int chunk_pairs, int T, int k, bool choice_major, int E,
+                                                          int32_t* __restrict__ counts) {
     extern __shared__ int32_t hist[];                // [E]
     for (int e = threadIdx.x; e < E; e += 256) hist[e] = 0;
     __syncthreads();
     const long long p0 = (long long)blockIdx.x * chunk_pairs;
     const long long p1 = p0 + chunk_pairs < P ? p0 + chunk_pairs : P;
     for (long long p = p0 + threadIdx.x; p < p1; p += 256) {
-        const int e = topk_expert[p];
+        const int e = topk_expert[pair_index(p, T, k, choice_major)];
         if (e >= 0 && e < E) atomicAdd(&hist[e], 1);
     }
     __syncthreads();
@@ -75,8 +82,8 @@ __global__ __launch_bounds__(256) void route_scan_kernel(int32_t* __restrict__ c
 
 __global__ __launch_bounds__(64) void route_scatter_kernel(const int32_t* __restrict__ topk_expert,
                                                            const float* __restrict__ topk_weight, long long P,
-                                                           int chunk_pairs, int n_chunks, int E, int k, int C,
-                                                           const int32_t* __restrict__ base,
+                                                           int chunk_pairs, int n_chunks, int T, bool choice_major,
+                                                           int E, int k, int C, const int32_t* __restrict__ base,
                                                            int32_t* __restrict__ slot,
                                                            int32_t* __restrict__ slot_token,
                                                            float* __restrict__ slot_weight,
@@ -95,7 +102,8 @@ __global__ __launch_bounds__(64) void route_scatter_kernel(const int32_t* __rest
     const long long p_end = ((long long)c + 1) * chunk_pairs < P ? ((long long)c + 1) * chunk_pairs : P;
     for (long long p0 = (long long)c * chunk_pairs; p0 < p_end; p0 += kWave) {
         const long long p = p0 + lane;
-        int e = p < p_end ? topk_expert[p] : -1;
+        const long long m = p < p_end ? pair_index(p, T, k, choice_major) : 0;   // index in the [T, k] tables
+        int e = p < p_end ? topk_expert[m] : -1;
         const bool valid = (e >= 0 && e < E);
         if (!valid) e = 0;
         // lanes naming the same expert: intersect ballots over the bits of e
@@ -114,10 +122,10 @@ __global__ __launch_bounds__(64) void route_scatter_kernel(const int32_t* __rest
         __syncthreads();
         if (p < p_end) {
             const bool kept = valid && s < C;
-            slot[p] = kept ? s : -1;
+            slot[m] = kept ? s : -1;
             if (kept) {
-                slot_token[(size_t)e * C + s] = (int32_t)(p / k);
-                slot_weight[(size_t)e * C + s] = topk_weight[p];
+                slot_token[(size_t)e * C + s] = (int32_t)(m / k);
+                slot_weight[(size_t)e * C + s] = topk_weight[m];
             }
         }
     }
@@ -146,7 +154,7 @@ int route_chunk_tokens() { return kChunkTokens; }
 int route_chunks(int T) { return (T + kChunkTokens - 1) / kChunkTokens; }
 
 hipError_t launch_route(const int32_t* topk_expert, const float* topk_weight, int T, int E, int k, int C,
-                        int32_t* counts, bool counts_ready, int32_t* slot, int32_t* expert_demand,
+                        bool choice_major, int32_t* counts, bool counts_ready, int32_t* slot, int32_t* expert_demand,
                         int32_t* slot_token, float* slot_weight, int32_t* ffn_units, hipStream_t stream) {
     const long long P = (long long)T * k;
     const int n_chunks = route_chunks(T);
@@ -154,12 +162,12 @@ hipError_t launch_route(const int32_t* topk_expert, const float* topk_weight, in
     const long long EC = (long long)E * C;
     if (!counts_ready)
         hipLaunchKernelGGL(route_count_kernel, dim3(n_chunks), dim3(256), (size_t)E * sizeof(int32_t), stream,
-                           topk_expert, P, chunk_pairs, E, counts);
+                           topk_expert, P, chunk_pairs, T, k, choice_major, E, counts);
     hipLaunchKernelGGL(route_scan_kernel, dim3((E + 3) / 4), dim3(256), 0, stream, counts, n_chunks, E,
                        expert_demand, slot_token, slot_weight, EC);
     hipLaunchKernelGGL(route_scatter_kernel, dim3(n_chunks + (ffn_units ? 1 : 0)), dim3(64),
-                       (size_t)E * sizeof(int32_t), stream, topk_expert, topk_weight, P, chunk_pairs, n_chunks, E, k,
-                       C, counts, slot, slot_token, slot_weight, expert_demand, ffn_units);
+                       (size_t)E * sizeof(int32_t), stream, topk_expert, topk_weight, P, chunk_pairs, n_chunks, T,
+                       choice_major, E, k, C, counts, slot, slot_token, slot_weight, expert_demand, ffn_units);
     return hipGetLastError();
 }
 

@@ -75,8 +75,9 @@ hipError_t launch_topk(const float* logits, int T, int E, int k, int32_t* topk_e
 // for rows_cap = max_rows = C (see launch_ffn_units).
 int route_chunk_tokens();
 int route_chunks(int T);
+// choice_major: the pairs are taken in the order (choice rank, token) instead of (token, choice rank).
 hipError_t launch_route(const int32_t* topk_expert, const float* topk_weight, int T, int E, int k, int C,
-                        int32_t* counts, bool counts_ready, int32_t* slot, int32_t* expert_demand,
+                        bool choice_major, int32_t* counts, bool counts_ready, int32_t* slot, int32_t* expert_demand,
                         int32_t* slot_token, float* slot_weight, int32_t* ffn_units, hipStream_t stream);
 
 // xe[e][slot][:] = x[token][:] for every kept (token, choice).

@@ -72,11 +72,12 @@ def gpu_forward(w, dev_inputs, staged=False):
 
 def check_routing(oracle, w, host, C, slot_token=None, slot_weight=None):
     """(ii): the oracle's routing of the GPU's logits must equal the GPU's routing."""
+    choice_major = getattr(w, "drop_policy", "token_major") == "choice_major"
     te, tw = oracle.topk(host["gate_logits"], w.k)
     np.testing.assert_array_equal(host["topk_expert"], te, err_msg="topk_expert")
     np.testing.assert_allclose(host["topk_weight"], tw, rtol=1e-5, atol=1e-7, err_msg="topk_weight")
     # slots from the GPU's own (expert, weight) tables: bit-exact integer work
-    slot, demand, st, sw = oracle.slots(host["topk_expert"], host["topk_weight"], w.E, C)
+    slot, demand, st, sw = oracle.slots(host["topk_expert"], host["topk_weight"], w.E, C, choice_major=choice_major)
     np.testing.assert_array_equal(host["slot"], slot, err_msg="slot")
     np.testing.assert_array_equal(host["expert_demand"], demand, err_msg="expert_demand")
     if slot_token is not None:

@@ -267,21 +267,22 @@ def test_route_tie_heavy_logits(oracle):
         np.testing.assert_allclose(tw.cpu().numpy(), tw_ref, rtol=1e-5, atol=1e-7)
 
 
+@pytest.mark.parametrize("policy", ["token_major", "choice_major"])
 @pytest.mark.parametrize("T,E,k,C", [(1, 1, 1, 0), (5, 3, 3, 2), (1000, 6, 2, 1), (4099, 37, 3, 0), (777, 128, 2, 7),
                                      (3000, 2, 2, 1000), (70000, 16, 4, 0)])
-def test_dispatch_slots_bit_exact(oracle, T, E, k, C):
+def test_dispatch_slots_bit_exact(oracle, T, E, k, C, policy):
     rng = np.random.default_rng(T + E)
     # skewed choices: some experts overflow, some stay empty
     logits = (rng.standard_normal((T, E)) + np.linspace(0, 4, E)).astype(np.float32)
     if E > 4:
         logits[:, 1] = -50.0                                  # an expert nobody picks (k < E)
     te, tw = oracle.topk(logits, k)
-    cfg = moe.make_config(T, 8, 8, E, k, 1.0, "relu", "f32", capacity_override=C)
+    cfg = moe.make_config(T, 8, 8, E, k, 1.0, "relu", "f32", capacity_override=C, drop_policy=policy)
     b = moe.Buffers(cfg).alloc_staged()
     te_d, tw_d = torch.from_numpy(te).cuda(), torch.from_numpy(tw).cuda()
     moe.moe_dispatch(cfg, b.workspace, None, te_d, tw_d, b.slot, b.expert_demand, b.slot_token, b.slot_weight, None)
     torch.cuda.synchronize()
-    slot, demand, st, sw = oracle.slots(te, tw, E, b.C)
+    slot, demand, st, sw = oracle.slots(te, tw, E, b.C, choice_major=(policy == "choice_major"))
     np.testing.assert_array_equal(b.slot.cpu().numpy(), slot)
     np.testing.assert_array_equal(b.expert_demand.cpu().numpy(), demand)
     np.testing.assert_array_equal(b.slot_token.cpu().numpy(), st)
@@ -314,6 +315,37 @@ def test_capacity_override_paper_layout_reading(oracle):
                capacity_override=64)
     cpu, dev, b, host, rep = _run(oracle, w)
     assert b.C == 64 and rep["dropped"] >= 512
+
+
+class _ChoiceMajor:
+    """A workload description with the choice-major drop priority (everything else from a MoEWorkload)."""
+    drop_policy = "choice_major"
+
+    def __init__(self, w):
+        self.__dict__.update(w.__dict__)
+
+    def __repr__(self):
+        return "choice_major(%r)" % (self.__dict__,)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_choice_major_drop_priority_end_to_end(oracle, dtype):
+    # half the capacity the demand needs: many second choices lose their slots to later tokens' first choices
+    base = scaled(WORKLOADS["paper_bf16_e128"], name="choice_major", seed=43, T=2100, H=256, I=256, E=16, k=2,
+                  capacity_factor=0.6, dtype=dtype, act="gelu_tanh")
+    w = _ChoiceMajor(base)
+    cpu = make_inputs(base)
+    dev = parity.to_device(cpu)
+    b, host = parity.gpu_forward(w, dev)
+    rep = parity.check_layer(oracle, w, cpu, b, host)
+    print("  ", rep, flush=True)
+    assert rep["dropped"] > 0
+    b_tok, host_tok = parity.gpu_forward(base, dev)            # the default priority keeps a different set
+    assert (host_tok["slot"] != host["slot"]).any()
+    dropped_first = (host["slot"][:, 0] < 0).sum(), (host_tok["slot"][:, 0] < 0).sum()
+    assert dropped_first[0] <= dropped_first[1]                # first choices fare no worse when they go first
+    b2, host2 = parity.gpu_forward(w, dev, staged=True)
+    assert torch.equal(b.out, b2.out)
 
 
 def test_forward_replays_from_a_hip_graph(oracle):
