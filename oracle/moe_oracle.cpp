@@ -186,6 +186,12 @@ int32_t oracle_capacity(int32_t T, int32_t E, int32_t k, float cf, int32_t capac
     return c < 1.0 ? 1 : (int32_t)c;
 }
 
+int32_t oracle_capacity_layout(int32_t T, int32_t E, float cf) {
+    if (T <= 0 || E <= 0 || !(cf > 0.0f)) return -1;
+    const double c = std::ceil((double)cf * (double)T / (double)E);
+    return c < 1.0 ? 1 : (int32_t)c;
+}
+
 int32_t oracle_align_up(int32_t C, int32_t bM) { return ((C + bM - 1) / bM) * bM; }
 
 double oracle_symmetric_layout_bytes(int64_t S, int64_t E, int64_t H, int64_t bM,

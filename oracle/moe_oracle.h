@@ -32,8 +32,8 @@
  *   - normalisation is over all k selected experts, before any drop, so the
  *     kept weights of a token sum to <= 1;
  *   - capacity carries the factor k (cf = 1 is "just enough under perfectly
- *     balanced routing"); the layout section's C = S/E reading is reachable
- *     through capacity_override;
+ *     balanced routing"); the layout section's C = S/E reading (no factor k)
+ *     is oracle_capacity_layout, or any value through capacity_override;
  *   - aligning C up to the tile height pads the buffer only, never the drop
  *     threshold;
  *   - drop priority is token order; top-k ties go to the smaller expert index;
@@ -69,6 +69,12 @@ int oracle_get_threads(void);
 /* O4. Returns C, or -1 on invalid arguments. */
 int32_t oracle_capacity(int32_t T, int32_t E, int32_t k, float capacity_factor,
                         int32_t capacity_override);
+
+/* The other reading of the capacity, from the symmetric layout of Sec. 3.2
+ * (C E W = S', uniform case S' = S): max(1, ceil(cf * T / E)), independent of k.
+ * Returns C, or -1 on invalid arguments.  Feed it to the other functions as
+ * capacity_override. */
+int32_t oracle_capacity_layout(int32_t T, int32_t E, float capacity_factor);
 
 /* In-place padding (Sec. 3.2.1): smallest multiple of bM that is >= C. */
 int32_t oracle_align_up(int32_t C, int32_t bM);

@@ -62,6 +62,8 @@ class Oracle:
         L.oracle_get_threads.restype = ctypes.c_int
         L.oracle_capacity.restype = i32
         L.oracle_capacity.argtypes = [i32, i32, i32, f32, i32]
+        L.oracle_capacity_layout.restype = i32
+        L.oracle_capacity_layout.argtypes = [i32, i32, f32]
         L.oracle_align_up.restype = i32
         L.oracle_align_up.argtypes = [i32, i32]
         L.oracle_symmetric_layout_bytes.restype = f64
@@ -97,6 +99,9 @@ class Oracle:
     # -- scalar helpers --------------------------------------------------------------
     def capacity(self, T, E, k, cf, override=0):
         return self.lib.oracle_capacity(T, E, k, cf, override)
+
+    def capacity_layout(self, T, E, cf):
+        return self.lib.oracle_capacity_layout(T, E, cf)
 
     def align_up(self, C, bM):
         return self.lib.oracle_align_up(C, bM)

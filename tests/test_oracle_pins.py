@@ -71,6 +71,31 @@ def test_symmetric_layout_matches_paper_table(oracle):
     assert checked == 5
 
 
+def test_layout_reading_of_capacity(oracle):
+    """Sec. 3.2: C E W = S' with S' = S gives C = S / E, no factor k.  Pinned by the memory-overhead table (four
+    staging copies of E cells of align_up(C, 128) rows), by the k = 1 coincidence with the default reading, and by
+    closed forms."""
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "memory_overhead_table.txt"))
+            if l.strip() and not l.startswith("#")]
+    for model, S, E, H, st_gb, fits in rows:
+        S, E, H = int(S), int(E), int(H)
+        C = oracle.capacity_layout(S, E, 1.0)
+        if int(fits):
+            assert 4 * E * oracle.align_up(C, 128) * H * 4 / 2 ** 30 == pytest.approx(float(st_gb), abs=0.005), model
+    assert oracle.capacity_layout(16384, 128, 1.0) == 128          # half the default reading at k = 2
+    assert oracle.capacity_layout(16384, 128, 1.25) == 160
+    assert oracle.capacity_layout(10, 3, 1.0) == 4 and oracle.capacity_layout(1, 64, 0.5) == 1
+    assert oracle.capacity_layout(0, 4, 1.0) == -1 and oracle.capacity_layout(8, 4, 0.0) == -1
+    rng = np.random.default_rng(5)
+    for _ in range(200):
+        T, E = int(rng.integers(1, 5000)), int(rng.integers(1, 300))
+        cf = float(rng.choice([0.5, 1.0, 1.25, 2.0]))
+        assert oracle.capacity_layout(T, E, cf) == oracle.capacity(T, E, 1, cf)
+        assert oracle.capacity_layout(T, E, cf) == max(1, -((-int(cf * 4) * T) // (4 * E)))   # exact integer ceil
+        if E >= 2:
+            assert oracle.capacity(T, E, 2, cf / 2) == oracle.capacity_layout(T, E, cf)
+
+
 def test_layout_size_two_branch_formula(oracle):
     """Sec. 3.2.1: Size(L) = 4 Size(T) when S/E >= bM, else 4 (bM E / S) Size(T)."""
     for S, E, H in [(8192, 64, 2048), (4096, 8, 512), (4096, 128, 1024), (1024, 64, 256)]:
