@@ -47,6 +47,8 @@ def parse_args():
     ap.add_argument("--experts", type=int, default=0, help="override E of the workload")
     ap.add_argument("--act", default="", help="override the activation (relu, gelu_tanh, gelu_erf, identity)")
     ap.add_argument("--with-bias", action="store_true", help="give the experts bias vectors b1, b2")
+    ap.add_argument("--capacity-mode", default="", help="per_choice (C = ceil(cf k T / E), default) or layout (no factor k)")
+    ap.add_argument("--drop-policy", default="", help="token_major (default) or choice_major")
     ap.add_argument("--graph", action="store_true",
                     help="replay the step from a captured HIP graph in the timed loop (the same kernels, one launch call)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -81,6 +83,8 @@ def main():
     if args.experts > 0: over["E"] = args.experts
     if args.act: over["act"] = args.act
     if args.with_bias: over["with_bias"] = True
+    if args.capacity_mode: over["capacity_mode"] = args.capacity_mode
+    if args.drop_policy: over["drop_policy"] = args.drop_policy
     if over:
         w = scaled(w, name=w.name + "+" + ",".join("%s=%s" % kv for kv in sorted(over.items())), **over)
     moe.load()
@@ -214,7 +218,8 @@ def main():
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": w.dtype, "data": "synthetic", "launch": "hip_graph_replay" if args.graph else "stream",
         "config": {"workload": w.name, "T": T, "H": H, "I": I, "E": E, "k": k,
-                   "capacity_factor": w.capacity_factor, "act": w.act, "capacity": b.C},
+                   "capacity_factor": w.capacity_factor, "act": w.act, "capacity": b.C,
+                   "capacity_mode": w.capacity_mode, "drop_policy": w.drop_policy},
         "tokens_per_s": round(T / (ms_per_step * 1e-3), 1),
         "kept_rows": R, "dropped_pairs": dropped,
         "expert_demand": {"min": int(demand.min()), "median": int(demand.median()), "max": int(demand.max()),

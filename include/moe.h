@@ -62,6 +62,12 @@ typedef enum {
     MOE_DROP_CHOICE_MAJOR = 1         /* every token's j-th choice before any (j+1)-th choice */
 } moe_drop_policy;
 
+/* Which expert capacity capacity_factor scales (the paper's text admits both): */
+typedef enum {
+    MOE_CAPACITY_PER_CHOICE = 0,      /* ceil(cf k T / E): cf = 1 holds every pair under balanced routing (default) */
+    MOE_CAPACITY_LAYOUT = 1           /* ceil(cf T / E): the symmetric layout's C E W = S' (Sec. 3.2), no factor k */
+} moe_capacity_mode;
+
 #define MOE_MAX_EXPERTS 8192
 
 typedef struct {
@@ -75,6 +81,7 @@ typedef struct {
     int32_t dtype;                    /* moe_dtype */
     int32_t act;                      /* moe_act: phi_1 of the first FFN task */
     int32_t drop_policy;              /* moe_drop_policy */
+    int32_t capacity_mode;            /* moe_capacity_mode, used when capacity_override == 0 */
 } moe_config;
 
 const char* moe_status_string(moe_status s);
@@ -84,7 +91,8 @@ const char* moe_status_string(moe_status s);
 int32_t moe_row_tile(void);
 
 /* Expert capacity.  C = capacity_override if > 0, else
- * max(1, ceil(capacity_factor * k * T / E)): the drop threshold (slots per expert
+ * max(1, ceil(capacity_factor * k * T / E)), or without the factor k under
+ * MOE_CAPACITY_LAYOUT: the drop threshold (slots per expert
  * in T_phi, Sec. 3 notation).  C_pad = C aligned up to moe_row_tile(): the row
  * stride of the per-expert buffers xe, y.  Alignment pads the buffer only.
  * Pure host arithmetic.  Either output may be NULL. */

@@ -24,7 +24,7 @@ class MoeConfig(ctypes.Structure):
     _fields_ = [("T", ctypes.c_int32), ("H", ctypes.c_int32), ("I", ctypes.c_int32),
                 ("E", ctypes.c_int32), ("k", ctypes.c_int32), ("capacity_factor", ctypes.c_float),
                 ("capacity_override", ctypes.c_int32), ("dtype", ctypes.c_int32), ("act", ctypes.c_int32),
-                ("drop_policy", ctypes.c_int32)]
+                ("drop_policy", ctypes.c_int32), ("capacity_mode", ctypes.c_int32)]
 
 
 class MoeError(RuntimeError):
@@ -74,17 +74,20 @@ def load(path=None):
 
 
 DROP_POLICY = {"token_major": 0, "choice_major": 1}
+CAPACITY_MODE = {"per_choice": 0, "layout": 1}
 
 
-def make_config(T, H, I, E, k, capacity_factor, act, dtype, capacity_override=0, drop_policy="token_major"):
+def make_config(T, H, I, E, k, capacity_factor, act, dtype, capacity_override=0, drop_policy="token_major",
+                capacity_mode="per_choice"):
     return MoeConfig(T, H, I, E, k, float(capacity_factor), int(capacity_override), DTYPE[dtype], ACT[act],
-                     DROP_POLICY[drop_policy])
+                     DROP_POLICY[drop_policy], CAPACITY_MODE[capacity_mode])
 
 
 def config_of(w):
     """moe_config of a workload description (anything with T, H, I, E, k, capacity_factor, act, dtype)."""
     return make_config(w.T, w.H, w.I, w.E, w.k, w.capacity_factor, w.act, w.dtype,
-                       getattr(w, "capacity_override", 0), getattr(w, "drop_policy", "token_major"))
+                       getattr(w, "capacity_override", 0), getattr(w, "drop_policy", "token_major"),
+                       getattr(w, "capacity_mode", "per_choice"))
 
 
 def _p(t):

@@ -34,6 +34,7 @@ moe_status check_config(const moe_config* c) {
     if (c->H % 8 != 0 || c->I % 8 != 0) return MOE_ERR_UNSUPPORTED;
     if (c->E > MOE_MAX_EXPERTS) return MOE_ERR_UNSUPPORTED;
     if (c->drop_policy < MOE_DROP_TOKEN_MAJOR || c->drop_policy > MOE_DROP_CHOICE_MAJOR) return MOE_ERR_UNSUPPORTED;
+    if (c->capacity_mode < MOE_CAPACITY_PER_CHOICE || c->capacity_mode > MOE_CAPACITY_LAYOUT) return MOE_ERR_UNSUPPORTED;
     return MOE_OK;
 }
 
@@ -42,7 +43,8 @@ moe_status capacity_of(const moe_config* c, int* C, int* C_pad) {
     if (c->capacity_override > 0) {
         cap = c->capacity_override;
     } else {
-        const double v = std::ceil((double)c->capacity_factor * (double)c->k * (double)c->T / (double)c->E);
+        const double per_token = c->capacity_mode == MOE_CAPACITY_LAYOUT ? 1.0 : (double)c->k;
+        const double v = std::ceil((double)c->capacity_factor * per_token * (double)c->T / (double)c->E);
         if (v > 2.0e9) return MOE_ERR_INVALID_ARG;
         cap = v < 1.0 ? 1 : (long long)v;
     }

@@ -6,14 +6,17 @@
 
 namespace moe {
 
-constexpr int kUnitRows = 256;                          // row tile of the streaming FFN kernels
+// Row tiles of the streaming FFN kernels.  A launch uses one of them for all its units: the large one, unless
+// no group can have more rows than the small one (then half the matrix-core work per weight byte goes away).
+constexpr int kUnitRowsLarge = 256, kUnitRowsSmall = 128;
 
 // Scratch block `w` of ffn_units_ints() ints: w[0] = fault word (cleared), w[1] = number of live units,
-// w[2 + q] = g * nrow + row tile in group order, then one completion counter per possible unit (cleared).
+// w[2 + q] = g * nrow + row tile in group order (row tiles of `unit_rows` rows, nrow of them cover the
+// capacity), then one completion counter per possible unit (cleared).
 // Called by every thread of ONE workgroup of `nthreads` threads (a multiple of 64, at most 1024);
 // `wave_total` is an LDS array of 16 ints.
-__device__ __forceinline__ void build_ffn_units(const int32_t* __restrict__ rows_dev, int rows_cap, int groups, int nrow,
-                                                int32_t* __restrict__ w, int* wave_total, int nthreads) {
+__device__ __forceinline__ void build_ffn_units(const int32_t* __restrict__ rows_dev, int rows_cap, int groups, int unit_rows,
+                                                int nrow, int32_t* __restrict__ w, int* wave_total, int nthreads) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nwaves = nthreads >> 6;
     const int cap = groups * nrow;
     int32_t* units = w + 2;
@@ -25,7 +28,7 @@ __device__ __forceinline__ void build_ffn_units(const int32_t* __restrict__ rows
         int nt = 0;
         if (g < groups) {
             const int rows = min(rows_dev[g], rows_cap);
-            nt = rows > 0 ? (rows + kUnitRows - 1) / kUnitRows : 0;
+            nt = rows > 0 ? (rows + unit_rows - 1) / unit_rows : 0;
         }
         int incl = nt;                                  // inclusive scan inside the wavefront
 #pragma unroll

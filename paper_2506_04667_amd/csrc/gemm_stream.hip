@@ -60,9 +60,11 @@ typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
 constexpr int kXcds = 8;
-constexpr int BM = 256, BN = 256, BK = 32, THREADS = 512;
-constexpr int TM = 8, TN = 4, WN = 4;                   // 16x16 MFMA tiles per wavefront (128 x 64); wavefronts along N
-constexpr int A_STAGE = BM * 128;                       // 256 rows x 64 k (two K-tiles)
+constexpr int BN = 256, BK = 32, THREADS = 512;
+constexpr int TN = 4, WN = 4;                           // 16-column MFMA tiles per wavefront; wavefronts along N
+// Row tile: 128 G rows, G = 2 (the design above) or G = 1 (launches in which no expert has more than 128
+// rows: wavefronts hold 64 x 64, half the MFMAs and half the activation copies per weight byte).
+constexpr int A_STAGE = kUnitRowsLarge * 128;           // up to 256 rows x 64 k (two K-tiles)
 constexpr int A_STAGES = 2;
 constexpr int B_STAGE = BK * BN * 2;                    // 32 k x 256 columns
 constexpr int B_STAGES = 4;
@@ -71,7 +73,6 @@ constexpr int B_REGION = A_STAGES * A_STAGE;            // weights ring starts a
 constexpr int EPI_REGION = B_REGION + B_STAGES * B_STAGE;
 constexpr int EPI_BYTES_PER_WAVE = 32 * 128;            // 32 rows x 64 columns x 2 B
 constexpr int LDS_BYTES = EPI_REGION + 8 * EPI_BYTES_PER_WAVE;
-static_assert(BM == kUnitRows, "the unit list is cut in row tiles of this kernel");
 static_assert(LDS_BYTES <= 160 * 1024, "LDS budget of a gfx950 CU");
 
 // v_mfma_f32_16x16x32: a lane holds, of each operand, 8 consecutive k (k = 8 (lane / 16) ..) of row/column
@@ -93,7 +94,7 @@ template <> struct Mma16<F16> {
 // MFMA operands of one K-tile (32 wide), double-buffered in registers: the weights of the wavefront's four
 // column tiles (two transpose reads each), and the activations of four of its eight row tiles at a time.
 struct WFrags { u32x4 w[TN]; };
-struct XFrags { u32x4 x[4]; };
+struct XFrags { u32x4 x[4]; };                          // four row tiles of 16
 
 struct Task {                                           // wave-uniform description of one output tile
     int ph;                                             // 0: first GEMM of the kernel's work, 1: the dependent second one
@@ -126,9 +127,12 @@ constexpr int kSpinLimit = 1 << 21;                     // polls (about 100 ns a
 
 #define PHF(t, f) ((NPH == 2 && (t).ph) ? a.ph[1].f : a.ph[0].f)
 
-template <class S, int ACT0, int NPH>
+template <class S, int ACT0, int NPH, int G>
 __global__ __launch_bounds__(THREADS) void ffn_gemm_stream_kernel(StreamArgs a) {
     typedef uint16_t elem;
+    constexpr int BM = 128 * G, TM = 4 * G;             // rows of a tile; 16-row MFMA tiles per wavefront
+    constexpr int A_COPIES = 2 * G;                     // 1 KB copies per wavefront and activation stage
+    static_assert(BM == (G == 2 ? kUnitRowsLarge : kUnitRowsSmall), "the unit list is cut in row tiles of this kernel");
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
     const int ncol0 = (a.ph[0].N + BN - 1) / BN, ncol1 = NPH == 2 ? (a.ph[1].N + BN - 1) / BN : 0;
@@ -235,7 +239,7 @@ __global__ __launch_bounds__(THREADS) void ffn_gemm_stream_kernel(StreamArgs a) 
     const int wm = wave / WN, wn = wave % WN;
 
     // ---- addresses of this wavefront's 1 KB copies, per task: uniform base + per-lane byte offset ----
-    // activations: 4 copies of 8 rows x 128 B per K-tile pair; weights: 2 copies of 2 k-rows x 512 B per K-tile
+    // activations: 2 G copies of 8 rows x 128 B per K-tile pair; weights: 2 copies of 2 k-rows x 512 B per K-tile
     auto task_bases = [&](const Task& t, const unsigned char*& base_a, const unsigned char*& base_b) __attribute__((always_inline)) {
         base_a = uniform((const unsigned char*)((const elem*)PHF(t, A) + (PHF(t, a_row_index) ? (size_t)0 : (size_t)t.grp * PHF(t, a_group_stride))));
         base_b = uniform((const unsigned char*)((const elem*)PHF(t, B) + (size_t)t.grp * PHF(t, b_group_stride)));
@@ -244,8 +248,8 @@ __global__ __launch_bounds__(THREADS) void ffn_gemm_stream_kernel(StreamArgs a) 
         const int32_t* row_index = PHF(t, a_row_index);
         const int lda = PHF(t, lda), ldb = PHF(t, ldb), N = PHF(t, N);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int r = (wave * 4 + j) * 8 + (lane >> 3), p = lane & 7;
+        for (int j = 0; j < A_COPIES; ++j) {
+            const int r = (wave * A_COPIES + j) * 8 + (lane >> 3), p = lane & 7;
             const int c = p ^ ((r >> 1) & 7);
             int grow = min(t.row0 + r, t.rows - 1);
             if (row_index) grow = row_index[(size_t)t.grp * PHF(t, a_index_stride) + grow];
@@ -281,26 +285,26 @@ __global__ __launch_bounds__(THREADS) void ffn_gemm_stream_kernel(StreamArgs a) 
     } else {
         na_base = a_base; nb_base = b_base;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) na_off[j] = a_off[j];
+        for (int j = 0; j < A_COPIES; ++j) na_off[j] = a_off[j];
 #pragma unroll
         for (int j = 0; j < 2; ++j) nb_off[j] = b_off[j];
     }
     int a_left = cur.nk / 2, b_left = cur.nk;           // requests left before a cursor moves to the next task
     size_t b_step = (size_t)BK * PHF(cur, ldb) * 2;     // bytes between K-tiles of the weights the cursor is in
     const uint32_t lds_base = (uint32_t)(size_t)(__attribute__((address_space(3))) unsigned char*)smem;
-    const uint32_t lds_a_wave = lds_base + wave * 4096;
+    const uint32_t lds_a_wave = lds_base + wave * (A_COPIES * 1024);
     const uint32_t lds_b_wave = lds_base + B_REGION + wave * 2048;
 
     int a_issue_stage = 0, b_issue_stage = 0;
     auto issue_a = [&]() __attribute__((always_inline)) {                              // next pair of K-tiles of the activation rows
         const uint32_t d = lds_a_wave + a_issue_stage * A_STAGE;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) copy_to_lds(a_base, a_off[j], d + j * 1024);
+        for (int j = 0; j < A_COPIES; ++j) copy_to_lds(a_base, a_off[j], d + j * 1024);
         if (--a_left == 0) {
             a_left = nxt.nk / 2;
             a_base = na_base;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) a_off[j] = na_off[j];
+            for (int j = 0; j < A_COPIES; ++j) a_off[j] = na_off[j];
         } else {
             a_base += 128;
         }
@@ -449,10 +453,13 @@ __global__ __launch_bounds__(THREADS) void ffn_gemm_stream_kernel(StreamArgs a) 
     // vacated) and, after an odd u, the activation pair (u+3)/2 (into the stage the pair u/2 vacated: every
     // wavefront holds the rest of that pair in registers by then).  Copies of one wave complete in issue
     // order, which in steady state reads
-    //   ... B | A B | B | A B | B | A B ...      (A = 4 copies, B = 2 copies; one group per K-tile)
-    // so "tile u+1 has landed" is vmcnt(8) before an odd tile (only its weights are new: the newer copies
-    // are B A B) and vmcnt(4) before an even tile (its activation pair is new: the newer copies are B B).
-    // Other vector memory operations in flight only make these waits stricter.
+    //   ... B | A B | B | A B | B | A B ...      (A = 2 G copies, B = 2 copies; one group per K-tile)
+    // so "tile u+1 has landed" is vmcnt(2 G + 4) before an odd tile (only its weights are new: the newer
+    // copies are B A B) and vmcnt(4) before an even tile (its activation pair is new: the newer copies are
+    // B B).  Other vector memory operations in flight only make these waits stricter.
+    // With G = 1 a wavefront has four row tiles, so a K-tile is one group of 16 MFMAs: the wait and the
+    // requests come after its first four, and the twelve reads of tile u+1's operands between the others,
+    // with the activations double-buffered by tile (x0 even, x1 odd) instead of by half.
     // requests of the virtual steps -4 .. -1, in steady-state order: B0 A0 B1 B2 A1 B3
     issue_b();
     issue_a();
@@ -462,7 +469,7 @@ __global__ __launch_bounds__(THREADS) void ffn_gemm_stream_kernel(StreamArgs a) 
     issue_b();
     wait_copies_and_barrier<4>();                       // A0 and B0 (and more) have landed
     WFrags w0, w1;                                      // weights of the even / odd tile of a pair
-    XFrags x0, x1;                                      // activations of row tiles 0-3 / 4-7
+    XFrags x0, x1;                                      // activations of row tiles 0-3 / 4-7 (G = 1: of the even / odd tile)
 #pragma unroll
     for (int i = 0; i < 8; ++i) read_w(i, 0, w0);
 #pragma unroll
@@ -494,25 +501,38 @@ __global__ __launch_bounds__(THREADS) void ffn_gemm_stream_kernel(StreamArgs a) 
     // One pair of K-tiles (u even, u + 1).  STEADY: u <= U - 6, so every request below exists and the wait
     // counts above hold; otherwise nothing more is requested and the waits are for everything in flight.
     // LAST: u + 2 == U, nothing follows.
+    // G = 1: the twelve MFMAs of a K-tile after its first four (operands wf, xf), with the twelve reads of
+    // the next tile's operands (-> wn_f, xn_f) between them.
+    auto single_tail = [&](const WFrags& wf, const XFrags& xf, WFrags& wn_f, XFrags& xn_f, int sb_n, int sa_n, int h_n) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 4; i < 16; ++i) {
+            mma_one(i, 0, wf, xf);
+            if (i < 12) read_w(i - 4, sb_n, wn_f);
+            else read_x(i - 12, 0, sa_n, h_n, xn_f);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
     auto pair_of_tiles = [&](int u, auto steady_tag, auto last_tag) __attribute__((always_inline)) {
         constexpr bool STEADY = decltype(steady_tag)::value, LAST = decltype(last_tag)::value;
+        constexpr int LAST_G = G - 1;                   // the half of a K-tile whose first four MFMAs cover the wait
         const int sa = (u >> 1) & 1;
         // ---- even tile u ----
-        first_half(w0, sa, 0);
+        if (G == 2) first_half(w0, sa, 0);
         const int sb1 = (sb + 1) & (B_STAGES - 1);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) mma_one(i, 1, w0, x1);   // these cover the wait for tile u+1
+        for (int i = 0; i < 4; ++i) mma_one(i, LAST_G, w0, G == 2 ? x1 : x0);   // these cover the wait for tile u+1
         __builtin_amdgcn_sched_barrier(0);
-        wait_copies_and_barrier<STEADY ? 8 : 0>();
+        wait_copies_and_barrier<STEADY ? A_COPIES + 4 : 0>();
         if (STEADY) issue_b();
         __builtin_amdgcn_sched_barrier(0);
-        second_half_tail(w0, w1, sb1, sa, 1);
+        if (G == 2) second_half_tail(w0, w1, sb1, sa, 1);
+        else single_tail(w0, x0, w1, x1, sb1, sa, 1);
         // ---- odd tile u + 1 ----
-        first_half(w1, sa, 1);
+        if (G == 2) first_half(w1, sa, 1);
         sb = (sb1 + 1) & (B_STAGES - 1);
         if (!LAST) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) mma_one(i, 1, w1, x1);
+            for (int i = 0; i < 4; ++i) mma_one(i, LAST_G, w1, x1);
             __builtin_amdgcn_sched_barrier(0);
             wait_copies_and_barrier<STEADY ? 4 : 0>();
             if (STEADY) {
@@ -520,10 +540,11 @@ __global__ __launch_bounds__(THREADS) void ffn_gemm_stream_kernel(StreamArgs a) 
                 issue_b();
             }
             __builtin_amdgcn_sched_barrier(0);
-            second_half_tail(w1, w0, sb, sa ^ 1, 0);
+            if (G == 2) second_half_tail(w1, w0, sb, sa ^ 1, 0);
+            else single_tail(w1, x1, w0, x0, sb, sa ^ 1, 0);
         } else {
 #pragma unroll
-            for (int i = 0; i < 16; ++i) mma_one(i, 1, w1, x1);
+            for (int i = 0; i < 16; ++i) mma_one(i, LAST_G, w1, x1);
             __builtin_amdgcn_sched_barrier(0);
         }
         k_done += 2;
@@ -540,9 +561,9 @@ __global__ __launch_bounds__(THREADS) void ffn_gemm_stream_kernel(StreamArgs a) 
 }
 
 __global__ __launch_bounds__(1024) void ffn_units_kernel(const int32_t* __restrict__ rows_dev, int rows_cap, int groups,
-                                                         int nrow, int32_t* __restrict__ w) {
+                                                         int unit_rows, int nrow, int32_t* __restrict__ w) {
     __shared__ int wave_total[16];
-    build_ffn_units(rows_dev, rows_cap, groups, nrow, w, wave_total, 1024);
+    build_ffn_units(rows_dev, rows_cap, groups, unit_rows, nrow, w, wave_total, 1024);
 }
 
 StreamPhase to_phase(const GemmArgs& g) {
@@ -557,9 +578,10 @@ StreamPhase to_phase(const GemmArgs& g) {
 }
 
 // g2 == nullptr: one GEMM.  Otherwise g2's A is g1's C and both share rows/groups/units.
-template <class S, int ACT0, int NPH>
-hipError_t launch_stream_t(const GemmArgs& g1, const GemmArgs* g2, hipStream_t stream) {
-    auto kernel = ffn_gemm_stream_kernel<S, ACT0, NPH>;
+template <class S, int ACT0, int NPH, int G>
+hipError_t launch_stream_g(const GemmArgs& g1, const GemmArgs* g2, hipStream_t stream) {
+    constexpr int BM = 128 * G;
+    auto kernel = ffn_gemm_stream_kernel<S, ACT0, NPH, G>;
     static bool attr_set = false;                       // LDS above 64 KB must be requested once per kernel
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
@@ -591,6 +613,12 @@ hipError_t launch_stream_t(const GemmArgs& g1, const GemmArgs* g2, hipStream_t s
     return hipGetLastError();
 }
 
+template <class S, int ACT0, int NPH>
+hipError_t launch_stream_t(const GemmArgs& g1, const GemmArgs* g2, hipStream_t stream) {
+    return ffn_unit_rows(g1.max_rows) == kUnitRowsSmall ? launch_stream_g<S, ACT0, NPH, 1>(g1, g2, stream)
+                                                        : launch_stream_g<S, ACT0, NPH, 2>(g1, g2, stream);
+}
+
 template <class S, int NPH>
 hipError_t launch_stream_act(const GemmArgs& g1, const GemmArgs* g2, hipStream_t stream) {
     switch (g1.act) {
@@ -615,14 +643,18 @@ int device_cu_count() {
     return cus;
 }
 
+int ffn_unit_rows(int max_rows) { return max_rows <= kUnitRowsSmall ? kUnitRowsSmall : kUnitRowsLarge; }
+
 size_t ffn_units_ints(int groups, int max_rows) {
-    return 2 + 2 * (size_t)groups * (size_t)((max_rows + BM - 1) / BM);
+    const int unit_rows = ffn_unit_rows(max_rows);
+    return 2 + 2 * (size_t)groups * (size_t)((max_rows + unit_rows - 1) / unit_rows);
 }
 
 hipError_t launch_ffn_units(const int32_t* rows_dev, int rows_cap, int groups, int max_rows, int32_t* units,
                             hipStream_t stream) {
-    hipLaunchKernelGGL(ffn_units_kernel, dim3(1), dim3(1024), 0, stream, rows_dev, rows_cap, groups,
-                       (max_rows + BM - 1) / BM, units);
+    const int unit_rows = ffn_unit_rows(max_rows);
+    hipLaunchKernelGGL(ffn_units_kernel, dim3(1), dim3(1024), 0, stream, rows_dev, rows_cap, groups, unit_rows,
+                       (max_rows + unit_rows - 1) / unit_rows, units);
     return hipGetLastError();
 }
 

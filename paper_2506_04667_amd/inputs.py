@@ -37,6 +37,8 @@ class MoEWorkload:
     zipf_s: float = 0.0               # > 0: gate_bias[e] = -s * ln(rank_e), rank a seeded permutation
     with_bias: bool = False           # draw b1, b2 (all paper configs: False)
     capacity_override: int = 0
+    drop_policy: str = "token_major"  # or "choice_major": who keeps a slot on overflow
+    capacity_mode: str = "per_choice" # or "layout": capacity factor scales k T / E, or T / E
 
 
 WORKLOADS = {

@@ -96,7 +96,10 @@ def check_layer(oracle, w, cpu_inputs, buffers, host, tokens=None, check_logits=
                                         w.T, w.H, w.E, w.dtype)
         report["logits_err"] = assert_close(host["gate_logits"], ref_logits, tol, "gate_logits")
     C = buffers.C
-    assert C == oracle.capacity(w.T, w.E, w.k, w.capacity_factor, w.capacity_override)
+    if getattr(w, "capacity_mode", "per_choice") == "layout" and not w.capacity_override:
+        assert C == oracle.capacity_layout(w.T, w.E, w.capacity_factor)
+    else:
+        assert C == oracle.capacity(w.T, w.E, w.k, w.capacity_factor, w.capacity_override)
     check_routing(oracle, w, host, C)
     ref_out = oracle.ffn_combine(i["x"], i["W1"], i["b1"], i["W2"], i["b2"], host["topk_expert"],
                                  host["topk_weight"], host["slot"], w.T, w.H, w.I, w.E, w.act, w.dtype,

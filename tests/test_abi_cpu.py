@@ -53,6 +53,9 @@ def test_capacity_matches_oracle_and_alignment(lib, oracle):
     for (T, E, k, cf, ov) in [(10, 3, 1, 1.0, 0), (1, 64, 1, 0.5, 0), (16384, 128, 2, 1.0, 128), (1000, 7, 3, 1.37, 0)]:
         C, C_pad = moe.moe_capacity(moe.make_config(T, 64, 64, E, k, cf, "relu", "f32", ov))
         assert C == oracle.capacity(T, E, k, cf, ov) and C_pad % 128 == 0 and 0 <= C_pad - C < 128
+        # the layout reading drops the factor k; an override wins over either mode
+        C, C_pad = moe.moe_capacity(moe.make_config(T, 64, 64, E, k, cf, "relu", "f32", ov, capacity_mode="layout"))
+        assert C == (ov if ov else oracle.capacity_layout(T, E, cf)) and C_pad == oracle.align_up(C, 128)
 
 
 def test_workspace_covers_the_per_expert_buffers(lib):
@@ -69,7 +72,7 @@ def test_workspace_covers_the_per_expert_buffers(lib):
     (dict(T=0), -1), (dict(E=0), -1), (dict(k=0), -1), (dict(k=5, E=4), -1), (dict(H=-8), -1),
     (dict(capacity_factor=0.0), -1), (dict(capacity_factor=float("nan")), -1), (dict(capacity_override=-1), -1),
     (dict(H=60), -2), (dict(I=100), -2), (dict(E=9000, k=1), -2), (dict(dtype=3), -2), (dict(act=9), -2),
-    (dict(drop_policy=2), -2), (dict(drop_policy=-1), -2),
+    (dict(drop_policy=2), -2), (dict(drop_policy=-1), -2), (dict(capacity_mode=2), -2), (dict(capacity_mode=-1), -2),
 ])
 def test_invalid_configs_are_rejected(lib, kw, code):
     base = dict(T=128, H=64, I=128, E=4, k=1, capacity_factor=2.0, capacity_override=0, dtype=0, act=0)

@@ -92,6 +92,12 @@ def test_activations_bf16(oracle, act):
     # one live expert out of nine: a single unit feeds one XCD only
     dict(T=300, H=256, I=512, E=9, k=1, capacity_factor=9.0, dtype="bf16", with_bias=True, act="identity",
          empty=(0, 1, 2, 3, 4, 5, 7, 8)),
+    # capacities of at most 128 rows take the 128-row tile: ragged rows (C = 108), ragged last column tile
+    dict(T=700, H=256, I=320, E=13, k=2, capacity_factor=1.0, dtype="bf16", with_bias=True, act="gelu_erf"),
+    # ... with drops (C = 47), more units than XCDs, experts nobody picks
+    dict(T=520, H=192, I=256, E=20, k=3, capacity_factor=0.6, dtype="f16", with_bias=False, act="relu", empty=(3, 19)),
+    # ... exactly one full 128-row tile per expert
+    dict(T=1024, H=512, I=512, E=16, k=2, capacity_factor=1.0, dtype="f16", with_bias=True, act="gelu_tanh"),
 ])
 def test_streaming_ffn_shapes(oracle, case):
     case = dict(case)
@@ -118,6 +124,8 @@ def test_single_launch_ffn_opt_in(oracle, monkeypatch):
                     capacity_factor=1.5, dtype="f16", with_bias=True, act="gelu_erf"),
              scaled(WORKLOADS["paper_bf16_e128"], name="fused_ffn_few_units", seed=24, T=700, H=512, I=256, E=3, k=1,
                     capacity_factor=1.2, dtype="bf16", act="relu"),
+             scaled(WORKLOADS["paper_bf16_e128"], name="fused_ffn_small_tile", seed=25, T=1200, H=256, I=512, E=24, k=2,
+                    capacity_factor=1.0, dtype="bf16", with_bias=True, act="gelu_tanh"),       # C = 100: 128-row tiles
              WORKLOADS["paper_bf16_e128"]]
     for w in cases:
         print("case", w, flush=True)
@@ -221,9 +229,11 @@ def _sample_tokens(host, n, seed):
     return sorted(toks)
 
 
-@pytest.mark.parametrize("name", ["paper_bf16_e128", "skew_f16_e128", "paper_f32_e64"])
+@pytest.mark.parametrize("name", ["paper_bf16_e128", "skew_f16_e128", "paper_f32_e64", "paper_bf16_e128/layout"])
 def test_paper_scale_sampled(oracle, name):
-    w = WORKLOADS[name]
+    w = WORKLOADS[name.split("/")[0]]
+    if name.endswith("/layout"):                       # the layout reading of the capacity: C = 128, half the pairs dropped
+        w = scaled(w, capacity_mode="layout")
     print("case", w, flush=True)
     cpu = make_inputs(w)
     dev = parity.to_device(cpu)
@@ -317,15 +327,23 @@ def test_capacity_override_paper_layout_reading(oracle):
     assert b.C == 64 and rep["dropped"] >= 512
 
 
-class _ChoiceMajor:
-    """A workload description with the choice-major drop priority (everything else from a MoEWorkload)."""
-    drop_policy = "choice_major"
-
-    def __init__(self, w):
-        self.__dict__.update(w.__dict__)
-
-    def __repr__(self):
-        return "choice_major(%r)" % (self.__dict__,)
+@pytest.mark.parametrize("dtype,cf", [("bf16", 1.0), ("f32", 1.25)])
+def test_layout_capacity_mode_end_to_end(oracle, dtype, cf):
+    # the layout section's reading as a mode of the configuration: half the slots of the default at k = 2
+    base = scaled(WORKLOADS["paper_bf16_e128"], name="layout_capacity", seed=47, T=3000, H=256, I=512, E=24, k=2,
+                  capacity_factor=cf, dtype=dtype, act="gelu_erf")
+    w = scaled(base, capacity_mode="layout")
+    cpu = make_inputs(base)
+    dev = parity.to_device(cpu)
+    b, host = parity.gpu_forward(w, dev)
+    assert b.C == oracle.capacity_layout(3000, 24, cf) == (125 if cf == 1.0 else 157)
+    rep = parity.check_layer(oracle, w, cpu, b, host)
+    print("  ", rep, flush=True)
+    assert rep["dropped"] >= 6000 - 24 * b.C
+    # the same layer through capacity_override gives the same bits
+    ov = scaled(base, name="layout_capacity_override", capacity_override=b.C)
+    b_ov, host_ov = parity.gpu_forward(ov, dev)
+    assert np.array_equal(host_ov["slot"], host["slot"]) and torch.equal(b_ov.out, b.out)
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
@@ -333,7 +351,7 @@ def test_choice_major_drop_priority_end_to_end(oracle, dtype):
     # half the capacity the demand needs: many second choices lose their slots to later tokens' first choices
     base = scaled(WORKLOADS["paper_bf16_e128"], name="choice_major", seed=43, T=2100, H=256, I=256, E=16, k=2,
                   capacity_factor=0.6, dtype=dtype, act="gelu_tanh")
-    w = _ChoiceMajor(base)
+    w = scaled(base, drop_policy="choice_major")
     cpu = make_inputs(base)
     dev = parity.to_device(cpu)
     b, host = parity.gpu_forward(w, dev)
