@@ -47,6 +47,7 @@ def parse_args():
     ap.add_argument("--experts", type=int, default=0, help="override E of the workload")
     ap.add_argument("--act", default="", help="override the activation (relu, gelu_tanh, gelu_erf, identity)")
     ap.add_argument("--with-bias", action="store_true", help="give the experts bias vectors b1, b2")
+    ap.add_argument("--capacity-factor", type=float, default=0.0, help="override the capacity factor of the workload")
     ap.add_argument("--capacity-mode", default="", help="per_choice (C = ceil(cf k T / E), default) or layout (no factor k)")
     ap.add_argument("--drop-policy", default="", help="token_major (default) or choice_major")
     ap.add_argument("--graph", action="store_true",
@@ -83,6 +84,7 @@ def main():
     if args.experts > 0: over["E"] = args.experts
     if args.act: over["act"] = args.act
     if args.with_bias: over["with_bias"] = True
+    if args.capacity_factor > 0: over["capacity_factor"] = args.capacity_factor
     if args.capacity_mode: over["capacity_mode"] = args.capacity_mode
     if args.drop_policy: over["drop_policy"] = args.drop_policy
     if over:

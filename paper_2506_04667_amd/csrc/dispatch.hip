@@ -88,11 +88,11 @@ __global__ __launch_bounds__(64) void route_scatter_kernel(const int32_t* __rest
                                                            int32_t* __restrict__ slot_token,
                                                            float* __restrict__ slot_weight,
                                                            const int32_t* __restrict__ expert_demand,
-                                                           int32_t* __restrict__ ffn_units, int unit_rows) {
+                                                           int32_t* __restrict__ ffn_units) {
     extern __shared__ int32_t run[];                 // [E] slots handed out so far, per expert
-    __shared__ int wave_total[16];
+    __shared__ int wave_total[32];
     if ((int)blockIdx.x == n_chunks) {               // the extra workgroup: list of live FFN units
-        build_ffn_units(expert_demand, C, E, unit_rows, (C + unit_rows - 1) / unit_rows, ffn_units, wave_total, 64);
+        build_ffn_units(expert_demand, C, E, C, ffn_units, wave_total, 64);
         return;
     }
     const int c = blockIdx.x, lane = threadIdx.x;
@@ -167,7 +167,7 @@ hipError_t launch_route(const int32_t* topk_expert, const float* topk_weight, in
                        expert_demand, slot_token, slot_weight, EC);
     hipLaunchKernelGGL(route_scatter_kernel, dim3(n_chunks + (ffn_units ? 1 : 0)), dim3(64),
                        (size_t)E * sizeof(int32_t), stream, topk_expert, topk_weight, P, chunk_pairs, n_chunks, T,
-                       choice_major, E, k, C, counts, slot, slot_token, slot_weight, expert_demand, ffn_units, ffn_unit_rows(C));
+                       choice_major, E, k, C, counts, slot, slot_token, slot_weight, expert_demand, ffn_units);
     return hipGetLastError();
 }
 

@@ -1,4 +1,4 @@
-// Device-side construction of the list of live (group, row tile) units that the weight-streaming FFN
+// Device-side construction of the lists of live (group, row tile) units that the weight-streaming FFN
 // kernels walk, shared by the stand-alone launcher and by the routing scatter launch (which appends it as
 // one more workgroup so that the whole layer needs no separate launch for it).
 #pragma once
@@ -6,50 +6,85 @@
 
 namespace moe {
 
-// Row tiles of the streaming FFN kernels.  A launch uses one of them for all its units: the large one, unless
-// no group can have more rows than the small one (then half the matrix-core work per weight byte goes away).
+// Row tiles of the streaming FFN kernels.  A group's live rows are cut into large tiles; what remains beyond
+// its full large tiles becomes one more large tile if it exceeds the small tile, else one small tile (half the
+// matrix-core work and half the activation copies for the same weight bytes).  Each tile size has its own
+// list and its own launch.
 constexpr int kUnitRowsLarge = 256, kUnitRowsSmall = 128;
 
-// Scratch block `w` of ffn_units_ints() ints: w[0] = fault word (cleared), w[1] = number of live units,
-// w[2 + q] = g * nrow + row tile in group order (row tiles of `unit_rows` rows, nrow of them cover the
-// capacity), then one completion counter per possible unit (cleared).
+// Scratch block: two lists of the same format, the large tiles' first.
+//   list = { fault word (cleared), number of live units n, ids[cap] (n used), completion counters[cap] (cleared) }
+//   large: cap = groups * nrow_large, id = g * nrow_large + (row tile of 256), nrow_large = ceil(max_rows / 256);
+//          absent (0 ints) when max_rows <= 128
+//   small: cap = groups, id = g * nrow_small + (row tile of 128), nrow_small = ceil(max_rows / 128)
+// both in order of group.
+__host__ __device__ inline int ffn_units_nrow_large(int max_rows) {
+    return max_rows > kUnitRowsSmall ? (max_rows + kUnitRowsLarge - 1) / kUnitRowsLarge : 0;
+}
+__host__ __device__ inline int ffn_units_nrow_small(int max_rows) { return (max_rows + kUnitRowsSmall - 1) / kUnitRowsSmall; }
+__host__ __device__ inline long long ffn_units_small_offset(int groups, int max_rows) {      // in ints
+    const int nl = ffn_units_nrow_large(max_rows);
+    return nl ? 2 + 2ll * groups * nl : 0;
+}
+__host__ __device__ inline long long ffn_units_total_ints(int groups, int max_rows) {
+    return ffn_units_small_offset(groups, max_rows) + 2 + 2ll * groups;
+}
+
 // Called by every thread of ONE workgroup of `nthreads` threads (a multiple of 64, at most 1024);
-// `wave_total` is an LDS array of 16 ints.
-__device__ __forceinline__ void build_ffn_units(const int32_t* __restrict__ rows_dev, int rows_cap, int groups, int unit_rows,
-                                                int nrow, int32_t* __restrict__ w, int* wave_total, int nthreads) {
+// `wave_total` is an LDS array of 32 ints.
+__device__ __forceinline__ void build_ffn_units(const int32_t* __restrict__ rows_dev, int rows_cap, int groups, int max_rows,
+                                                int32_t* __restrict__ w, int* wave_total, int nthreads) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nwaves = nthreads >> 6;
-    const int cap = groups * nrow;
-    int32_t* units = w + 2;
-    int32_t* done = w + 2 + cap;
-    for (int i = tid; i < cap; i += nthreads) done[i] = 0;
-    int carry = 0;                                      // units of the groups before this pass
+    const int nrow_l = ffn_units_nrow_large(max_rows), nrow_s = ffn_units_nrow_small(max_rows);
+    int32_t* wl = w;                                    // large list (unused when nrow_l == 0)
+    int32_t* ws = w + ffn_units_small_offset(groups, max_rows);
+    const int cap_l = groups * nrow_l;
+    for (int i = tid; i < cap_l; i += nthreads) wl[2 + cap_l + i] = 0;
+    for (int i = tid; i < groups; i += nthreads) ws[2 + groups + i] = 0;
+    int carry_l = 0, carry_s = 0;                       // units of the groups before this pass
     for (int g0 = 0; g0 < groups; g0 += nthreads) {
         const int g = g0 + tid;
-        int nt = 0;
+        int nl = 0, ns = 0, full = 0;
         if (g < groups) {
-            const int rows = min(rows_dev[g], rows_cap);
-            nt = rows > 0 ? (rows + unit_rows - 1) / unit_rows : 0;
+            const int rows = min(min(rows_dev[g], rows_cap), max_rows);
+            if (rows > 0) {
+                if (nrow_l) {
+                    full = rows / kUnitRowsLarge;
+                    const int rem = rows - full * kUnitRowsLarge;
+                    nl = full + (rem > kUnitRowsSmall ? 1 : 0);
+                    ns = rem > 0 && rem <= kUnitRowsSmall ? 1 : 0;
+                } else {
+                    ns = 1;
+                }
+            }
         }
-        int incl = nt;                                  // inclusive scan inside the wavefront
+        int incl_l = nl, incl_s = ns;                   // inclusive scans inside the wavefront
 #pragma unroll
         for (int d = 1; d < 64; d <<= 1) {
-            const int up = __shfl_up(incl, d);
-            if (lane >= d) incl += up;
+            const int up_l = __shfl_up(incl_l, d), up_s = __shfl_up(incl_s, d);
+            if (lane >= d) { incl_l += up_l; incl_s += up_s; }
         }
-        if (lane == 63) wave_total[wave] = incl;
+        if (lane == 63) { wave_total[wave] = incl_l; wave_total[16 + wave] = incl_s; }
         __syncthreads();
-        int before = 0, total = 0;
+        int before_l = 0, total_l = 0, before_s = 0, total_s = 0;
         for (int wv = 0; wv < nwaves; ++wv) {
-            const int t = wave_total[wv];
-            before += wv < wave ? t : 0;
-            total += t;
+            const int tl = wave_total[wv], ts = wave_total[16 + wv];
+            before_l += wv < wave ? tl : 0;
+            total_l += tl;
+            before_s += wv < wave ? ts : 0;
+            total_s += ts;
         }
-        const int start = carry + before + incl - nt;
-        for (int rt = 0; rt < nt; ++rt) units[start + rt] = g * nrow + rt;
-        carry += total;
+        const int start_l = carry_l + before_l + incl_l - nl;
+        for (int rt = 0; rt < nl; ++rt) wl[2 + start_l + rt] = g * nrow_l + rt;
+        if (ns) ws[2 + carry_s + before_s + incl_s - 1] = g * nrow_s + 2 * full;
+        carry_l += total_l;
+        carry_s += total_s;
         __syncthreads();
     }
-    if (tid == 0) { w[0] = 0; w[1] = carry; }
+    if (tid == 0) {
+        if (nrow_l) { wl[0] = 0; wl[1] = carry_l; }
+        ws[0] = 0; ws[1] = carry_s;
+    }
 }
 
 }  // namespace moe

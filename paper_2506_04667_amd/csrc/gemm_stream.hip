@@ -62,8 +62,10 @@ typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 constexpr int kXcds = 8;
 constexpr int BN = 256, BK = 32, THREADS = 512;
 constexpr int TN = 4, WN = 4;                           // 16-column MFMA tiles per wavefront; wavefronts along N
-// Row tile: 128 G rows, G = 2 (the design above) or G = 1 (launches in which no expert has more than 128
-// rows: wavefronts hold 64 x 64, half the MFMAs and half the activation copies per weight byte).
+// Row tile: 128 G rows, G = 2 (the design above) or G = 1 (wavefronts hold 64 x 64: half the MFMAs and half
+// the activation copies per weight byte).  An expert's rows are cut into 256-row tiles; a remainder of at
+// most 128 rows becomes a 128-row tile.  Each size has its own unit list and its own launch, so experts with
+// few rows (skewed routing, small capacities) do not pay for a half-empty large tile.
 constexpr int A_STAGE = kUnitRowsLarge * 128;           // up to 256 rows x 64 k (two K-tiles)
 constexpr int A_STAGES = 2;
 constexpr int B_STAGE = BK * BN * 2;                    // 32 k x 256 columns
@@ -156,8 +158,9 @@ __global__ __launch_bounds__(THREADS) void ffn_gemm_stream_kernel(StreamArgs a) 
     // producers finished rounds earlier and the waits normally do not spin at all.
     const int xcd = blockIdx.x % kXcds, wg_local = blockIdx.x / kXcds, wg_stride = gridDim.x / kXcds;
     const int n_units = uniform(a.units[0]);
-    // this XCD's units: every 8th one when an expert has at most one unit (nrow == 1), else a block of the list
-    const bool blocks = nrow > 1;
+    // this XCD's units: every 8th one when an expert has at most one unit in this list (always so for the
+    // small tiles), else a block of the list
+    const bool blocks = G == 2 && nrow > 1;
     const int unit0 = blocks ? (int)((long long)n_units * xcd / kXcds) : xcd;
     const int unit_step = blocks ? 1 : kXcds;
     const int ux = blocks ? (int)((long long)n_units * (xcd + 1) / kXcds) - unit0
@@ -561,9 +564,9 @@ __global__ __launch_bounds__(THREADS) void ffn_gemm_stream_kernel(StreamArgs a) 
 }
 
 __global__ __launch_bounds__(1024) void ffn_units_kernel(const int32_t* __restrict__ rows_dev, int rows_cap, int groups,
-                                                         int unit_rows, int nrow, int32_t* __restrict__ w) {
-    __shared__ int wave_total[16];
-    build_ffn_units(rows_dev, rows_cap, groups, unit_rows, nrow, w, wave_total, 1024);
+                                                         int max_rows, int32_t* __restrict__ w) {
+    __shared__ int wave_total[32];
+    build_ffn_units(rows_dev, rows_cap, groups, max_rows, w, wave_total, 1024);
 }
 
 StreamPhase to_phase(const GemmArgs& g) {
@@ -589,10 +592,12 @@ hipError_t launch_stream_g(const GemmArgs& g1, const GemmArgs* g2, hipStream_t s
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    const long long nrow = (g1.max_rows + BM - 1) / BM;
+    // units this list can hold: every row tile of every group (large), one per group (small)
+    const long long cap = G == 2 ? (long long)g1.groups * ffn_units_nrow_large(g1.max_rows) : (long long)g1.groups;
     const long long ncol = (g1.N + BN - 1) / BN + (g2 ? (g2->N + BN - 1) / BN : 0);
-    const long long total = (long long)g1.groups * nrow * ncol;          // upper bound of the live tasks
-    if ((long long)g1.groups * nrow > 0x7fffffffLL / (ncol > kXcds ? ncol : kXcds)) return hipErrorInvalidValue;
+    const long long total = cap * ncol;                                   // upper bound of the live tasks
+    if ((long long)g1.groups * ffn_units_nrow_small(g1.max_rows) > 0x7fffffffLL / (ncol > kXcds ? ncol : kXcds))
+        return hipErrorInvalidValue;
     // one persistent workgroup per CU, the same number on every XCD, never more workgroups than CUs
     long long grid = device_cu_count() / kXcds * kXcds;
     if (grid < kXcds) return hipErrorInvalidValue;
@@ -602,8 +607,8 @@ hipError_t launch_stream_g(const GemmArgs& g1, const GemmArgs* g2, hipStream_t s
     a.ph[0] = to_phase(g1);
     if (g2) a.ph[1] = to_phase(*g2);
     a.rows_dev = g1.rows_dev; a.rows_cap = g1.rows_cap; a.max_rows = g1.max_rows;
-    int32_t* w = const_cast<int32_t*>(g1.units);
-    a.fault = w; a.units = w + 1; a.done = w + 2 + (long long)g1.groups * nrow;
+    int32_t* w = const_cast<int32_t*>(g1.units) + (G == 2 ? 0 : ffn_units_small_offset(g1.groups, g1.max_rows));
+    a.fault = w; a.units = w + 1; a.done = w + 2 + cap;
     // a unit's second-GEMM tasks come `lag` units after its first-GEMM tasks: about four rounds of the XCD's
     // workgroups, so that the tiles they wait for were stored rounds ago
     const long long wg_per_xcd = grid / kXcds;
@@ -615,8 +620,12 @@ hipError_t launch_stream_g(const GemmArgs& g1, const GemmArgs* g2, hipStream_t s
 
 template <class S, int ACT0, int NPH>
 hipError_t launch_stream_t(const GemmArgs& g1, const GemmArgs* g2, hipStream_t stream) {
-    return ffn_unit_rows(g1.max_rows) == kUnitRowsSmall ? launch_stream_g<S, ACT0, NPH, 1>(g1, g2, stream)
-                                                        : launch_stream_g<S, ACT0, NPH, 2>(g1, g2, stream);
+    // the large row tiles, then the small ones (each launch exits at once if its list is empty)
+    if (ffn_units_nrow_large(g1.max_rows) > 0) {
+        hipError_t e = launch_stream_g<S, ACT0, NPH, 2>(g1, g2, stream);
+        if (e != hipSuccess) return e;
+    }
+    return launch_stream_g<S, ACT0, NPH, 1>(g1, g2, stream);
 }
 
 template <class S, int NPH>
@@ -643,18 +652,11 @@ int device_cu_count() {
     return cus;
 }
 
-int ffn_unit_rows(int max_rows) { return max_rows <= kUnitRowsSmall ? kUnitRowsSmall : kUnitRowsLarge; }
-
-size_t ffn_units_ints(int groups, int max_rows) {
-    const int unit_rows = ffn_unit_rows(max_rows);
-    return 2 + 2 * (size_t)groups * (size_t)((max_rows + unit_rows - 1) / unit_rows);
-}
+size_t ffn_units_ints(int groups, int max_rows) { return (size_t)ffn_units_total_ints(groups, max_rows); }
 
 hipError_t launch_ffn_units(const int32_t* rows_dev, int rows_cap, int groups, int max_rows, int32_t* units,
                             hipStream_t stream) {
-    const int unit_rows = ffn_unit_rows(max_rows);
-    hipLaunchKernelGGL(ffn_units_kernel, dim3(1), dim3(1024), 0, stream, rows_dev, rows_cap, groups, unit_rows,
-                       (max_rows + unit_rows - 1) / unit_rows, units);
+    hipLaunchKernelGGL(ffn_units_kernel, dim3(1), dim3(1024), 0, stream, rows_dev, rows_cap, groups, max_rows, units);
     return hipGetLastError();
 }
 

@@ -42,10 +42,9 @@ int device_cu_count();
 bool stream_gemm_eligible(const GemmArgs& a);
 hipError_t launch_grouped_gemm_stream(const GemmArgs& a, hipStream_t stream);
 // Scratch block of the streaming kernels, written by launch_ffn_units for the same rows_dev / rows_cap / groups /
-// max_rows: a fault word, the number of live (group, row tile) units, their list in order of group, and one
-// completion counter per unit.  ffn_units_ints() ints; GemmArgs::units points at the block.  The row tile is
-// ffn_unit_rows(max_rows): 128 rows when no group can have more, else 256.
-int ffn_unit_rows(int max_rows);
+// max_rows: for each of the two row-tile sizes (256 and 128 rows) a fault word, the number of live (group, row
+// tile) units, their list in order of group, and one completion counter per unit.  ffn_units_ints() ints;
+// GemmArgs::units points at the block.
 size_t ffn_units_ints(int groups, int max_rows);
 hipError_t launch_ffn_units(const int32_t* rows_dev, int rows_cap, int groups, int max_rows, int32_t* units,
                             hipStream_t stream);
