@@ -119,19 +119,33 @@ struct StreamPhase {
 struct StreamArgs {
     StreamPhase ph[2];
     const int32_t* rows_dev; int rows_cap; int max_rows;
-    const int32_t* units;                               // [0] = live units, [1 + q] = group * nrow + row tile
-    int32_t* done;                                      // [q] wavefronts that have stored a ph[0] tile of unit q; zero at launch
-    int32_t* fault;                                     // set to 1 if a dependency wait gave up
-    int lag;                                            // units between a unit's ph[0] and ph[1] tasks in an XCD's sequence
+    int32_t* lists;                                     // the scratch block with the two unit lists (see build_ffn_units)
+    int groups;
 };
 
 constexpr int kSpinLimit = 1 << 21;                     // polls (about 100 ns apart) before a dependency wait gives up
 
 #define PHF(t, f) ((NPH == 2 && (t).ph) ? a.ph[1].f : a.ph[0].f)
 
+// The units of a list that XCD `xcd` works on: unit0, unit0 + unit_step, ... (ux of them).  Every 8th unit
+// when an expert has at most one unit in the list (always so for the small tiles), else a contiguous block.
+template <int G>
+__device__ __forceinline__ void xcd_share(int n_units, int nrow, int xcd, int& unit0, int& unit_step, int& ux) {
+    const bool blocks = G == 2 && nrow > 1;
+    unit0 = blocks ? (int)((long long)n_units * xcd / kXcds) : xcd;
+    unit_step = blocks ? 1 : kXcds;
+    ux = blocks ? (int)((long long)n_units * (xcd + 1) / kXcds) - unit0
+                : (n_units > xcd ? (n_units - xcd + kXcds - 1) / kXcds : 0);
+}
+
+// The work of one workgroup on one list: `list` = { fault word, number of live units, ids[cap], completion
+// counters[cap] }; the workgroup is number wg_local of the wg_stride workgroups of XCD `xcd` that walk this list.
 template <class S, int ACT0, int NPH, int G>
-__global__ __launch_bounds__(THREADS) void ffn_gemm_stream_kernel(StreamArgs a) {
+__device__ __forceinline__ void stream_body(const StreamArgs& a, int32_t* list, int cap, int xcd, int wg_local, int wg_stride) {
     typedef uint16_t elem;
+    int32_t* const fault = list;
+    const int32_t* const units = list + 1;              // [0] = live units, [1 + q] = group * nrow + row tile
+    int32_t* const done = list + 2 + cap;               // [q] wavefronts that have stored a ph[0] tile of unit q; zero at launch
     constexpr int BM = 128 * G, TM = 4 * G;             // rows of a tile; 16-row MFMA tiles per wavefront
     constexpr int A_COPIES = 2 * G;                     // 1 KB copies per wavefront and activation stage
     static_assert(BM == (G == 2 ? kUnitRowsLarge : kUnitRowsSmall), "the unit list is cut in row tiles of this kernel");
@@ -156,18 +170,14 @@ __global__ __launch_bounds__(THREADS) void ffn_gemm_stream_kernel(StreamArgs a) 
     // earlier in the sequence, and each workgroup walks its share in order, so with all workgroups resident
     // (one per CU, never more workgroups than CUs) the waits cannot deadlock; `lag` is chosen so that the
     // producers finished rounds earlier and the waits normally do not spin at all.
-    const int xcd = blockIdx.x % kXcds, wg_local = blockIdx.x / kXcds, wg_stride = gridDim.x / kXcds;
-    const int n_units = uniform(a.units[0]);
-    // this XCD's units: every 8th one when an expert has at most one unit in this list (always so for the
-    // small tiles), else a block of the list
-    const bool blocks = G == 2 && nrow > 1;
-    const int unit0 = blocks ? (int)((long long)n_units * xcd / kXcds) : xcd;
-    const int unit_step = blocks ? 1 : kXcds;
-    const int ux = blocks ? (int)((long long)n_units * (xcd + 1) / kXcds) - unit0
-                          : (n_units > xcd ? (n_units - xcd + kXcds - 1) / kXcds : 0);
+    const int n_units = uniform(units[0]);
+    int unit0, unit_step, ux;
+    xcd_share<G>(n_units, nrow, xcd, unit0, unit_step, ux);
     const int xcd_tasks = ux * (ncol0 + ncol1);
     if (wg_local >= xcd_tasks) return;
-    const int lag = a.lag;
+    // a unit's second-GEMM tasks come `lag` units after its first-GEMM tasks: about four rounds of the
+    // workgroups, so that the tiles they wait for were stored rounds ago
+    const int lag = max((4 * wg_stride + ncol0 + ncol1 - 1) / (ncol0 + ncol1), 1);
     const int head_units = min(lag, ux), mid_units = max(ux - lag, 0);
     const int head = head_units * ncol0, mid = mid_units * (ncol0 + ncol1);
     // position p of the XCD's sequence -> phase, unit index inside the XCD, column tile (arithmetic only)
@@ -191,7 +201,7 @@ __global__ __launch_bounds__(THREADS) void ffn_gemm_stream_kernel(StreamArgs a) 
         if (p < xcd_tasks) {
             int ph, ui, ct;
             decode(p, ph, ui, ct);
-            info_unit = a.units[1 + unit0 + ui * unit_step];
+            info_unit = units[1 + unit0 + ui * unit_step];
             info_rows = min(a.rows_dev[info_unit / nrow], a.rows_cap);
         }
     };
@@ -218,9 +228,9 @@ __global__ __launch_bounds__(THREADS) void ffn_gemm_stream_kernel(StreamArgs a) 
         if (NPH == 2 && t.ph == 1) {
             const int need = ncol0 * (THREADS / 64);
             int spins = 0;
-            while (__hip_atomic_load(a.done + t.unit, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < need) {
+            while (__hip_atomic_load(done + t.unit, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < need) {
                 if (++spins > kSpinLimit) {
-                    if (threadIdx.x == 0) __hip_atomic_store(a.fault, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    if (threadIdx.x == 0) __hip_atomic_store(fault, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     break;
                 }
                 __builtin_amdgcn_s_sleep(4);
@@ -373,6 +383,11 @@ __global__ __launch_bounds__(THREADS) void ffn_gemm_stream_kernel(StreamArgs a) 
     unsigned char* epi = smem + EPI_REGION + wave * EPI_BYTES_PER_WAVE;   // [32 rows][64 columns], 128 B pitch
     auto store_tile = [&](auto act_tag, auto ph_tag) __attribute__((always_inline)) {
         constexpr int ACT = decltype(act_tag)::value, PH = decltype(ph_tag)::value;
+        // the lane number as the epilogue sees it: opaque to the compiler, so that the address arithmetic below
+        // is done here and not kept in registers across the main loop
+        int lane_e = lane;
+        asm volatile("" : "+v"(lane_e));
+        const int r16 = lane_e & 15, kq = lane_e >> 4;
         const StreamPhase& P = a.ph[PH];
         const int N = P.N;
         const int col_w = cur.n0 + wn * (TN * 16);      // first column of this wavefront
@@ -412,7 +427,7 @@ __global__ __launch_bounds__(THREADS) void ffn_gemm_stream_kernel(StreamArgs a) 
             // writes of the next pass come after these reads
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                const int r_local = i * 8 + (lane >> 3), chunk = lane & 7;
+                const int r_local = i * 8 + (lane_e >> 3), chunk = lane_e & 7;
                 const u32x4 v = *(const u32x4*)(epi + r_local * 128 + ((chunk ^ ((r_local >> 1) & 7)) << 4));
                 const int row = cur.row0 + wm * (TM * 16) + pass * 32 + r_local, col = col_w + chunk * 8;
                 if (row < cur.rows && col < N) *(u32x4*)((elem*)P.C + c_base + (size_t)row * P.ldc + col) = v;
@@ -440,7 +455,7 @@ __global__ __launch_bounds__(THREADS) void ffn_gemm_stream_kernel(StreamArgs a) 
             if (NPH == 2) {
                 // this wavefront's part of the tile has reached the XCD's L2 before it is counted
                 asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-                if (lane == 0) __hip_atomic_fetch_add(a.done + cur.unit, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (lane == 0) __hip_atomic_fetch_add(done + cur.unit, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
         }
         cur = nxt;
@@ -563,6 +578,30 @@ __global__ __launch_bounds__(THREADS) void ffn_gemm_stream_kernel(StreamArgs a) 
     pair_of_tiles(u + 2, std::false_type{}, std::true_type{});       // u == U - 2
 }
 
+// One persistent workgroup per CU.  A workgroup first walks its share of the XCD's large-tile tasks, then its
+// share of the small-tile tasks; nothing separates the two parts but a workgroup barrier, so workgroups with
+// few or no large tiles start on the small ones at once.  The small-tile tasks are dealt starting with the
+// workgroup after the one that got the XCD's last large-tile task, which evens out the counts.
+template <class S, int ACT0, int NPH>
+__global__ __launch_bounds__(THREADS) void ffn_gemm_stream_kernel(StreamArgs a) {
+    const int xcd = blockIdx.x % kXcds, wg = blockIdx.x / kXcds, wgs = gridDim.x / kXcds;
+    const int nrow_l = ffn_units_nrow_large(a.max_rows), nrow_s = ffn_units_nrow_small(a.max_rows);
+    int32_t* const list_l = a.lists;
+    int32_t* const list_s = a.lists + ffn_units_small_offset(a.groups, a.max_rows);
+    const int n_l = nrow_l ? uniform(list_l[1]) : 0, n_s = uniform(list_s[1]);
+    int unit0, unit_step, ux_l, ux_s;
+    xcd_share<2>(n_l, nrow_l, xcd, unit0, unit_step, ux_l);
+    xcd_share<1>(n_s, nrow_s, xcd, unit0, unit_step, ux_s);
+    if (ux_l > 0) stream_body<S, ACT0, NPH, 2>(a, list_l, a.groups * nrow_l, xcd, wg, wgs);
+    if (ux_s > 0) {
+        if (ux_l > 0) __syncthreads();                  // every wavefront is done with the LDS stages of the first part
+        const int ncol = (a.ph[0].N + BN - 1) / BN + (NPH == 2 ? (a.ph[1].N + BN - 1) / BN : 0);
+        int wg_s = wg - (int)(((long long)ux_l * ncol) % wgs);
+        if (wg_s < 0) wg_s += wgs;
+        stream_body<S, ACT0, NPH, 1>(a, list_s, a.groups, xcd, wg_s, wgs);
+    }
+}
+
 __global__ __launch_bounds__(1024) void ffn_units_kernel(const int32_t* __restrict__ rows_dev, int rows_cap, int groups,
                                                          int max_rows, int32_t* __restrict__ w) {
     __shared__ int wave_total[32];
@@ -581,10 +620,9 @@ StreamPhase to_phase(const GemmArgs& g) {
 }
 
 // g2 == nullptr: one GEMM.  Otherwise g2's A is g1's C and both share rows/groups/units.
-template <class S, int ACT0, int NPH, int G>
-hipError_t launch_stream_g(const GemmArgs& g1, const GemmArgs* g2, hipStream_t stream) {
-    constexpr int BM = 128 * G;
-    auto kernel = ffn_gemm_stream_kernel<S, ACT0, NPH, G>;
+template <class S, int ACT0, int NPH>
+hipError_t launch_stream_t(const GemmArgs& g1, const GemmArgs* g2, hipStream_t stream) {
+    auto kernel = ffn_gemm_stream_kernel<S, ACT0, NPH>;
     static bool attr_set = false;                       // LDS above 64 KB must be requested once per kernel
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
@@ -592,8 +630,9 @@ hipError_t launch_stream_g(const GemmArgs& g1, const GemmArgs* g2, hipStream_t s
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    // units this list can hold: every row tile of every group (large), one per group (small)
-    const long long cap = G == 2 ? (long long)g1.groups * ffn_units_nrow_large(g1.max_rows) : (long long)g1.groups;
+    // units the lists can hold: every large row tile of every group, and one small tile per group
+    const int nrow_l = ffn_units_nrow_large(g1.max_rows);
+    const long long cap = (long long)g1.groups * (nrow_l + 1);
     const long long ncol = (g1.N + BN - 1) / BN + (g2 ? (g2->N + BN - 1) / BN : 0);
     const long long total = cap * ncol;                                   // upper bound of the live tasks
     if ((long long)g1.groups * ffn_units_nrow_small(g1.max_rows) > 0x7fffffffLL / (ncol > kXcds ? ncol : kXcds))
@@ -607,25 +646,10 @@ hipError_t launch_stream_g(const GemmArgs& g1, const GemmArgs* g2, hipStream_t s
     a.ph[0] = to_phase(g1);
     if (g2) a.ph[1] = to_phase(*g2);
     a.rows_dev = g1.rows_dev; a.rows_cap = g1.rows_cap; a.max_rows = g1.max_rows;
-    int32_t* w = const_cast<int32_t*>(g1.units) + (G == 2 ? 0 : ffn_units_small_offset(g1.groups, g1.max_rows));
-    a.fault = w; a.units = w + 1; a.done = w + 2 + cap;
-    // a unit's second-GEMM tasks come `lag` units after its first-GEMM tasks: about four rounds of the XCD's
-    // workgroups, so that the tiles they wait for were stored rounds ago
-    const long long wg_per_xcd = grid / kXcds;
-    a.lag = (int)((4 * wg_per_xcd + ncol - 1) / ncol);
-    if (a.lag < 1) a.lag = 1;
+    a.lists = const_cast<int32_t*>(g1.units);
+    a.groups = g1.groups;
     hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(THREADS), LDS_BYTES, stream, a);
     return hipGetLastError();
-}
-
-template <class S, int ACT0, int NPH>
-hipError_t launch_stream_t(const GemmArgs& g1, const GemmArgs* g2, hipStream_t stream) {
-    // the large row tiles, then the small ones (each launch exits at once if its list is empty)
-    if (ffn_units_nrow_large(g1.max_rows) > 0) {
-        hipError_t e = launch_stream_g<S, ACT0, NPH, 2>(g1, g2, stream);
-        if (e != hipSuccess) return e;
-    }
-    return launch_stream_g<S, ACT0, NPH, 1>(g1, g2, stream);
 }
 
 template <class S, int NPH>
