@@ -117,6 +117,17 @@ def test_streaming_ffn_shapes(oracle, case):
     assert torch.equal(b.out, b2.out)
 
 
+def test_many_experts_few_rows_each(oracle):
+    # 2048 experts of at most 40 rows: the unit lists are built in several passes of the builder's workgroup, every
+    # live unit is a 128-row tile, most experts get a handful of rows and some none; gate on the unfused path (E > 256)
+    w = scaled(WORKLOADS["paper_bf16_e128"], name="many_experts", seed=29, T=5000, H=192, I=256, E=2048, k=2,
+               capacity_factor=8.0, dtype="bf16", act="gelu_erf")
+    cpu, dev, b, host, rep = _run(oracle, w)
+    assert b.C == 40 and (host["expert_demand"] == 0).any() and rep["dropped"] == 0
+    b2, host2 = parity.gpu_forward(w, dev, staged=True)
+    assert torch.equal(b.out, b2.out)
+
+
 def test_single_launch_ffn_opt_in(oracle, monkeypatch):
     # both FFN GEMMs in one persistent launch with tile-level dependencies (opt-in): same arithmetic in the same
     # order as the two-launch path, so the outputs must agree bit for bit, and with the oracle within the bar
