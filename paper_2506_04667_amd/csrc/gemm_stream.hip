@@ -686,7 +686,7 @@ hipError_t launch_ffn_units(const int32_t* rows_dev, int rows_cap, int groups, i
 
 bool stream_gemm_eligible(const GemmArgs& a) {
     return a.dtype != 0 && !a.b_is_nk && !a.c_f32 && a.rows_dev != nullptr && a.units != nullptr && a.K % (2 * BK) == 0 &&
-           a.K >= 6 * BK && a.N % 8 == 0 && a.N >= 256 && a.max_rows > 32 && a.lda % 8 == 0 && a.ldb % 8 == 0 &&
+           a.K >= 6 * BK && a.N % 8 == 0 && a.N >= 256 && a.lda % 8 == 0 && a.ldb % 8 == 0 &&
            a.ldc % 8 == 0 &&
            // copies address an operand as a 64-bit base plus 32-bit byte offsets
            (long long)a.a_rows_total * a.lda * 2 < (1ll << 32) && (long long)a.K * a.ldb * 2 < (1ll << 32);
