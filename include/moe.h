@@ -13,10 +13,11 @@
  *   - All tensor pointers are DEVICE pointers owned by the caller, row-major,
  *     contiguous, 16-byte aligned.  `cfg` is a HOST pointer.  The library
  *     allocates nothing and touches only the caller's buffers and workspace;
- *     between calls it keeps nothing but per-process facts (the device's CU
- *     count, and that a kernel's LDS limit has been raised: the first launch
- *     of each kernel sets that function attribute, so run one call before
- *     capturing calls into a HIP graph).
+ *     between calls it keeps nothing but a few facts per device (its CU
+ *     count, and that a kernel's LDS limit has been raised there: the first
+ *     launch of each kernel on a device sets that function attribute, so run
+ *     one call before capturing calls into a HIP graph).  Calls act on the
+ *     current device, which must be the one that owns the buffers.
  *   - All work is enqueued on `stream` (a hipStream_t passed as void*; NULL is
  *     the default stream).  No host synchronisation, no device-to-host copy:
  *     ragged per-expert sizes stay on the device.

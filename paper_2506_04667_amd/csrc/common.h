@@ -126,4 +126,20 @@ __device__ __forceinline__ float apply_act(float v, int act) {
     }
 }
 
+// Host side: a kernel that uses more than 64 KB of dynamic LDS has that limit raised once per device
+// (`done` is the kernel's own table of devices already served).
+constexpr int kMaxDevices = 64;
+inline hipError_t raise_lds_limit(const void* kernel, int bytes, bool (&done)[kMaxDevices]) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    if (!done[dev]) {
+        e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+        if (e != hipSuccess) return e;
+        done[dev] = true;
+    }
+    return hipSuccess;
+}
+
 }  // namespace moe

@@ -312,13 +312,8 @@ hipError_t launch_gate_fused_t(const void* x, const void* Wg, const float* gate_
                                hipStream_t stream) {
     auto kernel = gate_fused_kernel<S, BN>;
     constexpr int lds_bytes = GateCfg<S, BN>::LDS_BYTES;
-    static bool attr_set = false;                       // LDS above 64 KB must be requested once per kernel
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static bool limit_raised[kMaxDevices] = {};
+    if (hipError_t e = raise_lds_limit(reinterpret_cast<const void*>(kernel), lds_bytes, limit_raised); e != hipSuccess) return e;
     hipLaunchKernelGGL(kernel, dim3((unsigned)((T + G_BM - 1) / G_BM)), dim3(G_THREADS), lds_bytes, stream,
                        (const unsigned char*)x, (const unsigned char*)Wg, gate_bias, T, H, E, k, logits, topk_expert,
                        topk_weight, route_counts);

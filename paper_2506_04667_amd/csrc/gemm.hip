@@ -303,13 +303,8 @@ hipError_t launch_cfg(const GemmArgs& a, hipStream_t stream) {
     using C = Cfg<S, NT, WM, WN, TM, TN>;
     auto kernel = grouped_gemm_kernel<S, NT, WM, WN, TM, TN>;
     constexpr int lds_bytes = 2 * C::STAGE_BYTES;
-    static bool attr_set = false;                        // LDS above 64 KB must be requested once per kernel
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static bool limit_raised[kMaxDevices] = {};
+    if (hipError_t e = raise_lds_limit(reinterpret_cast<const void*>(kernel), lds_bytes, limit_raised); e != hipSuccess) return e;
     const long long ncol = (a.N + C::BN - 1) / C::BN;
     const long long nrow = (a.max_rows + C::BM - 1) / C::BM;
     const long long groups = a.groups >= kXcds ? (long long)(a.groups + kXcds - 1) / kXcds * kXcds : a.groups;

@@ -623,13 +623,8 @@ StreamPhase to_phase(const GemmArgs& g) {
 template <class S, int ACT0, int NPH>
 hipError_t launch_stream_t(const GemmArgs& g1, const GemmArgs* g2, hipStream_t stream) {
     auto kernel = ffn_gemm_stream_kernel<S, ACT0, NPH>;
-    static bool attr_set = false;                       // LDS above 64 KB must be requested once per kernel
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static bool limit_raised[kMaxDevices] = {};
+    if (hipError_t e = raise_lds_limit(reinterpret_cast<const void*>(kernel), LDS_BYTES, limit_raised); e != hipSuccess) return e;
     // units the lists can hold: every large row tile of every group, and one small tile per group
     const int nrow_l = ffn_units_nrow_large(g1.max_rows);
     const long long cap = (long long)g1.groups * (nrow_l + 1);
@@ -665,15 +660,15 @@ hipError_t launch_stream_act(const GemmArgs& g1, const GemmArgs* g2, hipStream_t
 }  // namespace
 
 int device_cu_count() {
-    static int cus = 0;
-    if (cus == 0) {
-        int dev = 0, n = 0;
-        if (hipGetDevice(&dev) != hipSuccess ||
-            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
-            n = 256;
-        cus = n;
+    static int cus[kMaxDevices] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return 256;
+    if (cus[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+        cus[dev] = n;
     }
-    return cus;
+    return cus[dev];
 }
 
 size_t ffn_units_ints(int groups, int max_rows) { return (size_t)ffn_units_total_ints(groups, max_rows); }
