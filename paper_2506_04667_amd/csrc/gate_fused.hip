@@ -42,7 +42,7 @@ struct GateCfg {
     static constexpr int PITCH = BN * EL;                // bytes per k-row of the Wg tile
     static constexpr int B_STAGE = KT * PITCH;
     static constexpr int STAGE = G_A_STAGE + B_STAGE;    // 16, 24 or 40 KB
-    static constexpr int STAGES = B_STAGE > 16384 ? 4 : 6;
+    static constexpr int STAGES = 4;                     // measured: 4 stages beat 3, 5 and 6 (19.5 against 21.5-22.4 us at T = 16K, E = 128, bf16)
     static constexpr int LDS_BYTES = STAGES * STAGE;     // at most 160 KB
     static constexpr int B_COPIES = B_STAGE / 1024 / G_WAVES;  // 1 KB copies per wavefront per K-tile
     static constexpr int COPIES = 1 + B_COPIES;
