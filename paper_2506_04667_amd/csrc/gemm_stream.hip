@@ -12,7 +12,8 @@
 //     of the next task are in flight while the current one finishes and while its
 //     epilogue runs -- no drain between tasks;
 //   * tile 256 x 256 (8 wavefronts as 2 x 4, 128 rows x 64 columns each, MFMA
-//     16x16x32): an expert with <= 256 live rows reads its weights exactly once;
+//     16x16x32): an expert with <= 256 live rows reads its weights exactly once; a
+//     128 x 256 variant of the same loop takes remainders of at most 128 rows;
 //   * K-tile 32.  Weights (from HBM) go through a ring of 4 LDS stages of 16 KB
 //     (32 x 256), requested 3 K-tiles ahead; activations (re-read from L2 by the 8
 //     column tiles of an expert) go through 2 stages of 32 KB that hold two K-tiles
@@ -64,8 +65,9 @@ constexpr int BN = 256, BK = 32, THREADS = 512;
 constexpr int TN = 4, WN = 4;                           // 16-column MFMA tiles per wavefront; wavefronts along N
 // Row tile: 128 G rows, G = 2 (the design above) or G = 1 (wavefronts hold 64 x 64: half the MFMAs and half
 // the activation copies per weight byte).  An expert's rows are cut into 256-row tiles; a remainder of at
-// most 128 rows becomes a 128-row tile.  Each size has its own unit list and its own launch, so experts with
-// few rows (skewed routing, small capacities) do not pay for a half-empty large tile.
+// most 128 rows becomes a 128-row tile.  Each size has its own unit list; one launch walks both (see the
+// kernel), so experts with few rows (skewed routing, small capacities, few tokens) do not pay for a
+// half-empty large tile.
 constexpr int A_STAGE = kUnitRowsLarge * 128;           // up to 256 rows x 64 k (two K-tiles)
 constexpr int A_STAGES = 2;
 constexpr int B_STAGE = BK * BN * 2;                    // 32 k x 256 columns
