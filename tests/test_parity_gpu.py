@@ -130,6 +130,17 @@ def test_many_experts_few_rows_each(oracle):
     assert torch.equal(b.out, b2.out)
 
 
+def test_maximum_expert_count(oracle):
+    # E = 8192, the largest count the configuration check admits: most experts get no token at all
+    w = scaled(WORKLOADS["tiny_f32"], name="max_experts", seed=31, T=300, H=64, I=64, E=8192, k=3, capacity_factor=30.0,
+               dtype="f32", act="gelu_tanh")
+    cpu, dev, b, host, rep = _run(oracle, w)
+    assert b.C == 4 and (host["expert_demand"] == 0).sum() > 7000
+    # half as many experts on the weight-streaming FFN kernel (its weights are 400 M elements to draw)
+    w16 = scaled(w, name="many_experts_bf16", dtype="bf16", E=4096, H=192, I=256, T=200, seed=32)
+    _run(oracle, w16)
+
+
 def test_single_launch_ffn_opt_in(oracle, monkeypatch):
     # both FFN GEMMs in one persistent launch with tile-level dependencies (opt-in): same arithmetic in the same
     # order as the two-launch path, so the outputs must agree bit for bit, and with the oracle within the bar
