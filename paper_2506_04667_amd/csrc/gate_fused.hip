@@ -157,42 +157,76 @@ __global__ __launch_bounds__(G_THREADS) void gate_fused_kernel(const unsigned ch
 #pragma unroll
         for (int q = 0; q < 16; ++q) acc[j][q] = 0.0f;
 
-    // ---- main loop: tile u is waited for, tile u + D - 1 requested into the stage tile u - 1 vacated ----
-    for (int t = 0; t < D - 1 && t < nk; ++t) issue(t);
-    for (int u = 0; u < nk; ++u) {
-        // a wavefront's copies complete in issue order: with tiles u .. u+D-2 requested, "tile u has landed"
-        // leaves the COPIES * (D - 2) newest in flight; near the end everything outstanding is waited for
-        if (u + D - 2 < nk) wait_copies_and_barrier<C::COPIES * (D - 2)>();
-        else wait_copies_and_barrier<0>();
-        if (u + D - 1 < nk) issue(u + D - 1);
-        const unsigned char* st = smem + (u % D) * STAGE;
+    // ---- main loop ----
+    // The operands of a K-tile are read from LDS into registers one iteration ahead, so the reads' latency
+    // hides behind the MFMAs of the tile before.  All D stages are requested up front; in iteration u the
+    // wavefront waits for tile u + 1 (its operands are read next), meets the others (every wavefront then holds
+    // tile u in registers, so stage u % D is free), requests tile u + D into that stage, starts the reads of
+    // tile u + 1 and multiplies tile u.
+    struct Ops {                                        // one wavefront's operands of one K-tile (its two k-steps)
+        u32x4 x[2];
+        u32x4 w[2][TN];                                 // 16-bit: one MFMA operand; fp32: four k of column n
+    };
+    auto load_ops = [&](int t, Ops& o) __attribute__((always_inline)) {
+        const unsigned char* st = smem + (t % D) * STAGE;
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks) {
-            if constexpr (k16) {
-                const u32x4 xf = *(const u32x4*)(st + a_rd[ks]);
+            o.x[ks] = *(const u32x4*)(st + a_rd[ks]);
 #pragma unroll
-                for (int tn = 0; tn < TN; ++tn) {
+            for (int tn = 0; tn < TN; ++tn) {
+                if constexpr (k16) {
                     const unsigned char* pw = st + b_rd[tn] + ks * 16 * PITCH;
                     const u32x2 lo = __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)pw));
                     const u32x2 hi = __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(pw + 4 * PITCH)));
-                    const u32x4 wf = {lo[0], lo[1], hi[0], hi[1]};
-                    acc[tn] = GateMma<S>::run(__builtin_bit_cast(s16x8, wf), __builtin_bit_cast(s16x8, xf), acc[tn]);
+                    o.w[ks][tn] = u32x4{lo[0], lo[1], hi[0], hi[1]};
+                } else {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) o.w[ks][tn][j] = *(const uint32_t*)(st + b_rd[tn] + (ks * 8 + j) * PITCH);
                 }
-            } else {
-                const f32x4 xf = *(const f32x4*)(st + a_rd[ks]);
-                float wv[TN][4];
+            }
+        }
+    };
+    auto mma_ops = [&](const Ops& o) __attribute__((always_inline)) {
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            if constexpr (k16) {
 #pragma unroll
                 for (int tn = 0; tn < TN; ++tn)
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) wv[tn][j] = *(const float*)(st + b_rd[tn] + (ks * 8 + j) * PITCH);
+                    acc[tn] = GateMma<S>::run(__builtin_bit_cast(s16x8, o.w[ks][tn]), __builtin_bit_cast(s16x8, o.x[ks]), acc[tn]);
+            } else {
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
 #pragma unroll
-                    for (int tn = 0; tn < TN; ++tn)
-                        acc[tn] = __builtin_amdgcn_mfma_f32_32x32x2f32(wv[tn][j], xf[j], acc[tn], 0, 0, 0);
+                    for (int tn = 0; tn < TN; ++tn) {
+                        const uint32_t wb = o.w[ks][tn][j], xb = o.x[ks][j];   // copy out first: bit_cast of a vector element reads element 0
+                        acc[tn] = __builtin_amdgcn_mfma_f32_32x32x2f32(__builtin_bit_cast(float, wb), __builtin_bit_cast(float, xb), acc[tn], 0, 0, 0);
+                    }
             }
         }
+    };
+    // One iteration: `cur` holds tile u, `nxt` receives tile u + 1.
+    auto step = [&](int u, const Ops& cur, Ops& nxt) __attribute__((always_inline)) {
+        if (u + 1 < nk) {
+            // a wavefront's copies complete in issue order: with tiles up to u + D - 1 requested, "tile u + 1 has
+            // landed" leaves the COPIES * (D - 2) newest in flight; near the end everything outstanding is waited for
+            if (u + D - 1 < nk) wait_copies_and_barrier<C::COPIES * (D - 2)>();
+            else wait_copies_and_barrier<0>();
+            if (u + D < nk) issue(u + D);
+            load_ops(u + 1, nxt);
+        }
+        mma_ops(cur);
+    };
+    for (int t = 0; t < D && t < nk; ++t) issue(t);
+    if (D <= nk) wait_copies_and_barrier<C::COPIES * (D - 1)>();   // tile 0 has landed
+    else wait_copies_and_barrier<0>();
+    Ops o0, o1;
+    load_ops(0, o0);
+    int u = 0;
+    for (; u + 1 < nk; u += 2) {
+        step(u, o0, o1);
+        step(u + 1, o1, o0);
     }
+    if (u < nk) step(u, o0, o1);
     wait_copies_and_barrier<0>();                       // every wavefront is done with the ring: reuse it
 
     // ---- logits tile [64 tokens][LP] fp32 in LDS: group 1 parks its partial sums, group 0 adds its own and
