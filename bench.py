@@ -45,6 +45,9 @@ def parse_args():
                     help="tokens in the oracle's timed sample (0 = skip the cpu_baseline leg)")
     ap.add_argument("--tokens", type=int, default=0, help="override T of the workload (sweeps; not the headline run)")
     ap.add_argument("--experts", type=int, default=0, help="override E of the workload")
+    ap.add_argument("--hidden", type=int, default=0, help="override H of the workload")
+    ap.add_argument("--inter", type=int, default=0, help="override I of the workload")
+    ap.add_argument("--topk", type=int, default=0, help="override k of the workload")
     ap.add_argument("--act", default="", help="override the activation (relu, gelu_tanh, gelu_erf, identity)")
     ap.add_argument("--with-bias", action="store_true", help="give the experts bias vectors b1, b2")
     ap.add_argument("--capacity-factor", type=float, default=0.0, help="override the capacity factor of the workload")
@@ -82,6 +85,9 @@ def main():
     over = {}
     if args.tokens > 0: over["T"] = args.tokens
     if args.experts > 0: over["E"] = args.experts
+    if args.hidden > 0: over["H"] = args.hidden
+    if args.inter > 0: over["I"] = args.inter
+    if args.topk > 0: over["k"] = args.topk
     if args.act: over["act"] = args.act
     if args.with_bias: over["with_bias"] = True
     if args.capacity_factor > 0: over["capacity_factor"] = args.capacity_factor
