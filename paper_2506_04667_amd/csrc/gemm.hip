@@ -316,22 +316,32 @@ hipError_t launch_cfg(const GemmArgs& a, hipStream_t stream) {
 
 template <class S>
 hipError_t launch_t(const GemmArgs& a, hipStream_t stream) {
-    // Tile choice from the row bound alone (live row counts are only known on the device): rounds of tasks over
-    // the chip times the time of a round.  A CU runs one 256 x 256 task, or two 128 x 128 tasks that each
-    // take a quarter of the work at about 0.94 of the large tile's efficiency.
-    bool large = (a.N > 128) && (a.max_rows > 128);
-    if (large) {
-        const long long cus = device_cu_count();
-        const long long t_l = (long long)a.groups * ((a.max_rows + 255) / 256) * ((a.N + 255) / 256);
-        const long long t_s = (long long)a.groups * ((a.max_rows + 127) / 128) * ((a.N + 127) / 128);
-        const double time_l = (double)((t_l + cus - 1) / cus);
-        const double time_s = (double)((t_s + 2 * cus - 1) / (2 * cus)) * (2.0 * 0.25 / 0.94);
-        large = time_l <= time_s;
+    // Tile choice from the row bound alone (live row counts are only known on the device).  A CU works through
+    // the tiles it is given at the same rate however many of them are resident, so the time of a launch is about
+    // ceil(tiles / CUs) x tile area / efficiency: 256 x 256 (one per CU), 128 x 128 (two per CU, about 0.94 of
+    // the large tile's efficiency) and, for fp32 storage, 128 x 64 (three per CU, about 0.85), which evens out
+    // launches with fewer 128 x 128 tiles than two per CU.
+    const long long cus = device_cu_count();
+    auto cost = [&](int bm, int bn, double eff) {
+        const long long tiles = (long long)a.groups * ((a.max_rows + bm - 1) / bm) * ((a.N + bn - 1) / bn);
+        return (double)((tiles + cus - 1) / cus) * (double)(bm * bn) / eff;
+    };
+    int pick = 1;                                        // 0: 256 x 256, 1: 128 x 128, 2: 128 x 64
+    double best = cost(128, 128, 0.94);
+    if (a.N > 128 && a.max_rows > 128 && cost(256, 256, 1.0) <= best) {
+        pick = 0;
+        best = cost(256, 256, 1.0);
+    }
+    if constexpr (S::kBytes == 4) {
+        if (!a.b_is_nk && a.N > 64 && cost(128, 64, 0.85) < best) pick = 2;
     }
     if (a.b_is_nk) {
-        return large ? launch_cfg<S, true, 2, 4, 4, 2>(a, stream) : launch_cfg<S, true, 2, 2, 2, 2>(a, stream);
+        return pick == 0 ? launch_cfg<S, true, 2, 4, 4, 2>(a, stream) : launch_cfg<S, true, 2, 2, 2, 2>(a, stream);
     }
-    return large ? launch_cfg<S, false, 2, 4, 4, 2>(a, stream) : launch_cfg<S, false, 2, 2, 2, 2>(a, stream);
+    if constexpr (S::kBytes == 4) {
+        if (pick == 2) return launch_cfg<S, false, 2, 2, 2, 1>(a, stream);
+    }
+    return pick == 0 ? launch_cfg<S, false, 2, 4, 4, 2>(a, stream) : launch_cfg<S, false, 2, 2, 2, 2>(a, stream);
 }
 
 }  // namespace
