@@ -326,20 +326,25 @@ hipError_t launch_t(const GemmArgs& a, hipStream_t stream) {
         const long long tiles = (long long)a.groups * ((a.max_rows + bm - 1) / bm) * ((a.N + bn - 1) / bn);
         return (double)((tiles + cus - 1) / cus) * (double)(bm * bn) / eff;
     };
-    int pick = 1;                                        // 0: 256 x 256, 1: 128 x 128, 2: 128 x 64
+    int pick = 1;                                        // 0: 256 x 256, 1: 128 x 128, 2: 128 x 64, 3: 64 x 128
     double best = cost(128, 128, 0.94);
     if (a.N > 128 && a.max_rows > 128 && cost(256, 256, 1.0) <= best) {
         pick = 0;
         best = cost(256, 256, 1.0);
     }
     if constexpr (S::kBytes == 4) {
-        if (!a.b_is_nk && a.N > 64 && cost(128, 64, 0.85) < best) pick = 2;
+        if (!a.b_is_nk && a.N > 64 && cost(128, 64, 0.85) < best) {
+            pick = 2;
+            best = cost(128, 64, 0.85);
+        }
+        if (!a.b_is_nk && a.max_rows > 64 && cost(64, 128, 0.85) < best) pick = 3;
     }
     if (a.b_is_nk) {
         return pick == 0 ? launch_cfg<S, true, 2, 4, 4, 2>(a, stream) : launch_cfg<S, true, 2, 2, 2, 2>(a, stream);
     }
     if constexpr (S::kBytes == 4) {
         if (pick == 2) return launch_cfg<S, false, 2, 2, 2, 1>(a, stream);
+        if (pick == 3) return launch_cfg<S, false, 1, 4, 2, 1>(a, stream);
     }
     return pick == 0 ? launch_cfg<S, false, 2, 4, 4, 2>(a, stream) : launch_cfg<S, false, 2, 2, 2, 2>(a, stream);
 }
