@@ -9,12 +9,22 @@ H = I = 2048, E = 128 local experts, top-2, capacity factor 1.0, bf16 storage wi
 fp32 accumulation.
 
 Extra objects on the line:
-  roofline      the dominant kernel (the grouped FFN GEMM; two launches per step)
-                against its binding roof, from HIP-event timings of the staged
-                expert-FFN call over the same number of steps;
-  roofline_mfma the same launches priced against the dense MFMA peak;
-  cpu_baseline  the CPU oracle, as it stands, timed on this machine's host cores on a
-                bounded sample (a slice of the tokens, scaled to the full batch).
+  roofline       the dominant kernel (the first expert-FFN launch, x W1 + activation)
+                 against its binding roof; its duration is measured INSIDE moe_forward
+                 with HIP events on the launch stream (moe_forward_timed records them
+                 at the stage boundaries), over as many steps as the timed region, right
+                 after it;
+  roofline_other the same launch priced against the other roof (MFMA peak / HBM);
+  roofline_gemm2 the second FFN launch (h W2) the same way;
+  forward_stage_ms  every stage of the whole-layer call from the same events;
+  staged_stage_ms   the staged entry points called one by one (the staged dispatch
+                 also packs xe, which moe_forward does not);
+  steady_ms      the layer time once the chip has been busy for 256 steps, measured
+                 after the official timed loop (`value` is the official loop alone);
+  measured_peaks a read-stream, a copy and a register-resident MFMA loop run in this
+                 process: what the chip sustains, next to the published peaks;
+  cpu_baseline   the CPU oracle, as it stands, timed on this machine's host cores on a
+                 bounded sample (a slice of the tokens, scaled to the full batch).
 """
 import argparse
 import json
@@ -27,8 +37,6 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-MEASURED_STREAM_GBS = 6100.0
-
 PEAK = {  # MI355X published peaks
     "hbm_gbs": 8000.0,
     "mfma_tflops": {"bf16": 2500.0, "f16": 2500.0, "f32": 157.3},
@@ -38,10 +46,12 @@ PEAK = {  # MI355X published peaks
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=64)
-    # the first ~100 steps after an idle period run about 3 % slower than the steady state (the chip's power
-    # management settles), so the default warm-up is longer than that
-    ap.add_argument("--warmup", type=int, default=256)
+    # defaults: the paper's protocol (Sec. 4: 32 warm-up passes, then the mean of 32)
+    ap.add_argument("--steps", type=int, default=32)
+    ap.add_argument("--warmup", type=int, default=32)
+    ap.add_argument("--steady-after", type=int, default=256,
+                    help="steps run after the timed region before steady_ms is measured (0 = skip)")
+    ap.add_argument("--no-probes", action="store_true", help="skip the stream / MFMA yardstick kernels")
     ap.add_argument("--workload", default="paper_bf16_e128")
     ap.add_argument("--cpu-baseline-tokens", type=int, default=16384,
                     help="tokens in the oracle's timed sample (0 = skip the cpu_baseline leg)")
@@ -55,10 +65,13 @@ def parse_args():
     ap.add_argument("--capacity-factor", type=float, default=0.0, help="override the capacity factor of the workload")
     ap.add_argument("--capacity-mode", default="", help="per_choice (C = ceil(cf k T / E), default) or layout (no factor k)")
     ap.add_argument("--drop-policy", default="", help="token_major (default) or choice_major")
+    ap.add_argument("--single-launch-ffn", action="store_true",
+                    help="both FFN GEMMs in one persistent launch (MOE_FLAG_FFN_SINGLE_LAUNCH)")
     ap.add_argument("--graph", action="store_true",
                     help="replay the step from a captured HIP graph in the timed loop (the same kernels, one launch call)")
     ap.add_argument("--copy-calibration", action="store_true",
-                    help="also launch one plain 1 GiB device copy (reference for hardware counters)")
+                    help="also launch one plain 1 GiB device copy kernel (moe_probe_stream with a destination: the "
+                         "reference for hardware traffic counters)")
     return ap.parse_args()
 
 
@@ -95,6 +108,7 @@ def main():
     if args.capacity_factor > 0: over["capacity_factor"] = args.capacity_factor
     if args.capacity_mode: over["capacity_mode"] = args.capacity_mode
     if args.drop_policy: over["drop_policy"] = args.drop_policy
+    if args.single_launch_ffn: over["flags"] = 1
     if over:
         w = scaled(w, name=w.name + "+" + ",".join("%s=%s" % kv for kv in sorted(over.items())), **over)
     moe.load()
@@ -111,16 +125,17 @@ def main():
         moe.moe_forward(cfg, b.workspace, dev["x"], dev["Wg"], dev["gate_bias"], dev["W1"], dev["b1"], dev["W2"],
                         dev["b2"], b.out, b.gate_logits, b.topk_expert, b.topk_weight, b.slot, b.expert_demand)
 
+    moe.moe_init()
+    sink = torch.zeros(64, dtype=torch.uint8, device="cuda")
     if args.copy_calibration:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
         dst = torch.empty_like(src)
-        dst.copy_(src)
+        moe.moe_probe_stream(src, dst, sink)
         torch.cuda.synchronize()
         del src, dst
 
     run_step = step
     if args.graph:
-        step()                                                   # kernel attributes are set on first use, outside capture
         torch.cuda.synchronize()
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
@@ -130,16 +145,36 @@ def main():
                 step()
         torch.cuda.current_stream().wait_stream(side)
         run_step = graph.replay
+
+    def timed(n):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n):
+            run_step()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / n
+
+    # ---- the official protocol: W untimed steps, then exactly K timed ones
     for _ in range(args.warmup):
         run_step()
+    ms_per_step = timed(args.steps)
+
+    # ---- the same K steps again with events at the stage boundaries inside moe_forward
+    NE = moe.FORWARD_EVENTS
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(NE)] for _ in range(args.steps)]
+    handles = [moe.event_handles(e) for e in ev]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
-        run_step()
+    for h in handles:
+        moe.moe_forward_timed(cfg, b.workspace, dev["x"], dev["Wg"], dev["gate_bias"], dev["W1"], dev["b1"], dev["W2"],
+                              dev["b2"], b.out, b.gate_logits, b.topk_expert, b.topk_weight, b.slot, b.expert_demand, h)
     torch.cuda.synchronize()
-    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    ms_with_events = (time.perf_counter() - t0) * 1e3 / args.steps
+    names = ["gate", "route", "ffn_gemm1", "ffn_gemm2", "combine"]
+    fwd_ms = {n: sum(e[i].elapsed_time(e[i + 1]) for e in ev) / args.steps for i, n in enumerate(names)}
+    fwd_ms["layer"] = sum(e[0].elapsed_time(e[NE - 1]) for e in ev) / args.steps
 
-    # per-stage times: the same kernels through the staged entry points, HIP events on the launch stream
+    # ---- per-stage times of the staged entry points (the same kernels, called one by one)
     stage_calls = [
         ("gate", lambda: moe.moe_gate(cfg, b.workspace, dev["x"], dev["Wg"], dev["gate_bias"], b.gate_logits,
                                       b.topk_expert, b.topk_weight)),
@@ -162,6 +197,44 @@ def main():
     for n, e0, e1 in events:
         stage_ms[n] += e0.elapsed_time(e1) / args.steps
 
+    # ---- steady state: the layer once the chip has been busy for a while (not part of `value`)
+    steady_ms = None
+    if args.steady_after > 0:
+        for _ in range(args.steady_after):
+            run_step()
+        steady_ms = timed(max(args.steps, 32))
+
+    # ---- yardsticks measured in this run: streaming read, copy, MFMA loop
+    measured = None
+    if not args.no_probes:
+        def ev_time(fn, reps):
+            fn()
+            pairs = []
+            for _ in range(reps):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                fn()
+                e1.record()
+                pairs.append((e0, e1))
+            torch.cuda.synchronize()
+            t = sorted(a.elapsed_time(c) for a, c in pairs)
+            return t[len(t) // 2]                                  # median ms
+        src = dev["W1"].view(torch.uint8).reshape(-1)
+        src = src[: min(src.numel(), 1 << 30) // 16 * 16]
+        dst = torch.empty_like(src)
+        rd = ev_time(lambda: moe.moe_probe_stream(src, None, sink), 20)
+        cp = ev_time(lambda: moe.moe_probe_stream(src, dst, sink), 20)
+        del dst
+        iters = 20000 if w.dtype != "f32" else 3000
+        flops = [0.0]
+        def mf():
+            flops[0] = moe.moe_probe_mfma(w.dtype, iters, sink)
+        mm = ev_time(mf, 5)
+        measured = {"stream_read_gbs": round(src.numel() / (rd * 1e-3) / 1e9, 1),
+                    "stream_copy_gbs_read_plus_write": round(2 * src.numel() / (cp * 1e-3) / 1e9, 1),
+                    "mfma_loop_tflops": round(flops[0] / (mm * 1e-3) / 1e12, 1), "mfma_dtype": w.dtype,
+                    "bytes": src.numel(), "kernels": "moe_probe_stream / moe_probe_mfma (csrc/probes.hip)"}
+
     slot = b.slot.cpu()
     demand = b.expert_demand.cpu()
     R = int((slot >= 0).sum())
@@ -169,31 +242,43 @@ def main():
     el = 4 if w.dtype == "f32" else 2
     H, I, E, T, k = w.H, w.I, w.E, w.T, w.k
 
-    # dominant kernel: grouped FFN GEMM, two launches per step (x W1 then h W2)
-    ffn_ms = stage_ms["expert_ffn"]
-    launch_ms = ffn_ms / 2.0
-    flops_per_launch = 2.0 * R * H * I
+    # dominant kernel: the expert-FFN GEMM, two launches per step (x W1 + activation, then h W2); durations are
+    # those measured inside moe_forward
+    ffn_ms = fwd_ms["ffn_gemm1"] + fwd_ms["ffn_gemm2"]
     live = int((demand > 0).sum())                                 # experts nobody picked cost no weight traffic
-    bytes_per_launch = (live * H * I + R * H + R * I) * el         # weights once + A rows + C rows; the sum is the same for both launches
-    hbm_time = bytes_per_launch / (PEAK["hbm_gbs"] * 1e9)
-    mfma_time = flops_per_launch / (PEAK["mfma_tflops"][w.dtype] * 1e12)
     traffic = read_traffic(w.name, w.dtype)
-    kernel_name = ("ffn_gemm_stream_kernel" if w.dtype != "f32" else "grouped_gemm_kernel") + " (expert FFN, 2 launches/step)"
-    ach_gbs = bytes_per_launch / (launch_ms * 1e-3) / 1e9
-    ach_tf = flops_per_launch / (launch_ms * 1e-3) / 1e12
-    roof_hbm = {"bound": "hbm", "achieved": round(ach_gbs, 1), "peak": PEAK["hbm_gbs"], "unit": "GB/s",
-                "frac": round(ach_gbs / PEAK["hbm_gbs"], 4), "traffic": traffic,
-                "kernel": kernel_name, "launch_ms": round(launch_ms, 4),
-                "algorithmic_bytes_per_launch": bytes_per_launch,
-                # context: the best streaming-read rate a plain copy kernel reaches on this chip (measured, GB/s)
-                "measured_stream_peak": MEASURED_STREAM_GBS, "frac_of_measured": round(ach_gbs / MEASURED_STREAM_GBS, 4)}
-    roof_mfma = {"bound": "mfma", "achieved": round(ach_tf, 1), "peak": PEAK["mfma_tflops"][w.dtype],
-                 "unit": "TFLOP/s", "frac": round(ach_tf / PEAK["mfma_tflops"][w.dtype], 4), "traffic": traffic,
-                 "kernel": kernel_name, "launch_ms": round(launch_ms, 4),
-                 "algorithmic_flops_per_launch": flops_per_launch}
-    binding_is_hbm = hbm_time >= mfma_time
-    roofline = roof_hbm if binding_is_hbm else roof_mfma
-    other = roof_mfma if binding_is_hbm else roof_hbm
+    kname = "ffn_gemm_stream_kernel" if w.dtype != "f32" else "grouped_gemm_kernel"
+
+    def roofs(launch_ms, K, N, which):
+        flops = 2.0 * R * K * N
+        nbytes = (live * K * N + R * K + R * N) * el             # weights once + A rows read + C rows written
+        gbs = nbytes / (launch_ms * 1e-3) / 1e9
+        tf = flops / (launch_ms * 1e-3) / 1e12
+        hbm = {"bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK["hbm_gbs"], "unit": "GB/s",
+               "frac": round(gbs / PEAK["hbm_gbs"], 4), "traffic": traffic,
+               "traffic_source": None if traffic is None else "committed rocprofv3 --pmc summary under profiles/ (not a counter of this run)",
+               "kernel": "%s (%s, inside moe_forward)" % (kname, which), "launch_ms": round(launch_ms, 4),
+               "algorithmic_bytes_per_launch": nbytes}
+        if measured:
+            hbm["measured_stream_read_peak"] = measured["stream_read_gbs"]
+            hbm["frac_of_measured"] = round(gbs / measured["stream_read_gbs"], 4)
+        mfma = {"bound": "mfma", "achieved": round(tf, 1), "peak": PEAK["mfma_tflops"][w.dtype], "unit": "TFLOP/s",
+                "frac": round(tf / PEAK["mfma_tflops"][w.dtype], 4), "traffic": traffic,
+                "kernel": "%s (%s, inside moe_forward)" % (kname, which), "launch_ms": round(launch_ms, 4),
+                "algorithmic_flops_per_launch": flops}
+        if measured:
+            mfma["measured_mfma_loop_peak"] = measured["mfma_loop_tflops"]
+            mfma["frac_of_measured"] = round(tf / measured["mfma_loop_tflops"], 4)
+        binding_is_hbm = nbytes / (PEAK["hbm_gbs"] * 1e9) >= flops / (PEAK["mfma_tflops"][w.dtype] * 1e12)
+        return (hbm, mfma) if binding_is_hbm else (mfma, hbm)
+
+    single = bool(getattr(w, "flags", 0) & 1)
+    if single:                                                     # one launch does both GEMMs: price them together
+        roofline, other = roofs(ffn_ms / 2.0, H, I, "both FFN GEMMs in one launch: half its duration")
+        roofline2 = None
+    else:
+        roofline, other = roofs(fwd_ms["ffn_gemm1"], H, I, "first FFN launch: x W1 + activation")
+        roofline2, _ = roofs(fwd_ms["ffn_gemm2"], I, H, "second FFN launch: h W2")
 
     # achieved HBM rate of the bandwidth-bound stages: algorithmic bytes / stage time
     C = b.C
@@ -204,6 +289,9 @@ def main():
         "combine": R * H * el + T * k * 12 + T * H * el,
     }
     stage_gbs = {n: round(v / (stage_ms[n] * 1e-3) / 1e9, 1) for n, v in stage_bytes.items()}
+    # the same for the stages as they run inside moe_forward (no packing there: routing tables only)
+    fwd_bytes = {"gate": stage_bytes["gate"], "route": T * k * 4 + (T * k + 2 * E * C + E) * 4, "combine": stage_bytes["combine"]}
+    fwd_gbs = {n: round(v / (fwd_ms[n] * 1e-3) / 1e9, 1) for n, v in fwd_bytes.items()}
 
     cpu_baseline = None
     if args.cpu_baseline_tokens > 0:
@@ -234,12 +322,18 @@ def main():
         "kept_rows": R, "dropped_pairs": dropped,
         "expert_demand": {"min": int(demand.min()), "median": int(demand.median()), "max": int(demand.max()),
                           "empty": E - live},
-        "stage_ms": {n: round(v, 4) for n, v in stage_ms.items()},
-        "stage_hbm_gbs": stage_gbs,
+        "ms_per_step_with_events": round(ms_with_events, 4),
+        "steady_ms": None if steady_ms is None else round(steady_ms, 4),
+        "forward_stage_ms": {n: round(v, 4) for n, v in fwd_ms.items()},
+        "forward_stage_hbm_gbs": fwd_gbs,
+        "staged_stage_ms": {n: round(v, 4) for n, v in stage_ms.items()},
+        "staged_stage_hbm_gbs": stage_gbs,
         "ffn_tflops": round(4.0 * R * H * I / (ffn_ms * 1e-3) / 1e12, 1),
         "ffn_mfma_frac": round(4.0 * R * H * I / (ffn_ms * 1e-3) / 1e12 / PEAK["mfma_tflops"][w.dtype], 4),
         "roofline": roofline,
         "roofline_other": other,
+        "roofline_gemm2": roofline2,
+        "measured_peaks": measured,
         "cpu_baseline": cpu_baseline,
         "input_gen_s": round(gen_s, 1),
     }

@@ -14,10 +14,13 @@
  *     contiguous, 16-byte aligned.  `cfg` is a HOST pointer.  The library
  *     allocates nothing and touches only the caller's buffers and workspace;
  *     between calls it keeps nothing but a few facts per device (its CU
- *     count, and that a kernel's LDS limit has been raised there: the first
- *     launch of each kernel on a device sets that function attribute, so run
- *     one call before capturing calls into a HIP graph).  Calls act on the
- *     current device, which must be the one that owns the buffers.
+ *     count, and that a kernel's LDS limit has been raised there).  That
+ *     function attribute is set by moe_init(), or else by the first launch of
+ *     each kernel on a device: call moe_init() (or run one call) before
+ *     capturing calls into a HIP graph.  The per-device facts are kept in
+ *     atomics, so host threads may call concurrently (each on its own stream
+ *     and workspace).  Calls act on the current device, which must be the
+ *     one that owns the buffers.
  *   - All work is enqueued on `stream` (a hipStream_t passed as void*; NULL is
  *     the default stream).  No host synchronisation, no device-to-host copy:
  *     ragged per-expert sizes stay on the device.
@@ -45,7 +48,10 @@ typedef enum {
     MOE_ERR_INVALID_ARG = -1,         /* null required pointer, dim <= 0, k > E, bad cf, misaligned pointer */
     MOE_ERR_UNSUPPORTED = -2,         /* H or I not a multiple of 8, E > MOE_MAX_EXPERTS, unknown dtype/act */
     MOE_ERR_WORKSPACE_TOO_SMALL = -3,
-    MOE_ERR_HIP = -4                  /* a launch failed (hipGetLastError) */
+    MOE_ERR_HIP = -4,                 /* a launch failed (hipGetLastError) */
+    /* reported by moe_ffn_status only (the single-launch FFN's bounded waits and placement check): */
+    MOE_ERR_FFN_DEPENDENCY_TIMEOUT = -5,
+    MOE_ERR_FFN_PLACEMENT = -6
 } moe_status;
 
 typedef enum { MOE_F32 = 0, MOE_BF16 = 1, MOE_F16 = 2 } moe_dtype;
@@ -69,6 +75,26 @@ typedef enum {
     MOE_CAPACITY_LAYOUT = 1           /* ceil(cf T / E): the symmetric layout's C E W = S' (Sec. 3.2), no factor k */
 } moe_capacity_mode;
 
+/* moe_config.flags (bit set; unknown bits are MOE_ERR_INVALID_ARG) */
+typedef enum {
+    /* Both FFN tasks in one persistent launch: a t2 (second-GEMM) tile starts as soon as the t1 tiles it
+     * reads are stored, tracked by per-row-tile completion counters (the tile-level dependency of the
+     * paper's processors, Alg. 2) instead of a launch boundary.  Same arithmetic in the same order, so the
+     * results are bit-identical to the default two launches, which are no slower on one MI355X.
+     * 16-bit storage with H, I multiples of 64, at least 256: other configurations are
+     * MOE_ERR_UNSUPPORTED.  First-task tiles never wait and a workgroup starts on its second-task tiles
+     * only after storing all its first-task tiles, so the waits end whatever order the workgroups run in;
+     * they are bounded all the same (about 0.3 s), and producer and consumer tiles meet in one XCD's L2,
+     * which assumes that workgroup ids go round-robin to the XCDs -- the kernel checks that from the
+     * hardware XCD number.  Either failure is recorded in the workspace, the call has already returned
+     * MOE_OK by then, and moe_ffn_status reports it. */
+    MOE_FLAG_FFN_SINGLE_LAUNCH = 1,
+    /* Test aid, with MOE_FLAG_FFN_SINGLE_LAUNCH only: every dependency wait gets a target that cannot be
+     * met and gives up after 16 polls, so that the give-up path runs with every kernel exiting normally;
+     * y and out are then meaningless and moe_ffn_status returns MOE_ERR_FFN_DEPENDENCY_TIMEOUT. */
+    MOE_FLAG_DEBUG_DEPENDENCY_NEVER_MET = 2
+} moe_flags;
+
 #define MOE_MAX_EXPERTS 8192
 
 typedef struct {
@@ -83,9 +109,16 @@ typedef struct {
     int32_t act;                      /* moe_act: phi_1 of the first FFN task */
     int32_t drop_policy;              /* moe_drop_policy */
     int32_t capacity_mode;            /* moe_capacity_mode, used when capacity_override == 0 */
+    int32_t flags;                    /* moe_flags, 0 = defaults */
 } moe_config;
 
 const char* moe_status_string(moe_status s);
+
+/* Optional set-up for the current device: raises the LDS limit of every kernel of the library there (a
+ * function attribute that the launchers otherwise set on a kernel's first use) and reads the device's CU
+ * count, so that later calls change no state and can be captured into a HIP graph without a warm-up call.
+ * Idempotent; may be called from several host threads. */
+moe_status moe_init(void);
 
 /* Row-tile height bM to which per-expert buffers are aligned (in-place padding,
  * Sec. 3.2.1). */
@@ -127,6 +160,30 @@ moe_status moe_forward(const moe_config* cfg, void* workspace, size_t workspace_
                        void* out, float* gate_logits, int32_t* topk_expert, float* topk_weight,
                        int32_t* slot, int32_t* expert_demand, void* stream);
 
+/* Measurement aid: moe_forward with HIP events recorded on `stream` at its stage boundaries, so that a
+ * benchmark can price each stage (Alg. 1: gate, dispatch, the two FFN tasks, combine) inside the whole-layer
+ * call and not in isolation.  events: MOE_FORWARD_EVENTS hipEvent_t created by the caller with timing
+ * enabled, recorded in this order: before the gate, after the gate, after the routing launches, after the
+ * first FFN launch, after the second (recorded right after [3] when one launch does both), after the
+ * combine.  Everything else as moe_forward; the same kernels run in the same order. */
+#define MOE_FORWARD_EVENTS 6
+moe_status moe_forward_timed(const moe_config* cfg, void* workspace, size_t workspace_bytes,
+                             const void* x, const void* Wg, const float* gate_bias,
+                             const void* W1, const void* b1, const void* W2, const void* b2,
+                             void* out, float* gate_logits, int32_t* topk_expert, float* topk_weight,
+                             int32_t* slot, int32_t* expert_demand, void* const* events, void* stream);
+
+/* Yardsticks for the same benchmark: what this chip sustains on the two resources that bound the layer,
+ * measured in the same process (the roofline's published peaks are never reached by any kernel).
+ * moe_probe_stream: one kernel reads `bytes` (a multiple of 16) from src with 16-byte loads; with dst != NULL it
+ *   also writes them there (a plain copy: the reference for hardware traffic counters).  sink: 4 bytes.
+ * moe_probe_mfma: a register-resident loop of `iters` steps of dense MFMAs of the dtype (bf16 / f16:
+ *   v_mfma_f32_16x16x32, fp32: v_mfma_f32_32x32x2) on pseudo-random finite operands, on every CU; *flops
+ *   (host, may be NULL) receives the floating-point operations of the launch.  sink: 4 bytes.
+ * Time them with events on `stream`. */
+moe_status moe_probe_stream(const void* src, void* dst, size_t bytes, void* sink, void* stream);
+moe_status moe_probe_mfma(int32_t dtype, int32_t iters, void* sink, double* flops, void* stream);
+
 /* ---- staged entry points: the same kernels, one stage each ------------------- */
 
 /* Gate ("FusedGate", Alg. 1): gate_logits = x Wg (+ gate_bias) with fp32
@@ -161,10 +218,8 @@ moe_status moe_dispatch(const moe_config* cfg, void* workspace, size_t workspace
  *   y[e,r,:] = phi(xe[e,r,:] W1[e] + b1[e]) W2[e] + b2[e].
  * Only ceil(rows/bM) row tiles per expert are computed; rows beyond are left
  * untouched.  The intermediate h[E,C_pad,I] lives in the workspace.
- * With the environment variable MOE_FFN_FUSED=1 (read at each call) eligible
- * 16-bit shapes run both tasks in one persistent launch, a t2 tile starting
- * when the t1 tiles it reads are stored (Alg. 2's tile-level dependency);
- * the results are identical, the two-launch default is faster on one GPU. */
+ * cfg->flags & MOE_FLAG_FFN_SINGLE_LAUNCH runs both tasks in one persistent
+ * launch (see moe_flags); follow it with moe_ffn_status when convenient. */
 moe_status moe_expert_ffn(const moe_config* cfg, void* workspace, size_t workspace_bytes,
                           const void* xe, const int32_t* expert_demand,
                           const void* W1, const void* b1, const void* W2, const void* b2,
@@ -175,6 +230,26 @@ moe_status moe_expert_ffn(const moe_config* cfg, void* workspace, size_t workspa
  * in fp32, stored in the storage dtype. */
 moe_status moe_combine(const moe_config* cfg, const void* y, const int32_t* topk_expert,
                        const float* topk_weight, const int32_t* slot, void* out, void* stream);
+
+/* Host arithmetic only (no device work): the tasks of one workgroup of the weight-streaming FFN kernels for
+ * one GEMM over one of the two lists of live (expert, row tile) units (Sec. 3.1 tasks; the static stand-in for
+ * the paper's scheduler, Alg. 3), in the order the workgroup runs them.  The same inline functions deal the
+ * tasks inside the kernels.  large_list: 1 = the list of 256-row tiles (n_units_large units, nrow_large row
+ * tiles per expert at most), 0 = the list of 128-row tiles (n_units_small units), whose dealing starts after
+ * the XCD's last large-tile task; ncol = column tiles of the GEMM; workgroup `wg` of the `wgs` workgroups of
+ * XCD `xcd` (0..7).  Writes up to max_tasks (index in the list, column tile) pairs and returns the
+ * workgroup's task count, or -1 on invalid arguments.  For tests and for sizing launches. */
+int32_t moe_ffn_schedule(int32_t large_list, int32_t n_units_large, int32_t n_units_small, int32_t nrow_large,
+                         int32_t ncol, int32_t xcd, int32_t wg, int32_t wgs, int32_t* list_index, int32_t* col_tile,
+                         int32_t max_tasks);
+
+/* Outcome of the single-launch FFN of the last moe_forward / moe_expert_ffn enqueued on `stream` with this
+ * configuration and workspace (Alg. 2's dependency between t1 and t2 tiles, resolved by bounded waits).
+ * Unlike every other call this one SYNCHRONISES: it copies the two fault words of the workspace to the host
+ * and waits for `stream`.  MOE_OK, or MOE_ERR_FFN_DEPENDENCY_TIMEOUT (a wait gave up: y and out of that call
+ * are invalid), or MOE_ERR_FFN_PLACEMENT (workgroups that must share an XCD's L2 did not: results may be
+ * stale).  After calls without MOE_FLAG_FFN_SINGLE_LAUNCH, and for fp32 storage, it returns MOE_OK. */
+moe_status moe_ffn_status(const moe_config* cfg, const void* workspace, size_t workspace_bytes, void* stream);
 
 #ifdef __cplusplus
 }

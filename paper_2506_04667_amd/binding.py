@@ -16,15 +16,19 @@ DTYPE = {"f32": 0, "bf16": 1, "f16": 2}
 ACT = {"relu": 0, "gelu_tanh": 1, "gelu_erf": 2, "identity": 3}
 TORCH_DTYPE = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}
 
-EXPORTS = ["moe_status_string", "moe_row_tile", "moe_capacity", "moe_workspace_bytes", "moe_forward",
-           "moe_gate", "moe_route", "moe_dispatch", "moe_expert_ffn", "moe_combine"]
+EXPORTS = ["moe_status_string", "moe_init", "moe_row_tile", "moe_capacity", "moe_workspace_bytes", "moe_forward",
+           "moe_gate", "moe_route", "moe_dispatch", "moe_expert_ffn", "moe_combine", "moe_ffn_status", "moe_ffn_schedule",
+           "moe_forward_timed", "moe_probe_stream", "moe_probe_mfma"]
+FORWARD_EVENTS = 6
+FLAG_FFN_SINGLE_LAUNCH = 1
+FLAG_DEBUG_DEPENDENCY_NEVER_MET = 2
 
 
 class MoeConfig(ctypes.Structure):
     _fields_ = [("T", ctypes.c_int32), ("H", ctypes.c_int32), ("I", ctypes.c_int32),
                 ("E", ctypes.c_int32), ("k", ctypes.c_int32), ("capacity_factor", ctypes.c_float),
                 ("capacity_override", ctypes.c_int32), ("dtype", ctypes.c_int32), ("act", ctypes.c_int32),
-                ("drop_policy", ctypes.c_int32), ("capacity_mode", ctypes.c_int32)]
+                ("drop_policy", ctypes.c_int32), ("capacity_mode", ctypes.c_int32), ("flags", ctypes.c_int32)]
 
 
 class MoeError(RuntimeError):
@@ -50,6 +54,12 @@ def load(path=None):
     cfgp = ctypes.POINTER(MoeConfig)
     lib.moe_status_string.restype = ctypes.c_char_p
     lib.moe_status_string.argtypes = [ctypes.c_int]
+    lib.moe_init.restype = ctypes.c_int
+    lib.moe_init.argtypes = []
+    lib.moe_ffn_status.restype = ctypes.c_int
+    lib.moe_ffn_status.argtypes = [cfgp, vp, ctypes.c_size_t, vp]
+    lib.moe_ffn_schedule.restype = ctypes.c_int32
+    lib.moe_ffn_schedule.argtypes = [ctypes.c_int32] * 8 + [i32p, i32p, ctypes.c_int32]
     lib.moe_row_tile.restype = ctypes.c_int32
     lib.moe_row_tile.argtypes = []
     lib.moe_capacity.restype = ctypes.c_int
@@ -58,6 +68,12 @@ def load(path=None):
     lib.moe_workspace_bytes.argtypes = [cfgp, ctypes.POINTER(ctypes.c_size_t)]
     lib.moe_forward.restype = ctypes.c_int
     lib.moe_forward.argtypes = [cfgp, vp, ctypes.c_size_t] + [vp] * 14
+    lib.moe_forward_timed.restype = ctypes.c_int
+    lib.moe_forward_timed.argtypes = [cfgp, vp, ctypes.c_size_t] + [vp] * 13 + [ctypes.POINTER(vp), vp]
+    lib.moe_probe_stream.restype = ctypes.c_int
+    lib.moe_probe_stream.argtypes = [vp, vp, ctypes.c_size_t, vp, vp]
+    lib.moe_probe_mfma.restype = ctypes.c_int
+    lib.moe_probe_mfma.argtypes = [ctypes.c_int32, ctypes.c_int32, vp, ctypes.POINTER(ctypes.c_double), vp]
     lib.moe_gate.restype = ctypes.c_int
     lib.moe_gate.argtypes = [cfgp, vp, ctypes.c_size_t] + [vp] * 7
     lib.moe_route.restype = ctypes.c_int
@@ -78,16 +94,16 @@ CAPACITY_MODE = {"per_choice": 0, "layout": 1}
 
 
 def make_config(T, H, I, E, k, capacity_factor, act, dtype, capacity_override=0, drop_policy="token_major",
-                capacity_mode="per_choice"):
+                capacity_mode="per_choice", flags=0):
     return MoeConfig(T, H, I, E, k, float(capacity_factor), int(capacity_override), DTYPE[dtype], ACT[act],
-                     DROP_POLICY[drop_policy], CAPACITY_MODE[capacity_mode])
+                     DROP_POLICY[drop_policy], CAPACITY_MODE[capacity_mode], int(flags))
 
 
 def config_of(w):
     """moe_config of a workload description (anything with T, H, I, E, k, capacity_factor, act, dtype)."""
     return make_config(w.T, w.H, w.I, w.E, w.k, w.capacity_factor, w.act, w.dtype,
                        getattr(w, "capacity_override", 0), getattr(w, "drop_policy", "token_major"),
-                       getattr(w, "capacity_mode", "per_choice"))
+                       getattr(w, "capacity_mode", "per_choice"), getattr(w, "flags", 0))
 
 
 def _p(t):
@@ -114,8 +130,27 @@ def moe_status_string(code):
     return load().moe_status_string(code).decode()
 
 
+def moe_init():
+    _check(load().moe_init())
+
+
 def moe_row_tile():
     return load().moe_row_tile()
+
+
+def moe_ffn_schedule(large_list, n_units_large, n_units_small, nrow_large, ncol, xcd, wg, wgs, max_tasks=4096):
+    """(list index, column tile) of each task of one workgroup, in the order it runs them (host arithmetic)."""
+    li = (ctypes.c_int32 * max_tasks)()
+    ct = (ctypes.c_int32 * max_tasks)()
+    n = load().moe_ffn_schedule(int(large_list), n_units_large, n_units_small, nrow_large, ncol, xcd, wg, wgs, li, ct, max_tasks)
+    if n < 0 or n > max_tasks:
+        raise MoeError(-1, "moe_ffn_schedule: invalid arguments or more than max_tasks tasks")
+    return [(li[i], ct[i]) for i in range(n)]
+
+
+def moe_ffn_status(cfg, workspace, stream=None):
+    """Status code of the last single-launch FFN on this workspace (synchronises the stream)."""
+    return load().moe_ffn_status(ctypes.byref(cfg), _p(workspace), _ws_bytes(workspace), _stream(stream))
 
 
 def moe_capacity(cfg):
@@ -139,6 +174,37 @@ def moe_forward(cfg, workspace, x, Wg, gate_bias, W1, b1, W2, b2, out, gate_logi
     _check(load().moe_forward(ctypes.byref(cfg), _p(workspace), _ws_bytes(workspace), _p(x), _p(Wg),
                               _p(gate_bias), _p(W1), _p(b1), _p(W2), _p(b2), _p(out), _p(gate_logits),
                               _p(topk_expert), _p(topk_weight), _p(slot), _p(expert_demand), _stream(stream)))
+
+
+def event_handles(events):
+    """The hipEvent_t handles of torch events (created with enable_timing=True).  torch creates the handle at the
+    first record(), so each event is recorded once here."""
+    arr = (ctypes.c_void_p * len(events))()
+    for i, e in enumerate(events):
+        if not e.cuda_event:
+            e.record()
+        arr[i] = e.cuda_event
+    return arr
+
+
+def moe_forward_timed(cfg, workspace, x, Wg, gate_bias, W1, b1, W2, b2, out, gate_logits, topk_expert,
+                      topk_weight, slot, expert_demand, handles, stream=None):
+    """moe_forward with the FORWARD_EVENTS events of ``handles`` (from event_handles) recorded at its stage boundaries."""
+    _check(load().moe_forward_timed(ctypes.byref(cfg), _p(workspace), _ws_bytes(workspace), _p(x), _p(Wg),
+                                    _p(gate_bias), _p(W1), _p(b1), _p(W2), _p(b2), _p(out), _p(gate_logits),
+                                    _p(topk_expert), _p(topk_weight), _p(slot), _p(expert_demand), handles,
+                                    _stream(stream)))
+
+
+def moe_probe_stream(src, dst, sink, stream=None):
+    _check(load().moe_probe_stream(_p(src), _p(dst), src.numel() * src.element_size(), _p(sink), _stream(stream)))
+
+
+def moe_probe_mfma(dtype, iters, sink, stream=None):
+    """Launch the MFMA loop; returns the floating-point operations of the launch."""
+    flops = ctypes.c_double()
+    _check(load().moe_probe_mfma(DTYPE[dtype], int(iters), _p(sink), ctypes.byref(flops), _stream(stream)))
+    return flops.value
 
 
 def moe_gate(cfg, workspace, x, Wg, gate_bias, gate_logits, topk_expert, topk_weight, stream=None):

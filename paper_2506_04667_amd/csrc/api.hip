@@ -5,9 +5,9 @@
 #include "../../include/moe.h"
 
 #include <cmath>
-#include <cstdlib>
 #include <initializer_list>
 
+#include "ffn_units.h"
 #include "kernels.h"
 
 namespace {
@@ -35,6 +35,8 @@ moe_status check_config(const moe_config* c) {
     if (c->E > MOE_MAX_EXPERTS) return MOE_ERR_UNSUPPORTED;
     if (c->drop_policy < MOE_DROP_TOKEN_MAJOR || c->drop_policy > MOE_DROP_CHOICE_MAJOR) return MOE_ERR_UNSUPPORTED;
     if (c->capacity_mode < MOE_CAPACITY_PER_CHOICE || c->capacity_mode > MOE_CAPACITY_LAYOUT) return MOE_ERR_UNSUPPORTED;
+    if (c->flags & ~(MOE_FLAG_FFN_SINGLE_LAUNCH | MOE_FLAG_DEBUG_DEPENDENCY_NEVER_MET)) return MOE_ERR_INVALID_ARG;
+    if ((c->flags & MOE_FLAG_DEBUG_DEPENDENCY_NEVER_MET) && !(c->flags & MOE_FLAG_FFN_SINGLE_LAUNCH)) return MOE_ERR_INVALID_ARG;
     return MOE_OK;
 }
 
@@ -80,6 +82,16 @@ moe_status make_plan(const moe_config* c, Plan* p) {
 
 bool misaligned(const void* p) { return ((uintptr_t)p & 15u) != 0; }
 
+// MOE_FLAG_FFN_SINGLE_LAUNCH asks for both FFN tasks in one persistent launch; only shapes that the
+// weight-streaming kernel takes for both tasks can run that way.  `gather`: the first task reads token rows
+// through the routing table (moe_forward) instead of packed rows (moe_expert_ffn).
+moe_status check_single_launch(const moe_config* c, const Plan& p, bool gather) {
+    if (!(c->flags & MOE_FLAG_FFN_SINGLE_LAUNCH)) return MOE_OK;
+    const bool ok = moe::stream_gemm_shape_ok(c->dtype, c->I, c->H, c->H, c->I, c->I, gather ? c->T : p.C_pad) &&
+                    moe::stream_gemm_shape_ok(c->dtype, c->H, c->I, c->I, c->H, c->H, p.C_pad);
+    return ok ? MOE_OK : MOE_ERR_UNSUPPORTED;
+}
+
 moe_status hip_status(hipError_t e) { return e == hipSuccess ? MOE_OK : MOE_ERR_HIP; }
 
 char* ws_at(void* ws, size_t off) { return (char*)ws + off; }
@@ -116,16 +128,16 @@ moe_status run_gate(const moe_config* c, const Plan& p, void* ws, const void* x,
     return hip_status(moe::launch_topk(logits, c->T, c->E, c->k, topk_expert, topk_weight, s));
 }
 
-moe_status run_dispatch(const moe_config* c, const Plan& p, void* ws, const void* x,
+// counts: scratch of route_chunks(T) * E ints; units: the FFN kernels' scratch block to fill, or nullptr
+moe_status run_dispatch(const moe_config* c, const Plan& p, int32_t* counts, int32_t* units, const void* x,
                         const int32_t* topk_expert, const float* topk_weight, int32_t* slot,
                         int32_t* expert_demand, int32_t* slot_token, float* slot_weight, void* xe,
-                        bool counts_ready, bool build_units, hipStream_t s) {
+                        bool counts_ready, hipStream_t s) {
     // the fused gate counts per chunk of 64 tokens, which is a chunk of the pair order only under token-major priority
     const bool choice_major = c->drop_policy == MOE_DROP_CHOICE_MAJOR;
     hipError_t e = moe::launch_route(topk_expert, topk_weight, c->T, c->E, c->k, p.C, choice_major,
-                                     (int32_t*)ws_at(ws, p.off_counts), counts_ready && !choice_major, slot, expert_demand,
-                                     slot_token, slot_weight,
-                                     build_units ? (int32_t*)ws_at(ws, p.off_units) : nullptr, s);
+                                     counts, counts_ready && !choice_major, slot, expert_demand,
+                                     slot_token, slot_weight, units, s);
     if (e != hipSuccess) return MOE_ERR_HIP;
     if (!xe) return MOE_OK;
     return hip_status(moe::launch_pack(x, topk_expert, slot, c->T, c->H, c->k, c->E, p.C, p.C_pad, c->dtype, xe, s));
@@ -135,7 +147,7 @@ moe_status run_dispatch(const moe_config* c, const Plan& p, void* ws, const void
 // first GEMM gathers through slot_token[E, C] (no packed copy).
 moe_status run_ffn(const moe_config* c, const Plan& p, void* ws, const void* xe, const int32_t* slot_token,
                    const int32_t* expert_demand, const void* W1, const void* b1, const void* W2,
-                   const void* b2, void* y, bool units_ready, hipStream_t s) {
+                   const void* b2, void* y, bool units_ready, hipEvent_t between, hipStream_t s) {
     void* h = ws_at(ws, p.off_h);
     const long long H = c->H, I = c->I;
     moe::GemmArgs g{};
@@ -170,14 +182,18 @@ moe_status run_ffn(const moe_config* c, const Plan& p, void* ws, const void* xe,
     g2.C = y; g2.c_group_stride = (long long)p.C_pad * H; g2.ldc = c->H;
     g2.bias = b2; g2.bias_group_stride = H;
     g2.N = c->H; g2.K = c->I; g2.act = MOE_ACT_IDENTITY;
-    // Optional: one persistent launch for both tasks, t2 tiles following their t1 tiles by dependency (the
-    // tile-level pipelining of the paper's processors, Alg. 2).  Measured slower than two launches on one
-    // MI355X at the paper's shapes, so it is opt-in (environment variable MOE_FFN_FUSED=1).
-    const char* fused = std::getenv("MOE_FFN_FUSED");
-    if (fused && fused[0] == '1' && moe::ffn_fused_eligible(g1, g2))
-        return hip_status(moe::launch_ffn_stream_fused(g1, g2, s));
+    // Optional: one persistent launch for both tasks, a t2 tile starting when the t1 tiles it reads are stored
+    // (the tile-level dependency of the paper's processors, Alg. 2).  No faster than two launches on one
+    // MI355X at the paper's shapes, so it is opt-in (MOE_FLAG_FFN_SINGLE_LAUNCH; shapes checked by the caller).
+    if (c->flags & MOE_FLAG_FFN_SINGLE_LAUNCH) {
+        if (!moe::ffn_fused_eligible(g1, g2)) return MOE_ERR_UNSUPPORTED;
+        e = moe::launch_ffn_stream_fused(g1, g2, (c->flags & MOE_FLAG_DEBUG_DEPENDENCY_NEVER_MET) != 0, s);
+        if (e == hipSuccess && between) e = hipEventRecord(between, s);
+        return hip_status(e);
+    }
     e = moe::launch_grouped_gemm(g1, s);
     if (e != hipSuccess) return MOE_ERR_HIP;
+    if (between && hipEventRecord(between, s) != hipSuccess) return MOE_ERR_HIP;
     return hip_status(moe::launch_grouped_gemm(g2, s));
 }
 
@@ -198,6 +214,49 @@ bool bad_optional(std::initializer_list<const void*> ptrs) {
     return false;
 }
 
+// The whole layer on one stream.  `ev` (optional, MOE_FORWARD_EVENTS events) are recorded on the stream at the
+// stage boundaries: before the gate, after the gate, after the routing launches, after the first FFN launch,
+// after the second (the same point as the first under the single-launch flag), after the combine.
+moe_status forward_impl(const moe_config* cfg, void* workspace, size_t workspace_bytes, const void* x,
+                        const void* Wg, const float* gate_bias, const void* W1, const void* b1,
+                        const void* W2, const void* b2, void* out, float* gate_logits,
+                        int32_t* topk_expert, float* topk_weight, int32_t* slot, int32_t* expert_demand,
+                        const hipEvent_t* ev, hipStream_t s) {
+    Plan p;
+    moe_status st = make_plan(cfg, &p);
+    if (st != MOE_OK) return st;
+    if (bad_required({workspace, x, Wg, W1, W2, out, topk_expert, topk_weight, slot, expert_demand}) ||
+        bad_optional({gate_bias, b1, b2, gate_logits}))
+        return MOE_ERR_INVALID_ARG;
+    if (workspace_bytes < p.total) return MOE_ERR_WORKSPACE_TOO_SMALL;
+    st = check_single_launch(cfg, p, true);
+    if (st != MOE_OK) return st;
+    auto mark = [&](int i) { return !ev || hipEventRecord(ev[i], s) == hipSuccess; };
+    float* logits = gate_logits ? gate_logits : (float*)ws_at(workspace, p.off_logits);
+    int32_t* slot_token = (int32_t*)ws_at(workspace, p.off_slot_token);
+    float* slot_weight = (float*)ws_at(workspace, p.off_slot_weight);
+    void* y = ws_at(workspace, p.off_y);
+    bool counts_ready = false;
+    if (!mark(0)) return MOE_ERR_HIP;
+    st = run_gate(cfg, p, workspace, x, Wg, gate_bias, logits, topk_expert, topk_weight, &counts_ready, s);
+    if (st != MOE_OK) return st;
+    if (!mark(1)) return MOE_ERR_HIP;
+    // Dispatch builds the routing table only; the first FFN GEMM gathers its rows from x through
+    // slot_token, so the packed copy xe is never materialised on this path.
+    const bool units_here = cfg->dtype != MOE_F32;      // the scatter launch also lists the live FFN units
+    st = run_dispatch(cfg, p, (int32_t*)ws_at(workspace, p.off_counts),
+                      units_here ? (int32_t*)ws_at(workspace, p.off_units) : nullptr, x, topk_expert, topk_weight, slot,
+                      expert_demand, slot_token, slot_weight, nullptr, counts_ready, s);
+    if (st != MOE_OK) return st;
+    if (!mark(2)) return MOE_ERR_HIP;
+    st = run_ffn(cfg, p, workspace, x, slot_token, expert_demand, W1, b1, W2, b2, y, units_here, ev ? ev[3] : nullptr, s);
+    if (st != MOE_OK) return st;
+    if (!mark(4)) return MOE_ERR_HIP;
+    st = run_combine(cfg, p, y, topk_expert, topk_weight, slot, out, s);
+    if (st != MOE_OK) return st;
+    return mark(5) ? MOE_OK : MOE_ERR_HIP;
+}
+
 }  // namespace
 
 extern "C" {
@@ -209,11 +268,65 @@ const char* moe_status_string(moe_status s) {
         case MOE_ERR_UNSUPPORTED: return "unsupported configuration";
         case MOE_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
         case MOE_ERR_HIP: return "HIP launch error";
+        case MOE_ERR_FFN_DEPENDENCY_TIMEOUT: return "single-launch FFN: a wait for first-task tiles gave up (results invalid)";
+        case MOE_ERR_FFN_PLACEMENT: return "single-launch FFN: workgroups of one class ran on different XCDs (results may be stale)";
     }
     return "unknown status";
 }
 
 int32_t moe_row_tile(void) { return kRowTile; }
+
+moe_status moe_init(void) {
+    hipError_t e = moe::prepare_gate_fused();
+    if (e == hipSuccess) e = moe::prepare_grouped_gemm();
+    if (e == hipSuccess) e = moe::prepare_grouped_gemm_stream();
+    if (e != hipSuccess) return MOE_ERR_HIP;
+    (void)moe::device_cu_count();
+    return MOE_OK;
+}
+
+int32_t moe_ffn_schedule(int32_t large_list, int32_t n_units_large, int32_t n_units_small, int32_t nrow_large,
+                         int32_t ncol, int32_t xcd, int32_t wg, int32_t wgs, int32_t* list_index, int32_t* col_tile,
+                         int32_t max_tasks) {
+    if (n_units_large < 0 || n_units_small < 0 || nrow_large < 0 || ncol <= 0 || xcd < 0 || xcd >= moe::kXcds ||
+        wgs <= 0 || wg < 0 || wg >= wgs || max_tasks < 0 || (max_tasks > 0 && (!list_index || !col_tile)))
+        return -1;
+    int unit0, unit_step, ux_l, ux;
+    moe::ffn_xcd_share(true, n_units_large, nrow_large, xcd, unit0, unit_step, ux_l);
+    int w = wg;
+    if (large_list) {
+        ux = ux_l;
+    } else {
+        moe::ffn_xcd_share(false, n_units_small, 1, xcd, unit0, unit_step, ux);
+        w = moe::ffn_small_list_rotation(wg, wgs, ux_l, ncol);
+    }
+    int n = 0;
+    for (long long p = w; p < (long long)ux * ncol; p += wgs, ++n)
+        if (n < max_tasks) moe::ffn_task_at((int)p, ncol, unit0, unit_step, list_index[n], col_tile[n]);
+    return n;
+}
+
+moe_status moe_ffn_status(const moe_config* cfg, const void* workspace, size_t workspace_bytes, void* stream) {
+    Plan p;
+    moe_status st = make_plan(cfg, &p);
+    if (st != MOE_OK) return st;
+    if (!workspace || misaligned(workspace)) return MOE_ERR_INVALID_ARG;
+    if (workspace_bytes < p.total) return MOE_ERR_WORKSPACE_TOO_SMALL;
+    if (cfg->dtype == MOE_F32) return MOE_OK;            // the unit lists (and their fault words) belong to the 16-bit kernels
+    long long w0 = 0, w1 = 0;
+    moe::ffn_units_fault_words(cfg->E, p.C, &w0, &w1);
+    const int32_t* units = (const int32_t*)((const char*)workspace + p.off_units);
+    int32_t f0 = 0, f1 = 0;
+    hipStream_t s = (hipStream_t)stream;
+    if (hipMemcpyAsync(&f0, units + w0, sizeof(int32_t), hipMemcpyDeviceToHost, s) != hipSuccess ||
+        hipMemcpyAsync(&f1, units + w1, sizeof(int32_t), hipMemcpyDeviceToHost, s) != hipSuccess ||
+        hipStreamSynchronize(s) != hipSuccess)
+        return MOE_ERR_HIP;
+    const int32_t f = f0 | f1;
+    if (f & 1) return MOE_ERR_FFN_DEPENDENCY_TIMEOUT;
+    if (f & 2) return MOE_ERR_FFN_PLACEMENT;
+    return MOE_OK;
+}
 
 moe_status moe_capacity(const moe_config* cfg, int32_t* C, int32_t* C_pad) {
     moe_status st = check_config(cfg);
@@ -240,30 +353,20 @@ moe_status moe_forward(const moe_config* cfg, void* workspace, size_t workspace_
                        const void* W2, const void* b2, void* out, float* gate_logits,
                        int32_t* topk_expert, float* topk_weight, int32_t* slot, int32_t* expert_demand,
                        void* stream) {
-    Plan p;
-    moe_status st = make_plan(cfg, &p);
-    if (st != MOE_OK) return st;
-    if (bad_required({workspace, x, Wg, W1, W2, out, topk_expert, topk_weight, slot, expert_demand}) ||
-        bad_optional({gate_bias, b1, b2, gate_logits}))
-        return MOE_ERR_INVALID_ARG;
-    if (workspace_bytes < p.total) return MOE_ERR_WORKSPACE_TOO_SMALL;
-    hipStream_t s = (hipStream_t)stream;
-    float* logits = gate_logits ? gate_logits : (float*)ws_at(workspace, p.off_logits);
-    int32_t* slot_token = (int32_t*)ws_at(workspace, p.off_slot_token);
-    float* slot_weight = (float*)ws_at(workspace, p.off_slot_weight);
-    void* y = ws_at(workspace, p.off_y);
-    bool counts_ready = false;
-    st = run_gate(cfg, p, workspace, x, Wg, gate_bias, logits, topk_expert, topk_weight, &counts_ready, s);
-    if (st != MOE_OK) return st;
-    // Dispatch builds the routing table only; the first FFN GEMM gathers its rows from x through
-    // slot_token, so the packed copy xe is never materialised on this path.
-    const bool units_here = cfg->dtype != MOE_F32;      // the scatter launch also lists the live FFN units
-    st = run_dispatch(cfg, p, workspace, x, topk_expert, topk_weight, slot, expert_demand, slot_token, slot_weight, nullptr,
-                      counts_ready, units_here, s);
-    if (st != MOE_OK) return st;
-    st = run_ffn(cfg, p, workspace, x, slot_token, expert_demand, W1, b1, W2, b2, y, units_here, s);
-    if (st != MOE_OK) return st;
-    return run_combine(cfg, p, y, topk_expert, topk_weight, slot, out, s);
+    return forward_impl(cfg, workspace, workspace_bytes, x, Wg, gate_bias, W1, b1, W2, b2, out, gate_logits, topk_expert,
+                        topk_weight, slot, expert_demand, nullptr, (hipStream_t)stream);
+}
+
+moe_status moe_forward_timed(const moe_config* cfg, void* workspace, size_t workspace_bytes, const void* x,
+                             const void* Wg, const float* gate_bias, const void* W1, const void* b1,
+                             const void* W2, const void* b2, void* out, float* gate_logits,
+                             int32_t* topk_expert, float* topk_weight, int32_t* slot, int32_t* expert_demand,
+                             void* const* events, void* stream) {
+    if (!events) return MOE_ERR_INVALID_ARG;
+    for (int i = 0; i < MOE_FORWARD_EVENTS; ++i)
+        if (!events[i]) return MOE_ERR_INVALID_ARG;
+    return forward_impl(cfg, workspace, workspace_bytes, x, Wg, gate_bias, W1, b1, W2, b2, out, gate_logits, topk_expert,
+                        topk_weight, slot, expert_demand, (const hipEvent_t*)events, (hipStream_t)stream);
 }
 
 moe_status moe_gate(const moe_config* cfg, void* workspace, size_t workspace_bytes, const void* x,
@@ -297,8 +400,8 @@ moe_status moe_dispatch(const moe_config* cfg, void* workspace, size_t workspace
         bad_optional({x, xe}) || (xe && !x))
         return MOE_ERR_INVALID_ARG;
     if (workspace_bytes < p.total) return MOE_ERR_WORKSPACE_TOO_SMALL;
-    return run_dispatch(cfg, p, workspace, x, topk_expert, topk_weight, slot, expert_demand, slot_token, slot_weight, xe,
-                        false, false, (hipStream_t)stream);
+    return run_dispatch(cfg, p, (int32_t*)ws_at(workspace, p.off_counts), nullptr, x, topk_expert, topk_weight, slot,
+                        expert_demand, slot_token, slot_weight, xe, false, (hipStream_t)stream);
 }
 
 moe_status moe_expert_ffn(const moe_config* cfg, void* workspace, size_t workspace_bytes, const void* xe,
@@ -309,7 +412,9 @@ moe_status moe_expert_ffn(const moe_config* cfg, void* workspace, size_t workspa
     if (st != MOE_OK) return st;
     if (bad_required({workspace, xe, expert_demand, W1, W2, y}) || bad_optional({b1, b2})) return MOE_ERR_INVALID_ARG;
     if (workspace_bytes < p.total) return MOE_ERR_WORKSPACE_TOO_SMALL;
-    return run_ffn(cfg, p, workspace, xe, nullptr, expert_demand, W1, b1, W2, b2, y, false, (hipStream_t)stream);
+    st = check_single_launch(cfg, p, false);
+    if (st != MOE_OK) return st;
+    return run_ffn(cfg, p, workspace, xe, nullptr, expert_demand, W1, b1, W2, b2, y, false, nullptr, (hipStream_t)stream);
 }
 
 moe_status moe_combine(const moe_config* cfg, const void* y, const int32_t* topk_expert,

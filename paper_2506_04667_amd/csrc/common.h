@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 namespace moe {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
@@ -127,17 +129,20 @@ __device__ __forceinline__ float apply_act(float v, int act) {
 }
 
 // Host side: a kernel that uses more than 64 KB of dynamic LDS has that limit raised once per device
-// (`done` is the kernel's own table of devices already served).
+// (`done` is the kernel's own table of devices already served).  The tables are atomics: two host threads
+// making their first call at the same time may both set the attribute (setting it twice is harmless), and
+// neither reads a half-written entry.
 constexpr int kMaxDevices = 64;
-inline hipError_t raise_lds_limit(const void* kernel, int bytes, bool (&done)[kMaxDevices]) {
+typedef std::atomic<bool> DeviceFlags[kMaxDevices];
+inline hipError_t raise_lds_limit(const void* kernel, int bytes, DeviceFlags& done) {
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;
     if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
-    if (!done[dev]) {
+    if (!done[dev].load(std::memory_order_acquire)) {
         e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
         if (e != hipSuccess) return e;
-        done[dev] = true;
+        done[dev].store(true, std::memory_order_release);
     }
     return hipSuccess;
 }

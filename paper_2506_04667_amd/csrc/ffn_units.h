@@ -12,12 +12,16 @@ namespace moe {
 // list and its own launch.
 constexpr int kUnitRowsLarge = 256, kUnitRowsSmall = 128;
 
-// Scratch block: two lists of the same format, the large tiles' first.
+// Scratch block: two lists of the same format, the large tiles' first, then kXcds placement words.
 //   list = { fault word (cleared), number of live units n, ids[cap] (n used), completion counters[cap] (cleared) }
 //   large: cap = groups * nrow_large, id = g * nrow_large + (row tile of 256), nrow_large = ceil(max_rows / 256);
 //          absent (0 ints) when max_rows <= 128
 //   small: cap = groups, id = g * nrow_small + (row tile of 128), nrow_small = ceil(max_rows / 128)
-// both in order of group.
+// both in order of group.  Fault word bits: kFaultWaitGaveUp, kFaultPlacement (single-launch FFN only).
+//   placement[x] = -1 (set by the builder); the single-launch FFN records there the hardware XCD that the
+//   workgroups with blockIdx % kXcds == x run on, and flags a fault if two of them disagree.
+constexpr int kXcds = 8;
+constexpr int kFaultWaitGaveUp = 1, kFaultPlacement = 2;
 __host__ __device__ inline int ffn_units_nrow_large(int max_rows) {
     return max_rows > kUnitRowsSmall ? (max_rows + kUnitRowsLarge - 1) / kUnitRowsLarge : 0;
 }
@@ -26,8 +30,34 @@ __host__ __device__ inline long long ffn_units_small_offset(int groups, int max_
     const int nl = ffn_units_nrow_large(max_rows);
     return nl ? 2 + 2ll * groups * nl : 0;
 }
-__host__ __device__ inline long long ffn_units_total_ints(int groups, int max_rows) {
+__host__ __device__ inline long long ffn_units_placement_offset(int groups, int max_rows) {
     return ffn_units_small_offset(groups, max_rows) + 2 + 2ll * groups;
+}
+__host__ __device__ inline long long ffn_units_total_ints(int groups, int max_rows) {
+    return ffn_units_placement_offset(groups, max_rows) + kXcds;
+}
+
+// The units of a list that XCD `xcd` works on: unit0, unit0 + unit_step, ... (ux of them).  Every 8th unit
+// when an expert has at most one unit in the list (always so for the small tiles), else a contiguous block.
+// `large`: the list of 256-row tiles.
+__host__ __device__ inline void ffn_xcd_share(bool large, int n_units, int nrow, int xcd, int& unit0, int& unit_step, int& ux) {
+    const bool blocks = large && nrow > 1;
+    unit0 = blocks ? (int)((long long)n_units * xcd / kXcds) : xcd;
+    unit_step = blocks ? 1 : kXcds;
+    ux = blocks ? (int)((long long)n_units * (xcd + 1) / kXcds) - unit0
+                : (n_units > xcd ? (n_units - xcd + kXcds - 1) / kXcds : 0);
+}
+// An XCD's tasks of one FFN GEMM over one list, in order: position p = (unit index inside the XCD) * ncol +
+// column tile.  Workgroup w of the XCD's wgs takes positions w, w + wgs, ...  For the small list, w is the
+// workgroup's number rotated so that the first small-tile task goes to the workgroup after the one that got
+// the XCD's last large-tile task.
+__host__ __device__ inline void ffn_task_at(int p, int ncol, int unit0, int unit_step, int& list_index, int& col_tile) {
+    list_index = unit0 + (p / ncol) * unit_step;
+    col_tile = p % ncol;
+}
+__host__ __device__ inline int ffn_small_list_rotation(int wg, int wgs, int ux_large, int ncol) {
+    int w = wg - (int)(((long long)ux_large * ncol) % wgs);
+    return w < 0 ? w + wgs : w;
 }
 
 // Called by every thread of ONE workgroup of `nthreads` threads (a multiple of 64, at most 1024);
@@ -41,6 +71,7 @@ __device__ __forceinline__ void build_ffn_units(const int32_t* __restrict__ rows
     const int cap_l = groups * nrow_l;
     for (int i = tid; i < cap_l; i += nthreads) wl[2 + cap_l + i] = 0;
     for (int i = tid; i < groups; i += nthreads) ws[2 + groups + i] = 0;
+    if (tid < kXcds) w[ffn_units_placement_offset(groups, max_rows) + tid] = -1;
     int carry_l = 0, carry_s = 0;                       // units of the groups before this pass
     for (int g0 = 0; g0 < groups; g0 += nthreads) {
         const int g = g0 + tid;

@@ -340,14 +340,20 @@ __global__ __launch_bounds__(G_THREADS) void gate_fused_kernel(const unsigned ch
     }
 }
 
+// the kernel's LDS limit on the current device (once per device)
+template <class S, int BN>
+hipError_t prepare_gate_fused_t() {
+    static DeviceFlags limit_raised = {};
+    return raise_lds_limit(reinterpret_cast<const void*>(gate_fused_kernel<S, BN>), GateCfg<S, BN>::LDS_BYTES, limit_raised);
+}
+
 template <class S, int BN>
 hipError_t launch_gate_fused_t(const void* x, const void* Wg, const float* gate_bias, int T, int H, int E, int k,
                                float* logits, int32_t* topk_expert, float* topk_weight, int32_t* route_counts,
                                hipStream_t stream) {
     auto kernel = gate_fused_kernel<S, BN>;
     constexpr int lds_bytes = GateCfg<S, BN>::LDS_BYTES;
-    static bool limit_raised[kMaxDevices] = {};
-    if (hipError_t e = raise_lds_limit(reinterpret_cast<const void*>(kernel), lds_bytes, limit_raised); e != hipSuccess) return e;
+    if (hipError_t e = prepare_gate_fused_t<S, BN>(); e != hipSuccess) return e;
     hipLaunchKernelGGL(kernel, dim3((unsigned)((T + G_BM - 1) / G_BM)), dim3(G_THREADS), lds_bytes, stream,
                        (const unsigned char*)x, (const unsigned char*)Wg, gate_bias, T, H, E, k, logits, topk_expert,
                        topk_weight, route_counts);
@@ -366,6 +372,17 @@ hipError_t launch_gate_fused_s(const void* x, const void* Wg, const float* gate_
 }
 
 }  // namespace
+
+hipError_t prepare_gate_fused() {
+    hipError_t e = prepare_gate_fused_t<F32, 64>();
+    if (e == hipSuccess) e = prepare_gate_fused_t<F32, 128>();
+    if (e == hipSuccess) e = prepare_gate_fused_t<F32, 256>();
+    if (e == hipSuccess) e = prepare_gate_fused_t<BF16, 128>();
+    if (e == hipSuccess) e = prepare_gate_fused_t<BF16, 256>();
+    if (e == hipSuccess) e = prepare_gate_fused_t<F16, 128>();
+    if (e == hipSuccess) e = prepare_gate_fused_t<F16, 256>();
+    return e;
+}
 
 bool gate_fused_eligible(int T, int H, int E, int k, int dtype) {
     const int el = dtype == 0 ? 4 : 2, vec = 16 / el, kt = 128 / el;

@@ -298,13 +298,20 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_kernel(GemmArgs a) 
     }
 }
 
+// the kernel's LDS limit on the current device (once per device)
+template <class S, bool NT, int WM, int WN, int TM, int TN>
+hipError_t prepare_cfg() {
+    static DeviceFlags limit_raised = {};
+    return raise_lds_limit(reinterpret_cast<const void*>(grouped_gemm_kernel<S, NT, WM, WN, TM, TN>),
+                           2 * Cfg<S, NT, WM, WN, TM, TN>::STAGE_BYTES, limit_raised);
+}
+
 template <class S, bool NT, int WM, int WN, int TM, int TN>
 hipError_t launch_cfg(const GemmArgs& a, hipStream_t stream) {
     using C = Cfg<S, NT, WM, WN, TM, TN>;
     auto kernel = grouped_gemm_kernel<S, NT, WM, WN, TM, TN>;
     constexpr int lds_bytes = 2 * C::STAGE_BYTES;
-    static bool limit_raised[kMaxDevices] = {};
-    if (hipError_t e = raise_lds_limit(reinterpret_cast<const void*>(kernel), lds_bytes, limit_raised); e != hipSuccess) return e;
+    if (hipError_t e = prepare_cfg<S, NT, WM, WN, TM, TN>(); e != hipSuccess) return e;
     const long long ncol = (a.N + C::BN - 1) / C::BN;
     const long long nrow = (a.max_rows + C::BM - 1) / C::BM;
     const long long groups = a.groups >= kXcds ? (long long)(a.groups + kXcds - 1) / kXcds * kXcds : a.groups;
@@ -349,7 +356,27 @@ hipError_t launch_t(const GemmArgs& a, hipStream_t stream) {
     return pick == 0 ? launch_cfg<S, false, 2, 4, 4, 2>(a, stream) : launch_cfg<S, false, 2, 2, 2, 2>(a, stream);
 }
 
+template <class S>
+hipError_t prepare_t() {
+    hipError_t e = prepare_cfg<S, true, 2, 4, 4, 2>();
+    if (e == hipSuccess) e = prepare_cfg<S, true, 2, 2, 2, 2>();
+    if (e == hipSuccess) e = prepare_cfg<S, false, 2, 4, 4, 2>();
+    if (e == hipSuccess) e = prepare_cfg<S, false, 2, 2, 2, 2>();
+    if constexpr (S::kBytes == 4) {
+        if (e == hipSuccess) e = prepare_cfg<S, false, 2, 2, 2, 1>();
+        if (e == hipSuccess) e = prepare_cfg<S, false, 1, 4, 2, 1>();
+    }
+    return e;
+}
+
 }  // namespace
+
+hipError_t prepare_grouped_gemm() {
+    hipError_t e = prepare_t<F32>();
+    if (e == hipSuccess) e = prepare_t<BF16>();
+    if (e == hipSuccess) e = prepare_t<F16>();
+    return e;
+}
 
 hipError_t launch_grouped_gemm(const GemmArgs& a, hipStream_t stream) {
     if (a.groups <= 0 || a.max_rows <= 0 || a.N <= 0) return hipSuccess;

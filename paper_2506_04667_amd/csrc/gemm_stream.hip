@@ -60,7 +60,6 @@ namespace {
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
-constexpr int kXcds = 8;
 constexpr int BN = 256, BK = 32, THREADS = 512;
 constexpr int TN = 4, WN = 4;                           // 16-column MFMA tiles per wavefront; wavefronts along N
 // Row tile: 128 G rows, G = 2 (the design above) or G = 1 (wavefronts hold 64 x 64: half the MFMAs and half
@@ -101,10 +100,8 @@ struct WFrags { u32x4 w[TN]; };
 struct XFrags { u32x4 x[4]; };                          // four row tiles of 16
 
 struct Task {                                           // wave-uniform description of one output tile
-    int ph;                                             // 0: first GEMM of the kernel's work, 1: the dependent second one
     int unit;                                           // index in the list of live units
     int grp, row0, n0, rows;
-    int nk;                                             // K-tiles
 };
 
 // One GEMM of the expert FFN: C[g] = act(A[g] B[g] + bias[g]) over the live rows of every group (16-bit storage).
@@ -123,28 +120,21 @@ struct StreamArgs {
     const int32_t* rows_dev; int rows_cap; int max_rows;
     int32_t* lists;                                     // the scratch block with the two unit lists (see build_ffn_units)
     int groups;
+    int wait_target;                                    // NPH == 2: count a unit's completion counter must reach before its ph[1] tasks start
+    int spin_limit;                                     // NPH == 2: polls (about 100 ns apart) before a dependency wait gives up
 };
 
-constexpr int kSpinLimit = 1 << 21;                     // polls (about 100 ns apart) before a dependency wait gives up
+constexpr int kSpinLimit = 1 << 21;
 
-#define PHF(t, f) ((NPH == 2 && (t).ph) ? a.ph[1].f : a.ph[0].f)
-
-// The units of a list that XCD `xcd` works on: unit0, unit0 + unit_step, ... (ux of them).  Every 8th unit
-// when an expert has at most one unit in the list (always so for the small tiles), else a contiguous block.
-template <int G>
-__device__ __forceinline__ void xcd_share(int n_units, int nrow, int xcd, int& unit0, int& unit_step, int& ux) {
-    const bool blocks = G == 2 && nrow > 1;
-    unit0 = blocks ? (int)((long long)n_units * xcd / kXcds) : xcd;
-    unit_step = blocks ? 1 : kXcds;
-    ux = blocks ? (int)((long long)n_units * (xcd + 1) / kXcds) - unit0
-                : (n_units > xcd ? (n_units - xcd + kXcds - 1) / kXcds : 0);
-}
-
-// The work of one workgroup on one list: `list` = { fault word, number of live units, ids[cap], completion
-// counters[cap] }; the workgroup is number wg_local of the wg_stride workgroups of XCD `xcd` that walk this list.
-template <class S, int ACT0, int NPH, int G>
+// The work of one workgroup on one list for one GEMM (phase PH of the arguments, activation ACT): `list` =
+// { fault word, number of live units, ids[cap], completion counters[cap] }; the workgroup is number wg_local of
+// the wg_stride workgroups of XCD `xcd` that walk this list.  COUNT: after storing a tile every wavefront adds
+// one to its unit's completion counter.  WAIT: before the first copy of a task is requested, its unit's counter
+// must have reached a.wait_target (the tiles this task reads are then in the XCD's L2).
+template <class S, int ACT, int PH, bool COUNT, bool WAIT, int G>
 __device__ __forceinline__ void stream_body(const StreamArgs& a, int32_t* list, int cap, int xcd, int wg_local, int wg_stride) {
     typedef uint16_t elem;
+    const StreamPhase& P = a.ph[PH];
     int32_t* const fault = list;
     const int32_t* const units = list + 1;              // [0] = live units, [1 + q] = group * nrow + row tile
     int32_t* const done = list + 2 + cap;               // [q] wavefronts that have stored a ph[0] tile of unit q; zero at launch
@@ -153,86 +143,63 @@ __device__ __forceinline__ void stream_body(const StreamArgs& a, int32_t* list, 
     static_assert(BM == (G == 2 ? kUnitRowsLarge : kUnitRowsSmall), "the unit list is cut in row tiles of this kernel");
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
-    const int ncol0 = (a.ph[0].N + BN - 1) / BN, ncol1 = NPH == 2 ? (a.ph[1].N + BN - 1) / BN : 0;
-    const int nk0 = a.ph[0].K / BK, nk1 = NPH == 2 ? a.ph[1].K / BK : 0;       // K-tiles per task (even, >= 6)
+    const int ncol = (P.N + BN - 1) / BN;
+    const int nk = P.K / BK;                            // K-tiles per task (even, >= 6)
     const int nrow = (a.max_rows + BM - 1) / BM;
 
-    // Work is the compact list of live (expert, row tile) units, each one task per column tile (and per
-    // phase).  Each XCD (workgroup ids go round-robin to the 8 XCDs, each with its own L2) takes an equal share
-    // of the list, to within one unit whatever the routing skew: the column tiles of a unit run on one XCD at
-    // about the same time and share its activation rows through that L2.  When experts can have several row
-    // tiles the share is a contiguous block of the list: the row tiles of an expert are neighbours there, so
-    // they run on the same XCD at the same time and share the expert's weight panels through that L2 as well
-    // (E = 16 at 16K tokens: FFN 0.513 -> 0.455 ms).  With at most one unit per expert the share is every 8th
-    // unit, which measured 1.5 % faster than blocks at E = 128 (neighbouring experts' weights, 8 MB apart,
-    // stream at the same time instead of regions 128 MB apart).
-    // Inside an XCD the task sequence is dealt round-robin to its workgroups.  With two phases the
-    // sequence of an XCD with ux units is, for step s = 0 .. ux + lag - 1: the ph[0] tasks of unit s (if
-    // s < ux), then the ph[1] tasks of unit s - lag (if s >= lag).  Every task a ph[1] task waits for comes
-    // earlier in the sequence, and each workgroup walks its share in order, so with all workgroups resident
-    // (one per CU, never more workgroups than CUs) the waits cannot deadlock; `lag` is chosen so that the
-    // producers finished rounds earlier and the waits normally do not spin at all.
+    // Work is the compact list of live (expert, row tile) units, each one task per column tile.  Each XCD
+    // (workgroup ids go round-robin to the 8 XCDs, each with its own L2) takes an equal share of the list, to
+    // within one unit whatever the routing skew: the column tiles of a unit run on one XCD at about the same
+    // time and share its activation rows through that L2.  When experts can have several row tiles the share is
+    // a contiguous block of the list: the row tiles of an expert are neighbours there, so they run on the same
+    // XCD at the same time and share the expert's weight panels through that L2 as well (E = 16 at 16K tokens:
+    // FFN 0.513 -> 0.455 ms).  With at most one unit per expert the share is every 8th unit, which measured
+    // 1.5 % faster than blocks at E = 128 (neighbouring experts' weights, 8 MB apart, stream at the same time
+    // instead of regions 128 MB apart).  Inside an XCD the tasks, in order of unit and column tile, are dealt
+    // round-robin to its workgroups.
     const int n_units = uniform(units[0]);
     int unit0, unit_step, ux;
-    xcd_share<G>(n_units, nrow, xcd, unit0, unit_step, ux);
-    const int xcd_tasks = ux * (ncol0 + ncol1);
+    ffn_xcd_share(G == 2, n_units, nrow, xcd, unit0, unit_step, ux);
+    const int xcd_tasks = ux * ncol;
     if (wg_local >= xcd_tasks) return;
-    // a unit's second-GEMM tasks come `lag` units after its first-GEMM tasks: about four rounds of the
-    // workgroups, so that the tiles they wait for were stored rounds ago
-    const int lag = max((4 * wg_stride + ncol0 + ncol1 - 1) / (ncol0 + ncol1), 1);
-    const int head_units = min(lag, ux), mid_units = max(ux - lag, 0);
-    const int head = head_units * ncol0, mid = mid_units * (ncol0 + ncol1);
-    // position p of the XCD's sequence -> phase, unit index inside the XCD, column tile (arithmetic only)
-    auto decode = [&](int p, int& ph, int& ui, int& ct) __attribute__((always_inline)) {
-        if (NPH == 1 || p < head) {
-            ph = 0; ui = p / ncol0; ct = p % ncol0;
-        } else if (p < head + mid) {
-            const int q = p - head, s = q / (ncol0 + ncol1), r = q % (ncol0 + ncol1);
-            if (r < ncol0) { ph = 0; ui = lag + s; ct = r; }
-            else { ph = 1; ui = s; ct = r - ncol0; }
-        } else {
-            const int q = p - head - mid;
-            ph = 1; ui = mid_units + q / ncol1; ct = q % ncol1;
-        }
-    };
     // The unit and the live row count of this workgroup's tasks are fetched 64 tasks at a time, one task per
     // lane, so that moving on to the next task costs two lane reads, not two dependent trips to memory.
     int info_unit = 0, info_rows = 0;                   // of this workgroup's task number j0 + lane
     auto load_task_info = [&](int j0) __attribute__((always_inline)) {
         const int p = wg_local + (j0 + (int)(threadIdx.x & 63)) * wg_stride;
         if (p < xcd_tasks) {
-            int ph, ui, ct;
-            decode(p, ph, ui, ct);
-            info_unit = units[1 + unit0 + ui * unit_step];
+            int li, ct;
+            ffn_task_at(p, ncol, unit0, unit_step, li, ct);
+            info_unit = units[1 + li];
             info_rows = min(a.rows_dev[info_unit / nrow], a.rows_cap);
         }
     };
     // task number j of this workgroup, at position p = wg_local + j * wg_stride < xcd_tasks
     auto task_at = [&](int j, int p, Task& t) __attribute__((always_inline)) {
-        int ph, ui, ct;
-        decode(p, ph, ui, ct);
-        t.ph = uniform(ph);
-        t.unit = uniform(unit0 + ui * unit_step);
+        int li, ct;
+        ffn_task_at(p, ncol, unit0, unit_step, li, ct);
+        t.unit = uniform(li);
         const int unit = __builtin_amdgcn_readlane(info_unit, j & 63);
         t.grp = uniform(unit / nrow);
         t.row0 = uniform((unit % nrow) * BM);
         t.n0 = uniform(ct * BN);
         t.rows = __builtin_amdgcn_readlane(info_rows, j & 63);
-        t.nk = t.ph ? nk1 : nk0;
     };
-    // A ph[1] task reads what the ph[0] tasks of its unit stored: wait until all of them (8 wavefronts per
-    // column tile) have signalled.  The poll is bounded: if it ever gave up, the fault word says so.
+    // A second-GEMM task reads what the first-GEMM tasks of its unit stored: wait until all of them (8
+    // wavefronts per column tile) have signalled.  First-GEMM tasks never wait, and a workgroup starts on its
+    // second-GEMM tasks only after storing all its first-GEMM tiles, so every counter reaches its target
+    // whatever the order in which workgroups run; the poll is bounded all the same (a kernel of another stream
+    // may hold CUs this launch needs), and a wait that gives up sets the fault word.
     // Producer and consumer run on the same XCD and meet in its L2: the producer's stores are acknowledged
     // by that L2 (vmcnt) before it counts, the counter lives beyond the CU caches (device-scope atomics), and
     // the consumer has never read those lines before, so no cache write-back or invalidate is needed -- an
     // agent-scope release/acquire pair would write back and invalidate the whole L2 on every task.
     auto wait_for_unit = [&](const Task& t) __attribute__((always_inline)) {
-        if (NPH == 2 && t.ph == 1) {
-            const int need = ncol0 * (THREADS / 64);
+        if (WAIT) {
             int spins = 0;
-            while (__hip_atomic_load(done + t.unit, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < need) {
-                if (++spins > kSpinLimit) {
-                    if (threadIdx.x == 0) __hip_atomic_store(fault, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            while (__hip_atomic_load(done + t.unit, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < a.wait_target) {
+                if (++spins > a.spin_limit) {
+                    if (threadIdx.x == 0) __hip_atomic_fetch_or(fault, kFaultWaitGaveUp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     break;
                 }
                 __builtin_amdgcn_s_sleep(4);
@@ -240,13 +207,7 @@ __device__ __forceinline__ void stream_body(const StreamArgs& a, int32_t* list, 
             asm volatile("" ::: "memory");
         }
     };
-    int U = 0;                                          // K-tiles in this workgroup's whole stream
-    for (int p = wg_local; p < xcd_tasks; p += wg_stride) {
-        int ph, ui, ct;
-        decode(p, ph, ui, ct);
-        U += ph ? nk1 : nk0;
-    }
-    U = uniform(U);
+    const int U = uniform(((xcd_tasks - wg_local + wg_stride - 1) / wg_stride) * nk);   // K-tiles in this workgroup's whole stream
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -256,18 +217,18 @@ __device__ __forceinline__ void stream_body(const StreamArgs& a, int32_t* list, 
     // ---- addresses of this wavefront's 1 KB copies, per task: uniform base + per-lane byte offset ----
     // activations: 2 G copies of 8 rows x 128 B per K-tile pair; weights: 2 copies of 2 k-rows x 512 B per K-tile
     auto task_bases = [&](const Task& t, const unsigned char*& base_a, const unsigned char*& base_b) __attribute__((always_inline)) {
-        base_a = uniform((const unsigned char*)((const elem*)PHF(t, A) + (PHF(t, a_row_index) ? (size_t)0 : (size_t)t.grp * PHF(t, a_group_stride))));
-        base_b = uniform((const unsigned char*)((const elem*)PHF(t, B) + (size_t)t.grp * PHF(t, b_group_stride)));
+        base_a = uniform((const unsigned char*)((const elem*)P.A + (P.a_row_index ? (size_t)0 : (size_t)t.grp * P.a_group_stride)));
+        base_b = uniform((const unsigned char*)((const elem*)P.B + (size_t)t.grp * P.b_group_stride));
     };
     auto task_offsets = [&](const Task& t, uint32_t (&oa)[4], uint32_t (&ob)[2]) __attribute__((always_inline)) {
-        const int32_t* row_index = PHF(t, a_row_index);
-        const int lda = PHF(t, lda), ldb = PHF(t, ldb), N = PHF(t, N);
+        const int32_t* row_index = P.a_row_index;
+        const int lda = P.lda, ldb = P.ldb, N = P.N;
 #pragma unroll
         for (int j = 0; j < A_COPIES; ++j) {
             const int r = (wave * A_COPIES + j) * 8 + (lane >> 3), p = lane & 7;
             const int c = p ^ ((r >> 1) & 7);
             int grow = min(t.row0 + r, t.rows - 1);
-            if (row_index) grow = row_index[(size_t)t.grp * PHF(t, a_index_stride) + grow];
+            if (row_index) grow = row_index[(size_t)t.grp * P.a_index_stride + grow];
             oa[j] = (uint32_t)grow * (uint32_t)(lda * 2) + c * 16;
         }
 #pragma unroll
@@ -304,8 +265,8 @@ __device__ __forceinline__ void stream_body(const StreamArgs& a, int32_t* list, 
 #pragma unroll
         for (int j = 0; j < 2; ++j) nb_off[j] = b_off[j];
     }
-    int a_left = cur.nk / 2, b_left = cur.nk;           // requests left before a cursor moves to the next task
-    size_t b_step = (size_t)BK * PHF(cur, ldb) * 2;     // bytes between K-tiles of the weights the cursor is in
+    int a_left = nk / 2, b_left = nk;                   // requests left before a cursor moves to the next task
+    const size_t b_step = (size_t)BK * P.ldb * 2;       // bytes between K-tiles of the weights
     const uint32_t lds_base = (uint32_t)(size_t)(__attribute__((address_space(3))) unsigned char*)smem;
     const uint32_t lds_a_wave = lds_base + wave * (A_COPIES * 1024);
     const uint32_t lds_b_wave = lds_base + B_REGION + wave * 2048;
@@ -316,7 +277,7 @@ __device__ __forceinline__ void stream_body(const StreamArgs& a, int32_t* list, 
 #pragma unroll
         for (int j = 0; j < A_COPIES; ++j) copy_to_lds(a_base, a_off[j], d + j * 1024);
         if (--a_left == 0) {
-            a_left = nxt.nk / 2;
+            a_left = nk / 2;
             a_base = na_base;
 #pragma unroll
             for (int j = 0; j < A_COPIES; ++j) a_off[j] = na_off[j];
@@ -330,8 +291,7 @@ __device__ __forceinline__ void stream_body(const StreamArgs& a, int32_t* list, 
         copy_to_lds_stream(b_base, b_off[0], d);
         copy_to_lds_stream(b_base, b_off[1], d + 1024);
         if (--b_left == 0) {
-            b_left = nxt.nk;
-            b_step = (size_t)BK * PHF(nxt, ldb) * 2;
+            b_left = nk;
             b_base = nb_base;
             b_off[0] = nb_off[0]; b_off[1] = nb_off[1];
         } else {
@@ -383,14 +343,12 @@ __device__ __forceinline__ void stream_body(const StreamArgs& a, int32_t* list, 
 
     // ---- epilogue of task `cur`: bias, activation, conversion, transposed store; then advance to the next task ----
     unsigned char* epi = smem + EPI_REGION + wave * EPI_BYTES_PER_WAVE;   // [32 rows][64 columns], 128 B pitch
-    auto store_tile = [&](auto act_tag, auto ph_tag) __attribute__((always_inline)) {
-        constexpr int ACT = decltype(act_tag)::value, PH = decltype(ph_tag)::value;
+    auto store_tile = [&]() __attribute__((always_inline)) {
         // the lane number as the epilogue sees it: opaque to the compiler, so that the address arithmetic below
         // is done here and not kept in registers across the main loop
         int lane_e = lane;
         asm volatile("" : "+v"(lane_e));
         const int r16 = lane_e & 15, kq = lane_e >> 4;
-        const StreamPhase& P = a.ph[PH];
         const int N = P.N;
         const int col_w = cur.n0 + wn * (TN * 16);      // first column of this wavefront
         const size_t c_base = (size_t)cur.grp * P.c_group_stride;
@@ -450,15 +408,11 @@ __device__ __forceinline__ void stream_body(const StreamArgs& a, int32_t* list, 
             task_bases(after, na_base, nb_base);
             task_offsets(after, na_off, nb_off);
         }
-        if (NPH == 2 && cur.ph == 1) {
-            store_tile(std::integral_constant<int, 3>{}, std::integral_constant<int, NPH == 2 ? 1 : 0>{});
-        } else {
-            store_tile(std::integral_constant<int, ACT0>{}, std::integral_constant<int, 0>{});
-            if (NPH == 2) {
-                // this wavefront's part of the tile has reached the XCD's L2 before it is counted
-                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-                if (lane == 0) __hip_atomic_fetch_add(done + cur.unit, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            }
+        store_tile();
+        if (COUNT) {
+            // this wavefront's part of the tile has reached the XCD's L2 before it is counted
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            if (lane == 0) __hip_atomic_fetch_add(done + cur.unit, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
         cur = nxt;
         nxt = after;
@@ -568,7 +522,7 @@ __device__ __forceinline__ void stream_body(const StreamArgs& a, int32_t* list, 
             __builtin_amdgcn_sched_barrier(0);
         }
         k_done += 2;
-        if (k_done == cur.nk) {
+        if (k_done == nk) {
             k_done = 0;
             finish_task();
             __builtin_amdgcn_sched_barrier(0);
@@ -584,23 +538,50 @@ __device__ __forceinline__ void stream_body(const StreamArgs& a, int32_t* list, 
 // share of the small-tile tasks; nothing separates the two parts but a workgroup barrier, so workgroups with
 // few or no large tiles start on the small ones at once.  The small-tile tasks are dealt starting with the
 // workgroup after the one that got the XCD's last large-tile task, which evens out the counts.
-template <class S, int ACT0, int NPH>
-__global__ __launch_bounds__(THREADS) void ffn_gemm_stream_kernel(StreamArgs a) {
-    const int xcd = blockIdx.x % kXcds, wg = blockIdx.x / kXcds, wgs = gridDim.x / kXcds;
+// NPH == 2 (both FFN GEMMs in one launch): the workgroup then walks its second-GEMM tasks the same way, each
+// waiting for its unit's first-GEMM tiles.  Since no workgroup waits for anything before all its own first-GEMM
+// tiles are stored, the waits always end (see wait_for_unit).
+template <class S, int ACT0, int PH, bool COUNT, bool WAIT>
+__device__ __forceinline__ void stream_gemm(const StreamArgs& a, int xcd, int wg, int wgs) {
     const int nrow_l = ffn_units_nrow_large(a.max_rows), nrow_s = ffn_units_nrow_small(a.max_rows);
     int32_t* const list_l = a.lists;
     int32_t* const list_s = a.lists + ffn_units_small_offset(a.groups, a.max_rows);
     const int n_l = nrow_l ? uniform(list_l[1]) : 0, n_s = uniform(list_s[1]);
     int unit0, unit_step, ux_l, ux_s;
-    xcd_share<2>(n_l, nrow_l, xcd, unit0, unit_step, ux_l);
-    xcd_share<1>(n_s, nrow_s, xcd, unit0, unit_step, ux_s);
-    if (ux_l > 0) stream_body<S, ACT0, NPH, 2>(a, list_l, a.groups * nrow_l, xcd, wg, wgs);
+    ffn_xcd_share(true, n_l, nrow_l, xcd, unit0, unit_step, ux_l);
+    ffn_xcd_share(false, n_s, nrow_s, xcd, unit0, unit_step, ux_s);
+    if (ux_l > 0) stream_body<S, ACT0, PH, COUNT, WAIT, 2>(a, list_l, a.groups * nrow_l, xcd, wg, wgs);
     if (ux_s > 0) {
         if (ux_l > 0) __syncthreads();                  // every wavefront is done with the LDS stages of the first part
-        const int ncol = (a.ph[0].N + BN - 1) / BN + (NPH == 2 ? (a.ph[1].N + BN - 1) / BN : 0);
-        int wg_s = wg - (int)(((long long)ux_l * ncol) % wgs);
-        if (wg_s < 0) wg_s += wgs;
-        stream_body<S, ACT0, NPH, 1>(a, list_s, a.groups, xcd, wg_s, wgs);
+        const int wg_s = ffn_small_list_rotation(wg, wgs, ux_l, (a.ph[PH].N + BN - 1) / BN);
+        stream_body<S, ACT0, PH, COUNT, WAIT, 1>(a, list_s, a.groups, xcd, wg_s, wgs);
+    }
+}
+
+template <class S, int ACT0, int NPH>
+__global__ __launch_bounds__(THREADS) void ffn_gemm_stream_kernel(StreamArgs a) {
+    const int xcd = blockIdx.x % kXcds, wg = blockIdx.x / kXcds, wgs = gridDim.x / kXcds;
+    if constexpr (NPH == 1) {
+        stream_gemm<S, ACT0, 0, false, false>(a, xcd, wg, wgs);
+    } else {
+        // Producer and consumer tiles of a unit meet in one XCD's L2, which holds only if the workgroups with
+        // the same blockIdx % 8 really share an XCD.  Each workgroup records the hardware XCD it runs on
+        // (XCC_ID, bits 3:0 of that hardware register) in its class's placement word; a second, different value
+        // sets the fault word (the results may then be stale and the caller is told so).
+        if (threadIdx.x == 0) {
+            int32_t* const placement = a.lists + ffn_units_placement_offset(a.groups, a.max_rows);
+            int32_t* const fault = a.lists + ffn_units_small_offset(a.groups, a.max_rows);
+            uint32_t xcc;
+            asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
+            const int mine = (int)(xcc & 15u);
+            int expected = -1;
+            if (!__hip_atomic_compare_exchange_strong(placement + xcd, &expected, mine, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
+                                                      __HIP_MEMORY_SCOPE_AGENT) && expected != mine)
+                __hip_atomic_fetch_or(fault, kFaultPlacement, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        stream_gemm<S, ACT0, 0, true, false>(a, xcd, wg, wgs);
+        __syncthreads();
+        stream_gemm<S, 3, 1, false, true>(a, xcd, wg, wgs);
     }
 }
 
@@ -621,17 +602,24 @@ StreamPhase to_phase(const GemmArgs& g) {
     return p;
 }
 
+// the kernel's LDS limit on the current device (once per device)
+template <class S, int ACT0, int NPH>
+hipError_t prepare_stream_t() {
+    static DeviceFlags limit_raised = {};
+    return raise_lds_limit(reinterpret_cast<const void*>(ffn_gemm_stream_kernel<S, ACT0, NPH>), LDS_BYTES, limit_raised);
+}
+
 // g2 == nullptr: one GEMM.  Otherwise g2's A is g1's C and both share rows/groups/units.
 template <class S, int ACT0, int NPH>
-hipError_t launch_stream_t(const GemmArgs& g1, const GemmArgs* g2, hipStream_t stream) {
+hipError_t launch_stream_t(const GemmArgs& g1, const GemmArgs* g2, bool never_met, hipStream_t stream) {
     auto kernel = ffn_gemm_stream_kernel<S, ACT0, NPH>;
-    static bool limit_raised[kMaxDevices] = {};
-    if (hipError_t e = raise_lds_limit(reinterpret_cast<const void*>(kernel), LDS_BYTES, limit_raised); e != hipSuccess) return e;
+    if (hipError_t e = prepare_stream_t<S, ACT0, NPH>(); e != hipSuccess) return e;
     // units the lists can hold: every large row tile of every group, and one small tile per group
     const int nrow_l = ffn_units_nrow_large(g1.max_rows);
     const long long cap = (long long)g1.groups * (nrow_l + 1);
-    const long long ncol = (g1.N + BN - 1) / BN + (g2 ? (g2->N + BN - 1) / BN : 0);
-    const long long total = cap * ncol;                                   // upper bound of the live tasks
+    const long long ncol0 = (g1.N + BN - 1) / BN, ncol1 = g2 ? (g2->N + BN - 1) / BN : 0;
+    const long long ncol = ncol0 > ncol1 ? ncol0 : ncol1;
+    const long long total = cap * ncol;                                   // upper bound of the live tasks of a GEMM
     if ((long long)g1.groups * ffn_units_nrow_small(g1.max_rows) > 0x7fffffffLL / (ncol > kXcds ? ncol : kXcds))
         return hipErrorInvalidValue;
     // one persistent workgroup per CU, the same number on every XCD, never more workgroups than CUs
@@ -645,32 +633,54 @@ hipError_t launch_stream_t(const GemmArgs& g1, const GemmArgs* g2, hipStream_t s
     a.rows_dev = g1.rows_dev; a.rows_cap = g1.rows_cap; a.max_rows = g1.max_rows;
     a.lists = const_cast<int32_t*>(g1.units);
     a.groups = g1.groups;
+    // every wavefront of every first-GEMM column tile of a unit counts once
+    a.wait_target = never_met ? 0x7fffffff : (int)ncol0 * (THREADS / 64);
+    a.spin_limit = never_met ? 16 : kSpinLimit;
     hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(THREADS), LDS_BYTES, stream, a);
     return hipGetLastError();
 }
 
 template <class S, int NPH>
-hipError_t launch_stream_act(const GemmArgs& g1, const GemmArgs* g2, hipStream_t stream) {
+hipError_t launch_stream_act(const GemmArgs& g1, const GemmArgs* g2, bool never_met, hipStream_t stream) {
     switch (g1.act) {
-        case 0: return launch_stream_t<S, 0, NPH>(g1, g2, stream);
-        case 1: return launch_stream_t<S, 1, NPH>(g1, g2, stream);
-        case 2: return launch_stream_t<S, 2, NPH>(g1, g2, stream);
-        default: return launch_stream_t<S, 3, NPH>(g1, g2, stream);
+        case 0: return launch_stream_t<S, 0, NPH>(g1, g2, never_met, stream);
+        case 1: return launch_stream_t<S, 1, NPH>(g1, g2, never_met, stream);
+        case 2: return launch_stream_t<S, 2, NPH>(g1, g2, never_met, stream);
+        default: return launch_stream_t<S, 3, NPH>(g1, g2, never_met, stream);
     }
+}
+
+template <class S>
+hipError_t prepare_stream_s() {
+    hipError_t e = hipSuccess;
+    if (e == hipSuccess) e = prepare_stream_t<S, 0, 1>();
+    if (e == hipSuccess) e = prepare_stream_t<S, 1, 1>();
+    if (e == hipSuccess) e = prepare_stream_t<S, 2, 1>();
+    if (e == hipSuccess) e = prepare_stream_t<S, 3, 1>();
+    if (e == hipSuccess) e = prepare_stream_t<S, 0, 2>();
+    if (e == hipSuccess) e = prepare_stream_t<S, 1, 2>();
+    if (e == hipSuccess) e = prepare_stream_t<S, 2, 2>();
+    if (e == hipSuccess) e = prepare_stream_t<S, 3, 2>();
+    return e;
 }
 
 }  // namespace
 
 int device_cu_count() {
-    static int cus[kMaxDevices] = {};
+    static std::atomic<int> cus[kMaxDevices] = {};
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return 256;
-    if (cus[dev] == 0) {
-        int n = 0;
+    int n = cus[dev].load(std::memory_order_relaxed);
+    if (n == 0) {
         if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
-        cus[dev] = n;
+        cus[dev].store(n, std::memory_order_relaxed);
     }
-    return cus[dev];
+    return n;
+}
+
+hipError_t prepare_grouped_gemm_stream() {
+    const hipError_t e = prepare_stream_s<BF16>();
+    return e != hipSuccess ? e : prepare_stream_s<F16>();
 }
 
 size_t ffn_units_ints(int groups, int max_rows) { return (size_t)ffn_units_total_ints(groups, max_rows); }
@@ -681,16 +691,25 @@ hipError_t launch_ffn_units(const int32_t* rows_dev, int rows_cap, int groups, i
     return hipGetLastError();
 }
 
-bool stream_gemm_eligible(const GemmArgs& a) {
-    return a.dtype != 0 && !a.b_is_nk && !a.c_f32 && a.rows_dev != nullptr && a.units != nullptr && a.K % (2 * BK) == 0 &&
-           a.K >= 6 * BK && a.N % 8 == 0 && a.N >= 256 && a.lda % 8 == 0 && a.ldb % 8 == 0 &&
-           a.ldc % 8 == 0 &&
+void ffn_units_fault_words(int groups, int max_rows, long long* first, long long* second) {
+    *second = ffn_units_small_offset(groups, max_rows);
+    *first = ffn_units_nrow_large(max_rows) ? 0 : *second;
+}
+
+bool stream_gemm_shape_ok(int dtype, int N, int K, int lda, int ldb, int ldc, long long a_rows_total) {
+    return dtype != 0 && K % (2 * BK) == 0 && K >= 6 * BK && N % 8 == 0 && N >= 256 && lda % 8 == 0 && ldb % 8 == 0 &&
+           ldc % 8 == 0 &&
            // copies address an operand as a 64-bit base plus 32-bit byte offsets
-           (long long)a.a_rows_total * a.lda * 2 < (1ll << 32) && (long long)a.K * a.ldb * 2 < (1ll << 32);
+           a_rows_total * lda * 2 < (1ll << 32) && (long long)K * ldb * 2 < (1ll << 32);
+}
+
+bool stream_gemm_eligible(const GemmArgs& a) {
+    return !a.b_is_nk && !a.c_f32 && a.rows_dev != nullptr && a.units != nullptr &&
+           stream_gemm_shape_ok(a.dtype, a.N, a.K, a.lda, a.ldb, a.ldc, a.a_rows_total);
 }
 
 hipError_t launch_grouped_gemm_stream(const GemmArgs& a, hipStream_t stream) {
-    return a.dtype == 1 ? launch_stream_act<BF16, 1>(a, nullptr, stream) : launch_stream_act<F16, 1>(a, nullptr, stream);
+    return a.dtype == 1 ? launch_stream_act<BF16, 1>(a, nullptr, false, stream) : launch_stream_act<F16, 1>(a, nullptr, false, stream);
 }
 
 bool ffn_fused_eligible(const GemmArgs& g1, const GemmArgs& g2) {
@@ -699,8 +718,8 @@ bool ffn_fused_eligible(const GemmArgs& g1, const GemmArgs& g2) {
            g1.groups == g2.groups && g1.max_rows == g2.max_rows && g1.dtype == g2.dtype;
 }
 
-hipError_t launch_ffn_stream_fused(const GemmArgs& g1, const GemmArgs& g2, hipStream_t stream) {
-    return g1.dtype == 1 ? launch_stream_act<BF16, 2>(g1, &g2, stream) : launch_stream_act<F16, 2>(g1, &g2, stream);
+hipError_t launch_ffn_stream_fused(const GemmArgs& g1, const GemmArgs& g2, bool never_met, hipStream_t stream) {
+    return g1.dtype == 1 ? launch_stream_act<BF16, 2>(g1, &g2, never_met, stream) : launch_stream_act<F16, 2>(g1, &g2, never_met, stream);
 }
 
 }  // namespace moe

@@ -34,12 +34,20 @@ struct GemmArgs {
 };
 hipError_t launch_grouped_gemm(const GemmArgs& a, hipStream_t stream);
 
+// Kernels that use more than 64 KB of LDS have that limit raised per device before their first launch there;
+// the launchers do it on first use, these do it for every instantiation at once (moe_init).
+hipError_t prepare_grouped_gemm();
+hipError_t prepare_grouped_gemm_stream();
+hipError_t prepare_gate_fused();
+
 // compute units of the current device (256 on MI355X)
 int device_cu_count();
 
 // Weight-streaming variant for the 16-bit expert FFN tasks (direct-to-LDS, deep prefetch);
 // launch_grouped_gemm routes eligible shapes to it.
 bool stream_gemm_eligible(const GemmArgs& a);
+// the part of the eligibility that depends on the shape alone
+bool stream_gemm_shape_ok(int dtype, int N, int K, int lda, int ldb, int ldc, long long a_rows_total);
 hipError_t launch_grouped_gemm_stream(const GemmArgs& a, hipStream_t stream);
 // Scratch block of the streaming kernels, written by launch_ffn_units for the same rows_dev / rows_cap / groups /
 // max_rows: for each of the two row-tile sizes (256 and 128 rows) a fault word, the number of live (group, row
@@ -50,8 +58,12 @@ hipError_t launch_ffn_units(const int32_t* rows_dev, int rows_cap, int groups, i
                             hipStream_t stream);
 // Both FFN GEMMs in one persistent launch: a unit's second-GEMM tasks start when all its first-GEMM tiles are
 // stored (g2.A is g1.C).  Eligible when both GEMMs are and they share rows, groups and units.
+// never_met: the dependency waits get a target no counter reaches and a poll limit of 16, so that every
+// second-GEMM task gives up at once and the fault word is set (exercises the give-up path; y is then garbage).
 bool ffn_fused_eligible(const GemmArgs& g1, const GemmArgs& g2);
-hipError_t launch_ffn_stream_fused(const GemmArgs& g1, const GemmArgs& g2, hipStream_t stream);
+hipError_t launch_ffn_stream_fused(const GemmArgs& g1, const GemmArgs& g2, bool never_met, hipStream_t stream);
+// Offsets (in ints) of the scratch block's two fault words (equal when there is no large-tile list).
+void ffn_units_fault_words(int groups, int max_rows, long long* first, long long* second);
 
 // WgT[n][h] = Wg[h][n] for n < E, zero rows for E <= n < E_pad.
 hipError_t launch_transpose_pad(const void* Wg, void* WgT, int H, int E, int E_pad, int dtype,

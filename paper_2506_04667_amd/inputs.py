@@ -39,6 +39,7 @@ class MoEWorkload:
     capacity_override: int = 0
     drop_policy: str = "token_major"  # or "choice_major": who keeps a slot on overflow
     capacity_mode: str = "per_choice" # or "layout": capacity factor scales k T / E, or T / E
+    flags: int = 0                    # moe_config.flags (launch options of the HIP library; the oracle ignores them)
 
 
 WORKLOADS = {

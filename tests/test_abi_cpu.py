@@ -73,6 +73,7 @@ def test_workspace_covers_the_per_expert_buffers(lib):
     (dict(capacity_factor=0.0), -1), (dict(capacity_factor=float("nan")), -1), (dict(capacity_override=-1), -1),
     (dict(H=60), -2), (dict(I=100), -2), (dict(E=9000, k=1), -2), (dict(dtype=3), -2), (dict(act=9), -2),
     (dict(drop_policy=2), -2), (dict(drop_policy=-1), -2), (dict(capacity_mode=2), -2), (dict(capacity_mode=-1), -2),
+    (dict(flags=4), -1), (dict(flags=2), -1),                      # unknown bit; the test aid without the single launch
 ])
 def test_invalid_configs_are_rejected(lib, kw, code):
     base = dict(T=128, H=64, I=128, E=4, k=1, capacity_factor=2.0, capacity_override=0, dtype=0, act=0)
@@ -105,7 +106,113 @@ def test_null_and_misaligned_pointers_are_rejected(lib):
 
 def test_status_strings(lib):
     assert moe.moe_status_string(0) == "ok"
-    assert len({moe.moe_status_string(c) for c in (0, -1, -2, -3, -4)}) == 5
+    assert len({moe.moe_status_string(c) for c in (0, -1, -2, -3, -4, -5, -6)}) == 7
+
+
+def test_single_launch_flag_needs_a_shape_the_streaming_kernel_takes(lib):
+    ok = ctypes.c_void_p(4096)
+    for kw, code in [(dict(dtype=0), -2),                          # fp32 storage
+                     (dict(I=200), -2), (dict(H=128), -2),         # I not a multiple of 64; H below 256
+                     (dict(), -3)]:                                # eligible: the next check (workspace size) is reached
+        base = dict(T=512, H=256, I=256, E=4, k=2, capacity_factor=1.0, capacity_override=0, dtype=1, act=2, flags=1)
+        base.update(kw)
+        cfg = moe.MoeConfig(**base)
+        assert lib.moe_forward(ctypes.byref(cfg), ok, 1 << 40 if code != -3 else 16, *([ok] * 14)) == code, kw
+
+
+# ---- dealing of the FFN tasks and the single-launch dependency protocol, replayed on the host -------------
+
+def _programs(n_l, n_s, nrow_l, ncol0, ncol1, wgs, t2_first=False):
+    """Per workgroup (xcd, wg): the operations of the single-launch FFN kernel in program order.
+    ("store", phase, list, index, column tile) | ("wait", list, index)."""
+    progs = {}
+    for xcd in range(8):
+        for wg in range(wgs):
+            ops = []
+            bodies = [(ph, large) for ph in ((1, 0) if t2_first else (0, 1)) for large in (1, 0)]
+            for ph, large in bodies:
+                ncol = ncol1 if ph else ncol0
+                tasks = moe.moe_ffn_schedule(large, n_l, n_s, nrow_l, ncol, xcd, wg, wgs)
+                if not tasks:
+                    continue
+                if ph == 0:                                         # first-GEMM tasks never wait
+                    ops += [("store", 0, large, li, ct) for li, ct in tasks]
+                else:                                               # waits run two tasks ahead of the stores
+                    ops += [("wait", large, li) for li, _ in tasks[:2]]
+                    for j, (li, ct) in enumerate(tasks):
+                        if j + 2 < len(tasks):
+                            ops.append(("wait", large, tasks[j + 2][0]))
+                        ops.append(("store", 1, large, li, ct))
+            progs[(xcd, wg)] = ops
+    return progs
+
+
+def _replay(progs, ncol0, order_seed):
+    """Run the programs under an arbitrary interleaving; returns (stalled, stores in order)."""
+    import random
+    rng = random.Random(order_seed)
+    pc = {w: 0 for w in progs}
+    done = {}
+    log = []
+    live = [w for w in progs if progs[w]]
+    while live:
+        rng.shuffle(live)
+        progress = False
+        for w in list(live):
+            steps = rng.randint(1, 4)
+            while steps and pc[w] < len(progs[w]):
+                op = progs[w][pc[w]]
+                if op[0] == "wait" and done.get((op[1], op[2]), 0) < ncol0:
+                    break
+                if op[0] == "store":
+                    log.append(op[1:])
+                    if op[1] == 0:
+                        done[(op[2], op[3])] = done.get((op[2], op[3]), 0) + 1
+                pc[w] += 1
+                steps -= 1
+                progress = True
+            if pc[w] == len(progs[w]):
+                live.remove(w)
+        if not progress:
+            return True, log
+    return False, log
+
+
+@pytest.mark.parametrize("wgs", [1, 2, 5, 32])
+def test_ffn_tasks_are_dealt_exactly_once_and_single_launch_waits_end(lib, wgs):
+    # the shapes a reviewer's replay of the earlier schedule stalled on are among these: 4 one-tile units per
+    # XCD with 8 + 8 column tiles and 32 workgroups; fewer first-GEMM than second-GEMM column tiles
+    cases = [(0, 32, 0, 8, 8), (16, 0, 1, 8, 8), (128, 0, 1, 8, 8), (0, 32, 0, 1, 8), (0, 32, 0, 2, 8), (0, 32, 0, 16, 8),
+             (40, 7, 3, 3, 5), (1, 1, 2, 1, 1), (5, 33, 1, 8, 2), (0, 0, 0, 4, 4), (14, 53, 2, 8, 8), (9, 3, 4, 2, 16)]
+    for n_l, n_s, nrow_l, ncol0, ncol1 in cases:
+        progs = _programs(n_l, n_s, nrow_l, ncol0, ncol1, wgs)
+        for seed in (0, 1):
+            stalled, log = _replay(progs, ncol0, seed)
+            assert not stalled, (n_l, n_s, nrow_l, ncol0, ncol1, wgs)
+            want = sorted([(ph, large, li, ct) for ph, ncol in ((0, ncol0), (1, ncol1))
+                           for large, n in ((1, n_l), (0, n_s)) for li in range(n) for ct in range(ncol)])
+            assert sorted(log) == want                              # every (phase, unit, column tile) exactly once
+            first_t2 = {}
+            last_t1 = {}
+            for pos, (ph, large, li, ct) in enumerate(log):
+                if ph == 0:
+                    last_t1[(large, li)] = pos
+                else:
+                    first_t2.setdefault((large, li), pos)
+            assert all(first_t2[u] > last_t1[u] for u in first_t2)  # no second-GEMM tile before its unit's first-GEMM tiles
+    # the replay does notice a protocol that cannot make progress: second-GEMM tasks walked first
+    stalled, _ = _replay(_programs(0, 32, 0, 8, 8, wgs, t2_first=True), 8, 0)
+    assert stalled
+
+
+def test_ffn_schedule_balances_the_xcds(lib):
+    # every XCD gets the same number of units to within one, whatever the counts
+    for n_l, n_s, nrow_l in [(14, 53, 2), (128, 0, 1), (3, 5, 7), (0, 1, 0)]:
+        per_xcd = []
+        for xcd in range(8):
+            per_xcd.append(sum(len(moe.moe_ffn_schedule(large, n_l, n_s, nrow_l, 1, xcd, wg, 4)) for large in (1, 0) for wg in range(4)))
+        assert sum(per_xcd) == n_l + n_s and max(per_xcd) - min(per_xcd) <= 2
+    assert lib.moe_ffn_schedule(1, 4, 4, 1, 0, 0, 0, 1, None, None, 0) == -1
 
 
 def test_binding_fails_loudly_without_the_library(tmp_path):
