@@ -98,6 +98,115 @@ double activation(double v, int act) {
     }
 }
 
+// derivative of the activation with respect to its argument
+double activation_grad(double v, int act) {
+    switch (act) {
+        case 0: return v > 0.0 ? 1.0 : 0.0;
+        case 1: {  // d/dv [ v/2 (1 + tanh u) ], u = c (v + 0.044715 v^3)
+            const double c = std::sqrt(2.0 / M_PI);
+            const double t = std::tanh(c * (v + 0.044715 * v * v * v));
+            return 0.5 * (1.0 + t) + 0.5 * v * (1.0 - t * t) * c * (1.0 + 3.0 * 0.044715 * v * v);
+        }
+        case 2:    // d/dv [ v Phi(v) ] = Phi(v) + v pdf(v)
+            return 0.5 * (1.0 + std::erf(v / std::sqrt(2.0))) + v * std::exp(-0.5 * v * v) / std::sqrt(2.0 * M_PI);
+        default: return 1.0;
+    }
+}
+
+// ---- B1..B5: gradients of the layer under a fixed routing (see the header) ----------
+template <class S>
+void backward_t(const void* x, const void* Wg, const float* gate_bias, const void* W1, const void* b1,
+                const void* W2, const void* b2, const int32_t* topk_expert, const int32_t* slot,
+                const double* dout, int T, int H, int I, int E, int k, int act, double* dx, double* dWg,
+                double* dgate_bias, double* dW1, double* db1, double* dW2, double* db2) {
+    const int64_t P = (int64_t)T * k;
+    // B1: combine weights as functions of the logits, in double (softmax over the k selected logits)
+    std::vector<double> w(P);
+    for (int i = 0; i < T; ++i) {
+        std::vector<double> l(k);
+        double m = -INFINITY;
+        for (int j = 0; j < k; ++j) {
+            const int e = topk_expert[(int64_t)i * k + j];
+            double acc = gate_bias ? (double)gate_bias[e] : 0.0;
+            for (int h = 0; h < H; ++h) acc += S::load(x, (int64_t)i * H + h) * S::load(Wg, (int64_t)h * E + e);
+            l[j] = acc;
+            if (acc > m) m = acc;
+        }
+        double z = 0.0;
+        for (int j = 0; j < k; ++j) z += std::exp(l[j] - m);
+        for (int j = 0; j < k; ++j) w[(int64_t)i * k + j] = std::exp(l[j] - m) / z;
+    }
+    std::vector<double> dweight(P, 0.0);                     // dL/dw_ij; stays zero for dropped pairs
+    std::vector<double> dx_pair((size_t)P * H, 0.0);         // the expert path's part of dL/dx_i, per pair
+    // B2 + B3, one expert at a time (an expert's gradients depend on its own kept pairs only)
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int e = 0; e < E; ++e) {
+        std::vector<double> a(I), hh(I), da(I), y(H), gy(H);
+        const int64_t w1 = (int64_t)e * H * I, w2 = (int64_t)e * I * H;
+        for (int i = 0; i < T; ++i)
+            for (int j = 0; j < k; ++j) {
+                const int64_t p = (int64_t)i * k + j;
+                if (topk_expert[p] != e || slot[p] < 0) continue;
+                // forward of this pair: a = x W1 + b1, h = phi(a), y = h W2 + b2
+                for (int q = 0; q < I; ++q) a[q] = b1 ? S::load(b1, (int64_t)e * I + q) : 0.0;
+                for (int h = 0; h < H; ++h) {
+                    const double xv = S::load(x, (int64_t)i * H + h);
+                    for (int q = 0; q < I; ++q) a[q] += xv * S::load(W1, w1 + (int64_t)h * I + q);
+                }
+                for (int q = 0; q < I; ++q) hh[q] = activation(a[q], act);
+                for (int h = 0; h < H; ++h) y[h] = b2 ? S::load(b2, (int64_t)e * H + h) : 0.0;
+                for (int q = 0; q < I; ++q)
+                    for (int h = 0; h < H; ++h) y[h] += hh[q] * S::load(W2, w2 + (int64_t)q * H + h);
+                // out_i = sum_j w_ij y_ij:  dL/dw_ij = <dout_i, y_ij>,  dL/dy_ij = w_ij dout_i
+                double dw = 0.0;
+                for (int h = 0; h < H; ++h) dw += dout[(int64_t)i * H + h] * y[h];
+                dweight[p] = dw;
+                for (int h = 0; h < H; ++h) gy[h] = w[p] * dout[(int64_t)i * H + h];
+                // through y = h W2 + b2
+                if (db2) for (int h = 0; h < H; ++h) db2[(int64_t)e * H + h] += gy[h];
+                for (int q = 0; q < I; ++q) {
+                    double dh = 0.0;
+                    for (int h = 0; h < H; ++h) {
+                        if (dW2) dW2[w2 + (int64_t)q * H + h] += hh[q] * gy[h];
+                        dh += gy[h] * S::load(W2, w2 + (int64_t)q * H + h);
+                    }
+                    da[q] = dh * activation_grad(a[q], act);
+                }
+                // through a = x W1 + b1
+                if (db1) for (int q = 0; q < I; ++q) db1[(int64_t)e * I + q] += da[q];
+                for (int h = 0; h < H; ++h) {
+                    const double xv = S::load(x, (int64_t)i * H + h);
+                    double g = 0.0;
+                    for (int q = 0; q < I; ++q) {
+                        if (dW1) dW1[w1 + (int64_t)h * I + q] += xv * da[q];
+                        g += da[q] * S::load(W1, w1 + (int64_t)h * I + q);
+                    }
+                    dx_pair[(size_t)p * H + h] = g;
+                }
+            }
+    }
+    // B4 + B5, token by token: softmax Jacobian of the gate, then both paths into x
+    for (int i = 0; i < T; ++i) {
+        double mean = 0.0;                                   // sum_j w_ij dL/dw_ij
+        for (int j = 0; j < k; ++j) mean += w[(int64_t)i * k + j] * dweight[(int64_t)i * k + j];
+        if (dx)
+            for (int h = 0; h < H; ++h) {
+                double g = 0.0;
+                for (int j = 0; j < k; ++j) g += dx_pair[((size_t)i * k + j) * H + h];
+                dx[(int64_t)i * H + h] = g;
+            }
+        for (int j = 0; j < k; ++j) {
+            const int e = topk_expert[(int64_t)i * k + j];
+            const double dl = w[(int64_t)i * k + j] * (dweight[(int64_t)i * k + j] - mean);
+            if (dgate_bias) dgate_bias[e] += dl;
+            for (int h = 0; h < H; ++h) {
+                if (dWg) dWg[(int64_t)h * E + e] += S::load(x, (int64_t)i * H + h) * dl;
+                if (dx) dx[(int64_t)i * H + h] += dl * S::load(Wg, (int64_t)h * E + e);
+            }
+        }
+    }
+}
+
 // ---- O6: one expert FFN applied to one token row (Eq. ffn, row-vector reading) -----
 template <class S>
 void ffn_row(const void* x, int64_t token, const void* W1, const void* b1, const void* W2,
@@ -342,6 +451,22 @@ void oracle_ffn_combine(const void* x, const void* W1, const void* b1, const voi
         }
     }
 }
+
+void oracle_backward(const void* x, const void* Wg, const float* gate_bias, const void* W1,
+                     const void* b1, const void* W2, const void* b2, const int32_t* topk_expert,
+                     const int32_t* slot, const double* dout, int32_t T, int32_t H, int32_t I, int32_t E,
+                     int32_t k, int32_t act, int32_t dtype, double* dx, double* dWg, double* dgate_bias,
+                     double* dW1, double* db1, double* dW2, double* db2) {
+    ThreadScope ts;
+    auto zero = [](double* p, int64_t n) { if (p) std::fill(p, p + n, 0.0); };
+    zero(dx, (int64_t)T * H); zero(dWg, (int64_t)H * E); zero(dgate_bias, E);
+    zero(dW1, (int64_t)E * H * I); zero(db1, (int64_t)E * I); zero(dW2, (int64_t)E * I * H); zero(db2, (int64_t)E * H);
+    if (dtype == 0) backward_t<F32>(x, Wg, gate_bias, W1, b1, W2, b2, topk_expert, slot, dout, T, H, I, E, k, act, dx, dWg, dgate_bias, dW1, db1, dW2, db2);
+    else if (dtype == 1) backward_t<BF16>(x, Wg, gate_bias, W1, b1, W2, b2, topk_expert, slot, dout, T, H, I, E, k, act, dx, dWg, dgate_bias, dW1, db1, dW2, db2);
+    else backward_t<F16>(x, Wg, gate_bias, W1, b1, W2, b2, topk_expert, slot, dout, T, H, I, E, k, act, dx, dWg, dgate_bias, dW1, db1, dW2, db2);
+}
+
+double oracle_activation_grad(double v, int32_t act) { return activation_grad(v, act); }
 
 int32_t oracle_forward(const void* x, const void* Wg, const float* gate_bias, const void* W1,
                        const void* b1, const void* W2, const void* b2, int32_t T, int32_t H,

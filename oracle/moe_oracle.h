@@ -144,6 +144,34 @@ int32_t oracle_forward(const void* x, const void* Wg, const float* gate_bias,
                        int32_t* slot_token, float* slot_weight,
                        double* out_f64, void* out);
 
+/* Gradients of the layer (the paper leaves training to future work and states no backward pass; this is
+ * the chain rule applied to O1..O7, i.e. to Eq. ffn and Eqs. combine 1/2, with the reading below).
+ * Reading: the routing -- which k experts a token selected (topk_expert) and which pairs kept a slot (slot) --
+ * is a constant of the differentiation; the combine weights are differentiated as the softmax over the k
+ * selected logits l_ij = x_i Wg[:, e_ij] + gate_bias[e_ij] (every selected logit enters the normalisation,
+ * dropped or not, as in O3); a dropped pair contributes nothing to out, so nothing flows into its expert and
+ * dL/dw_ij = 0.  Everything is evaluated in double on the exactly widened inputs (the float roundings of
+ * O1 and O3 are not differentiable and are not applied).  With L any scalar with dL/dout = dout:
+ *   B1  w_ij   = softmax_j(l_i,.)
+ *   B2  per kept pair: a = x_i W1_e + b1_e, h = phi(a), y = h W2_e + b2_e;
+ *       dL/dw_ij = <dout_i, y>;  gy = w_ij dout_i
+ *   B3  db2_e += gy;  dW2_e += h^T gy;  da = (gy W2_e^T) * phi'(a);  db1_e += da;  dW1_e += x_i^T da;
+ *       dx_i += da W1_e^T
+ *   B4  dl_ij = w_ij (dL/dw_ij - sum_j' w_ij' dL/dw_ij')
+ *   B5  dgate_bias[e_ij] += dl_ij;  dWg[:, e_ij] += x_i dl_ij;  dx_i += dl_ij Wg[:, e_ij]
+ * dout is [T,H] in double.  Every output is in double and may be NULL: dx [T,H], dWg [H,E], dgate_bias [E],
+ * dW1 [E,H,I], db1 [E,I], dW2 [E,I,H], db2 [E,H]. */
+void oracle_backward(const void* x, const void* Wg, const float* gate_bias,
+                     const void* W1, const void* b1, const void* W2, const void* b2,
+                     const int32_t* topk_expert, const int32_t* slot, const double* dout,
+                     int32_t T, int32_t H, int32_t I, int32_t E, int32_t k,
+                     int32_t act, int32_t dtype,
+                     double* dx, double* dWg, double* dgate_bias,
+                     double* dW1, double* db1, double* dW2, double* db2);
+
+/* derivative of the activation, for pins */
+double oracle_activation_grad(double v, int32_t act);
+
 /* storage-dtype helpers (exact widening; round-to-nearest-even narrowing) */
 double oracle_load_elem(const void* p, int64_t idx, int32_t dtype);
 void   oracle_store_elem(void* p, int64_t idx, int32_t dtype, double v);

@@ -86,6 +86,10 @@ class Oracle:
         L.oracle_ffn_rows.argtypes = [vp] * 7 + [i32] * 5 + [vp]
         L.oracle_ffn_combine.restype = None
         L.oracle_ffn_combine.argtypes = [vp] * 8 + [i32] * 7 + [vp, i32, vp, vp]
+        L.oracle_backward.restype = None
+        L.oracle_backward.argtypes = [vp] * 10 + [i32] * 7 + [vp] * 7
+        L.oracle_activation_grad.restype = f64
+        L.oracle_activation_grad.argtypes = [f64, i32]
         L.oracle_forward.restype = i32
         L.oracle_forward.argtypes = [vp] * 7 + [i32] * 5 + [f32, i32, i32, i32] + [vp] * 9
 
@@ -168,6 +172,22 @@ class Oracle:
                                     _ptr(tw), _ptr(sl), T, H, I, E, k, ACT[act], DTYPE[dtype],
                                     _ptr(tok), n, _ptr(out), None)
         return out
+
+    def activation_grad(self, v, act):
+        return self.lib.oracle_activation_grad(float(v), ACT[act])
+
+    def backward(self, x, Wg, gate_bias, W1, b1, W2, b2, topk_expert, slot, dout, T, H, I, E, act, dtype):
+        """Gradients under the given routing; dout is [T, H] float64.  Returns a dict of float64 arrays."""
+        te, sl = _i32(topk_expert), _i32(slot)
+        k = te.shape[1]
+        do = np.ascontiguousarray(np.asarray(dout, dtype=np.float64))
+        gb = None if gate_bias is None else _f32(gate_bias)
+        g = {"dx": np.empty((T, H)), "dWg": np.empty((H, E)), "dgate_bias": np.empty((E,)),
+             "dW1": np.empty((E, H, I)), "db1": np.empty((E, I)), "dW2": np.empty((E, I, H)), "db2": np.empty((E, H))}
+        self.lib.oracle_backward(_ptr(x), _ptr(Wg), _ptr(gb), _ptr(W1), _ptr(b1), _ptr(W2), _ptr(b2), _ptr(te), _ptr(sl),
+                                 _ptr(do), T, H, I, E, k, ACT[act], DTYPE[dtype], _ptr(g["dx"]), _ptr(g["dWg"]),
+                                 _ptr(g["dgate_bias"]), _ptr(g["dW1"]), _ptr(g["db1"]), _ptr(g["dW2"]), _ptr(g["db2"]))
+        return g
 
     def forward(self, x, Wg, gate_bias, W1, b1, W2, b2, T, H, I, E, k, cf, act, dtype,
                 capacity_override=0, compute_out=True):

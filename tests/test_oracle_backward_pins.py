@@ -1,0 +1,159 @@
+"""Pins for the oracle's backward pass (gradients of the layer under a fixed routing, steps B1..B5 of
+``oracle/moe_oracle.h``).  The paper states no backward pass, so there are no printed values to check against;
+the pins are central finite differences of the oracle's own *forward* (which is pinned elsewhere), a dense-FFN
+closed form written with numpy matmuls, and invariants of the softmax gate.  Shapes are asymmetric (H != I,
+biases, k > 1, drops) so that a transposed operand, a dropped term or a wrong index fails one of them."""
+import math
+
+import numpy as np
+import pytest
+
+ACTS = ["relu", "gelu_tanh", "gelu_erf", "identity"]
+
+
+def _draw(T, H, I, E, seed):
+    r = np.random.default_rng(seed)
+    f = lambda *s: r.standard_normal(s).astype(np.float32)
+    return {"x": f(T, H), "Wg": f(H, E) * 0.8, "gate_bias": f(E) * 0.3, "W1": f(E, H, I) / math.sqrt(H), "b1": f(E, I) * 0.2,
+            "W2": f(E, I, H) / math.sqrt(I), "b2": f(E, H) * 0.2}
+
+
+def _forward(oracle, p, T, H, I, E, k, C, act):
+    return oracle.forward(p["x"], p["Wg"], p["gate_bias"], p["W1"], p["b1"], p["W2"], p["b2"], T, H, I, E, k, 1.0, act, "f32",
+                          capacity_override=C)
+
+
+@pytest.mark.parametrize("act", ACTS)
+def test_activation_grad_against_central_differences_and_closed_forms(oracle, act):
+    for v in (-3.1, -1.7, -0.3, 0.4, 1.1, 2.9):
+        e = 1e-5
+        fd = (oracle.activation(v + e, act) - oracle.activation(v - e, act)) / (2 * e)
+        assert abs(oracle.activation_grad(v, act) - fd) < 1e-8, (act, v)
+    if act == "relu":
+        assert oracle.activation_grad(-2.0, act) == 0.0 and oracle.activation_grad(2.0, act) == 1.0
+    if act == "identity":
+        assert oracle.activation_grad(-7.0, act) == 1.0
+    if act in ("gelu_erf", "gelu_tanh"):
+        assert abs(oracle.activation_grad(0.0, act) - 0.5) < 1e-15           # phi'(0) = Phi(0)
+        assert abs(oracle.activation_grad(9.0, act) - 1.0) < 1e-12 and abs(oracle.activation_grad(-9.0, act)) < 1e-12
+
+
+@pytest.mark.parametrize("act", ["gelu_tanh", "gelu_erf", "identity"])
+@pytest.mark.parametrize("group", ["x", "Wg", "gate_bias", "W1", "b1", "W2", "b2"])
+def test_backward_against_finite_differences_of_the_forward(oracle, act, group):
+    # L = <out, G>.  For a random direction D in one parameter group, (L(p + tD) - L(p - tD)) must equal
+    # <grad, (p + tD) - (p - tD)>.  The forward is the whole oracle_forward (gate, routing, drops, FFN, combine);
+    # the step is small enough that no routing decision changes, which the test asserts.
+    T, H, I, E, k, C = 7, 5, 6, 3, 2, 4
+    seed = 5
+    p = _draw(T, H, I, E, seed)
+    G = np.random.default_rng(seed + 1).standard_normal((T, H))
+    base = _forward(oracle, p, T, H, I, E, k, C, act)
+    assert (base["slot"] < 0).any() and (base["slot"] >= 0).any()              # some pairs dropped, most kept
+    g = oracle.backward(p["x"], p["Wg"], p["gate_bias"], p["W1"], p["b1"], p["W2"], p["b2"], base["topk_expert"], base["slot"],
+                        G, T, H, I, E, act, "f32")
+    name = {"x": "dx", "Wg": "dWg", "gate_bias": "dgate_bias", "W1": "dW1", "b1": "db1", "W2": "dW2", "b2": "db2"}[group]
+    D = np.random.default_rng(seed + 2).standard_normal(p[group].shape)
+    t = 2.0 ** -9
+    plus, minus = dict(p), dict(p)
+    plus[group] = (p[group] + t * D).astype(np.float32)
+    minus[group] = (p[group] - t * D).astype(np.float32)
+    fp = _forward(oracle, plus, T, H, I, E, k, C, act)
+    fm = _forward(oracle, minus, T, H, I, E, k, C, act)
+    for r in (fp, fm):
+        np.testing.assert_array_equal(r["topk_expert"], base["topk_expert"])
+        np.testing.assert_array_equal(r["slot"], base["slot"])
+    fd = float(((fp["out"] - fm["out"]) * G).sum())
+    an = float((g[name] * (plus[group].astype(np.float64) - minus[group].astype(np.float64))).sum())
+    # the forward rounds logits and combine weights to float (steps O1, O3): 6e-8 relative noise on L, over a
+    # step of 4e-3; the central difference itself is exact to O(t^2)
+    scale = float(np.abs(g[name]).sum() * t)
+    assert abs(fd - an) <= 2e-3 * abs(an) + 2e-4 * scale + 1e-6, (group, fd, an)
+    assert abs(an) > 1e-4 * scale                                              # the check is not vacuous
+
+
+def test_backward_single_expert_is_the_dense_ffn_closed_form(oracle):
+    # E = 1, k = 1, nothing dropped: w = 1 for every token, the gate gets no gradient, and the rest is the
+    # textbook two-layer perceptron backward written with numpy matmuls
+    T, H, I = 9, 6, 4
+    p = _draw(T, H, I, 1, 11)
+    G = np.random.default_rng(12).standard_normal((T, H))
+    te = np.zeros((T, 1), dtype=np.int32)
+    slot = np.arange(T, dtype=np.int32).reshape(T, 1)
+    g = oracle.backward(p["x"], p["Wg"], p["gate_bias"], p["W1"], p["b1"], p["W2"], p["b2"], te, slot, G, T, H, I, 1, "relu", "f32")
+    x, W1, b1, W2 = (p[n].astype(np.float64) for n in ("x", "W1", "b1", "W2"))
+    a = x @ W1[0] + b1[0]
+    h = np.maximum(a, 0.0)
+    np.testing.assert_allclose(g["dW2"][0], h.T @ G, rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(g["db2"][0], G.sum(0), rtol=1e-12, atol=1e-13)
+    da = (G @ W2[0].T) * (a > 0)
+    np.testing.assert_allclose(g["dW1"][0], x.T @ da, rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(g["db1"][0], da.sum(0), rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(g["dx"], da @ W1[0].T, rtol=1e-12, atol=1e-13)
+    assert np.abs(g["dWg"]).max() < 1e-15 and np.abs(g["dgate_bias"]).max() < 1e-15
+
+
+def test_backward_dropped_pairs_carry_no_gradient(oracle):
+    # capacity 2 with 10 tokens on 3 experts: most pairs are dropped and some tokens lose every choice
+    T, H, I, E, k, C = 10, 4, 5, 3, 2, 2
+    p = _draw(T, H, I, E, 21)
+    G = np.random.default_rng(22).standard_normal((T, H))
+    base = _forward(oracle, p, T, H, I, E, k, C, "gelu_erf")
+    slot, te = base["slot"], base["topk_expert"]
+    all_dropped = (slot < 0).all(axis=1)
+    assert all_dropped.any() and not all_dropped.all()
+    g = oracle.backward(p["x"], p["Wg"], p["gate_bias"], p["W1"], p["b1"], p["W2"], p["b2"], te, slot, G, T, H, I, E, "gelu_erf", "f32")
+    assert (g["dx"][all_dropped] == 0.0).all()                                 # a token with no kept pair reaches nothing
+    assert np.abs(g["dx"][~all_dropped]).min(axis=1).max() > 0.0
+    # an expert's bias gradient is the weighted sum of dout over its kept pairs only (B2, B3)
+    w = base["topk_weight"].astype(np.float64)
+    for e in range(E):
+        want = np.zeros(H)
+        for i in range(T):
+            for j in range(k):
+                if te[i, j] == e and slot[i, j] >= 0:
+                    want += w[i, j] * G[i]
+        np.testing.assert_allclose(g["db2"][e], want, rtol=1e-6, atol=1e-7)    # w here is the float-rounded weight
+    # the same layer with the dropped pairs' experts renamed gives the same expert gradients: a dropped pair's
+    # expert id matters only through the gate's normalisation
+    g2 = oracle.backward(p["x"], p["Wg"], p["gate_bias"], p["W1"], p["b1"], p["W2"], p["b2"], te, np.full_like(slot, -1), G, T, H,
+                         I, E, "gelu_erf", "f32")
+    for n in g2:
+        assert (g2[n] == 0.0).all(), n                                         # nothing kept: every gradient is zero
+
+
+def test_backward_gate_gradient_is_shift_invariant(oracle):
+    # softmax over the selected logits does not change when all logits move together: the gradient with
+    # respect to the logits sums to zero per token, so dgate_bias sums to zero and so does every row of dWg
+    T, H, I, E, k, C = 12, 5, 4, 4, 3, 9
+    p = _draw(T, H, I, E, 31)
+    G = np.random.default_rng(32).standard_normal((T, H))
+    base = _forward(oracle, p, T, H, I, E, k, C, "gelu_tanh")
+    g = oracle.backward(p["x"], p["Wg"], p["gate_bias"], p["W1"], p["b1"], p["W2"], p["b2"], base["topk_expert"], base["slot"], G,
+                        T, H, I, E, "gelu_tanh", "f32")
+    assert np.abs(g["dgate_bias"]).max() > 1e-3
+    assert abs(g["dgate_bias"].sum()) < 1e-12
+    np.testing.assert_allclose(g["dWg"].sum(axis=1), 0.0, atol=1e-12)
+    # k = 1: the single weight is identically 1, so the gate receives no gradient at all
+    base1 = _forward(oracle, p, T, H, I, E, 1, T, "gelu_tanh")
+    g1 = oracle.backward(p["x"], p["Wg"], p["gate_bias"], p["W1"], p["b1"], p["W2"], p["b2"], base1["topk_expert"], base1["slot"],
+                         G, T, H, I, E, "gelu_tanh", "f32")
+    assert np.abs(g1["dWg"]).max() < 1e-15 and np.abs(g1["dgate_bias"]).max() < 1e-15
+
+
+def test_backward_16bit_storage_is_widened_exactly(oracle):
+    # bf16 inputs give the gradients of the same values held in fp32
+    import torch
+    T, H, I, E, k, C = 8, 4, 6, 2, 2, 6
+    p = _draw(T, H, I, E, 41)
+    pb = {n: torch.from_numpy(v).to(torch.bfloat16) for n, v in p.items() if n != "gate_bias"}
+    pf = {n: v.float().numpy() for n, v in pb.items()}
+    G = np.random.default_rng(42).standard_normal((T, H))
+    base = oracle.forward(pf["x"], pf["Wg"], p["gate_bias"], pf["W1"], pf["b1"], pf["W2"], pf["b2"], T, H, I, E, k, 1.0, "gelu_erf",
+                          "f32", capacity_override=C)
+    a = oracle.backward(pf["x"], pf["Wg"], p["gate_bias"], pf["W1"], pf["b1"], pf["W2"], pf["b2"], base["topk_expert"],
+                        base["slot"], G, T, H, I, E, "gelu_erf", "f32")
+    b = oracle.backward(pb["x"], pb["Wg"], p["gate_bias"], pb["W1"], pb["b1"], pb["W2"], pb["b2"], base["topk_expert"],
+                        base["slot"], G, T, H, I, E, "gelu_erf", "bf16")
+    for n in a:
+        np.testing.assert_array_equal(a[n], b[n], err_msg=n)
