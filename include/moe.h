@@ -51,7 +51,9 @@ typedef enum {
     MOE_ERR_HIP = -4,                 /* a launch failed (hipGetLastError) */
     /* reported by moe_ffn_status only (the single-launch FFN's bounded waits and placement check): */
     MOE_ERR_FFN_DEPENDENCY_TIMEOUT = -5,
-    MOE_ERR_FFN_PLACEMENT = -6
+    MOE_ERR_FFN_PLACEMENT = -6,
+    /* moe_dispatch_noalloc only: the configuration needs more scratch than its fixed array holds */
+    MOE_ERR_STATIC_SCRATCH_TOO_SMALL = -7
 } moe_status;
 
 typedef enum { MOE_F32 = 0, MOE_BF16 = 1, MOE_F16 = 2 } moe_dtype;
@@ -212,6 +214,21 @@ moe_status moe_dispatch(const moe_config* cfg, void* workspace, size_t workspace
                         const void* x, const int32_t* topk_expert, const float* topk_weight,
                         int32_t* slot, int32_t* expert_demand, int32_t* slot_token,
                         float* slot_weight, void* xe, void* stream);
+
+/* moe_dispatch for callers that can neither allocate nor bring a workspace: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments without the workspace, same kernels,
+ * same results bit for bit.  Its scratch (the routing scan's per-chunk expert counts, ceil(T / 64) * E ints)
+ * lives in a fixed array of MOE_STATIC_SCRATCH_BYTES that each GPU holds from the time the library's code is
+ * loaded there until the process ends; configurations that need more return MOE_ERR_STATIC_SCRATCH_TOO_SMALL
+ * before anything is enqueued (T = 16384 with E = 128 needs 128 KiB).  The call allocates nothing and frees
+ * nothing.  The array's address on the current device is looked up on the first call there, or by moe_init():
+ * call moe_init() first when the calls are to be captured.  All calls on one GPU share the one array: calls
+ * that overlap there (two streams, two host threads) race on it and give wrong slots -- serialise them, or
+ * use moe_dispatch with a workspace each. */
+#define MOE_STATIC_SCRATCH_BYTES (4u << 20)
+moe_status moe_dispatch_noalloc(const moe_config* cfg, const void* x, const int32_t* topk_expert,
+                                const float* topk_weight, int32_t* slot, int32_t* expert_demand,
+                                int32_t* slot_token, float* slot_weight, void* xe, void* stream);
 
 /* Expert FFNs (tasks t1, t2 of Sec. 3.1; Eq. ffn in row-vector form): for each
  * expert e and each row r < min(expert_demand[e], C):

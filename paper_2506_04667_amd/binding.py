@@ -18,7 +18,8 @@ TORCH_DTYPE = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float1
 
 EXPORTS = ["moe_status_string", "moe_init", "moe_row_tile", "moe_capacity", "moe_workspace_bytes", "moe_forward",
            "moe_gate", "moe_route", "moe_dispatch", "moe_expert_ffn", "moe_combine", "moe_ffn_status", "moe_ffn_schedule",
-           "moe_forward_timed", "moe_probe_stream", "moe_probe_mfma"]
+           "moe_forward_timed", "moe_probe_stream", "moe_probe_mfma", "moe_dispatch_noalloc"]
+STATIC_SCRATCH_BYTES = 4 << 20
 FORWARD_EVENTS = 6
 FLAG_FFN_SINGLE_LAUNCH = 1
 FLAG_DEBUG_DEPENDENCY_NEVER_MET = 2
@@ -80,6 +81,8 @@ def load(path=None):
     lib.moe_route.argtypes = [cfgp] + [vp] * 4
     lib.moe_dispatch.restype = ctypes.c_int
     lib.moe_dispatch.argtypes = [cfgp, vp, ctypes.c_size_t] + [vp] * 9
+    lib.moe_dispatch_noalloc.restype = ctypes.c_int
+    lib.moe_dispatch_noalloc.argtypes = [cfgp] + [vp] * 9
     lib.moe_expert_ffn.restype = ctypes.c_int
     lib.moe_expert_ffn.argtypes = [cfgp, vp, ctypes.c_size_t] + [vp] * 8
     lib.moe_combine.restype = ctypes.c_int
@@ -221,6 +224,11 @@ def moe_dispatch(cfg, workspace, x, topk_expert, topk_weight, slot, expert_deman
     _check(load().moe_dispatch(ctypes.byref(cfg), _p(workspace), _ws_bytes(workspace), _p(x), _p(topk_expert),
                                _p(topk_weight), _p(slot), _p(expert_demand), _p(slot_token), _p(slot_weight),
                                _p(xe), _stream(stream)))
+
+
+def moe_dispatch_noalloc(cfg, x, topk_expert, topk_weight, slot, expert_demand, slot_token, slot_weight, xe, stream=None):
+    _check(load().moe_dispatch_noalloc(ctypes.byref(cfg), _p(x), _p(topk_expert), _p(topk_weight), _p(slot),
+                                       _p(expert_demand), _p(slot_token), _p(slot_weight), _p(xe), _stream(stream)))
 
 
 def moe_expert_ffn(cfg, workspace, xe, expert_demand, W1, b1, W2, b2, y, stream=None):

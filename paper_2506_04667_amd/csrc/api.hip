@@ -10,7 +10,33 @@
 #include "ffn_units.h"
 #include "kernels.h"
 
+// Scratch of moe_dispatch_noalloc, the entry point for callers that cannot allocate: a fixed array in device
+// memory that every GPU the library runs on holds from the moment the code object is loaded there.  In host code
+// this name is only a handle for hipGetSymbolAddress; the address it yields (one per device) is what kernels,
+// fills and copies get.
+constexpr size_t kStaticScratchBytes = 4u << 20;
+static_assert(kStaticScratchBytes == MOE_STATIC_SCRATCH_BYTES, "the limit stated in the header");
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 namespace {
+
+// Device address of `scratch` on the current device, looked up once per device with that device current.
+hipError_t static_scratch(void** out) {
+    static std::atomic<void*> ptr[moe::kMaxDevices] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= moe::kMaxDevices) return hipErrorInvalidDevice;
+    void* p = ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        ptr[dev].store(p, std::memory_order_release);
+    }
+    *out = p;
+    return hipSuccess;
+}
 
 constexpr int kRowTile = 128;     // bM: per-expert buffers are aligned to this many rows
 constexpr int kGatePad = 128;     // WgT rows are padded to a multiple of the gate GEMM's column tile
@@ -270,6 +296,7 @@ const char* moe_status_string(moe_status s) {
         case MOE_ERR_HIP: return "HIP launch error";
         case MOE_ERR_FFN_DEPENDENCY_TIMEOUT: return "single-launch FFN: a wait for first-task tiles gave up (results invalid)";
         case MOE_ERR_FFN_PLACEMENT: return "single-launch FFN: workgroups of one class ran on different XCDs (results may be stale)";
+        case MOE_ERR_STATIC_SCRATCH_TOO_SMALL: return "configuration needs more than the fixed scratch of the no-allocation entry point";
     }
     return "unknown status";
 }
@@ -280,6 +307,8 @@ moe_status moe_init(void) {
     hipError_t e = moe::prepare_gate_fused();
     if (e == hipSuccess) e = moe::prepare_grouped_gemm();
     if (e == hipSuccess) e = moe::prepare_grouped_gemm_stream();
+    void* scratch_here = nullptr;
+    if (e == hipSuccess) e = static_scratch(&scratch_here);
     if (e != hipSuccess) return MOE_ERR_HIP;
     (void)moe::device_cu_count();
     return MOE_OK;
@@ -402,6 +431,25 @@ moe_status moe_dispatch(const moe_config* cfg, void* workspace, size_t workspace
     if (workspace_bytes < p.total) return MOE_ERR_WORKSPACE_TOO_SMALL;
     return run_dispatch(cfg, p, (int32_t*)ws_at(workspace, p.off_counts), nullptr, x, topk_expert, topk_weight, slot,
                         expert_demand, slot_token, slot_weight, xe, false, (hipStream_t)stream);
+}
+
+moe_status moe_dispatch_noalloc(const moe_config* cfg, const void* x, const int32_t* topk_expert,
+                                const float* topk_weight, int32_t* slot, int32_t* expert_demand, int32_t* slot_token,
+                                float* slot_weight, void* xe, void* stream) {
+    Plan p;
+    moe_status st = make_plan(cfg, &p);
+    if (st != MOE_OK) return st;
+    if (bad_required({topk_expert, topk_weight, slot, expert_demand, slot_token, slot_weight}) || bad_optional({x, xe}) ||
+        (xe && !x))
+        return MOE_ERR_INVALID_ARG;
+    // the only scratch of the routing kernels: per-chunk expert counts (every entry is written before it is read,
+    // so nothing of an earlier call has to be cleared)
+    const size_t need = (size_t)moe::route_chunks(cfg->T) * (size_t)cfg->E * sizeof(int32_t);
+    if (need > kStaticScratchBytes) return MOE_ERR_STATIC_SCRATCH_TOO_SMALL;
+    void* counts = nullptr;
+    if (static_scratch(&counts) != hipSuccess) return MOE_ERR_HIP;
+    return run_dispatch(cfg, p, (int32_t*)counts, nullptr, x, topk_expert, topk_weight, slot, expert_demand, slot_token,
+                        slot_weight, xe, false, (hipStream_t)stream);
 }
 
 moe_status moe_expert_ffn(const moe_config* cfg, void* workspace, size_t workspace_bytes, const void* xe,

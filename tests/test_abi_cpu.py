@@ -106,7 +106,7 @@ def test_null_and_misaligned_pointers_are_rejected(lib):
 
 def test_status_strings(lib):
     assert moe.moe_status_string(0) == "ok"
-    assert len({moe.moe_status_string(c) for c in (0, -1, -2, -3, -4, -5, -6)}) == 7
+    assert len({moe.moe_status_string(c) for c in (0, -1, -2, -3, -4, -5, -6, -7)}) == 8
 
 
 def test_single_launch_flag_needs_a_shape_the_streaming_kernel_takes(lib):
