@@ -67,6 +67,7 @@ def parse_args():
     ap.add_argument("--drop-policy", default="", help="token_major (default) or choice_major")
     ap.add_argument("--single-launch-ffn", action="store_true",
                     help="both FFN GEMMs in one persistent launch (MOE_FLAG_FFN_SINGLE_LAUNCH)")
+    ap.add_argument("--lib", default="", help="load this build of the library instead of the product (layout studies; see build.py --define)")
     ap.add_argument("--graph", action="store_true",
                     help="replay the step from a captured HIP graph in the timed loop (the same kernels, one launch call)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -111,6 +112,8 @@ def main():
     if args.single_launch_ffn: over["flags"] = 1
     if over:
         w = scaled(w, name=w.name + "+" + ",".join("%s=%s" % kv for kv in sorted(over.items())), **over)
+    if args.lib:
+        moe._LIB = moe.load(args.lib)
     moe.load()
     torch.cuda.set_device(0)
     t0 = time.time()

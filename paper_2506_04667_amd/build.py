@@ -17,16 +17,19 @@ HIPCC_FLAGS = [
 ]
 
 
-def build_hip(verbose=False):
+def build_hip(verbose=False, defines=(), out=None):
+    """Compile and link the library.  ``defines`` (e.g. ["MOE_STREAM_SWIZZLE_A=0"]) and ``out`` build a variant
+    for layout studies into another file; the default call builds the product next to this module."""
     csrc = os.path.join(_HERE, "csrc")
-    obj_dir = os.path.join(_HERE, "_build")
+    obj_dir = os.path.join(_HERE, "_build" if not defines else "_build_" + "_".join(d.replace("=", "") for d in defines))
+    lib_path = out or LIB_PATH
     os.makedirs(obj_dir, exist_ok=True)
     sources = sorted(glob.glob(os.path.join(csrc, "*.hip")))
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
     def compile_one(src):
         obj = os.path.join(obj_dir, os.path.basename(src) + ".o")
-        cmd = [hipcc] + HIPCC_FLAGS + ["-c", src, "-o", obj]
+        cmd = [hipcc] + HIPCC_FLAGS + ["-D" + d for d in defines] + ["-c", src, "-o", obj]
         r = subprocess.run(cmd, capture_output=True, text=True)
         if r.returncode != 0:
             raise RuntimeError("hipcc failed on %s:\n%s" % (src, r.stderr))
@@ -36,12 +39,19 @@ def build_hip(verbose=False):
 
     with ThreadPoolExecutor(max_workers=min(8, len(sources))) as ex:
         objs = list(ex.map(compile_one, sources))
-    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB_PATH] + objs
+    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib_path] + objs
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("link failed:\n%s" % r.stderr)
-    return LIB_PATH
+    return lib_path
 
 
 if __name__ == "__main__":
-    print(build_hip(verbose=True))
+    import argparse
+    ap = argparse.ArgumentParser(description=__doc__)
+    ap.add_argument("--define", action="append", default=[], help="NAME=VALUE passed to hipcc as -D (layout-study switches)")
+    ap.add_argument("--out", default=None, help="output file of a variant build (default: the product library)")
+    a = ap.parse_args()
+    if a.define and not a.out:
+        ap.error("a build with --define is a study variant: give it its own --out file")
+    print(build_hip(verbose=True, defines=a.define, out=a.out))

@@ -31,6 +31,7 @@ typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
 constexpr int G_BM = 64, G_THREADS = 512, G_WAVES = G_THREADS / 64;
 constexpr int G_A_STAGE = G_BM * 128;                    // 64 token rows x 128 bytes of k
+constexpr bool kRotateK = true;                          // workgroups start their K loops at different K-tiles
 
 // S: storage type; BN: experts covered (64 for fp32 only, 128, 256).  A K-tile is 128 bytes of k per token
 // row: 64 elements in 16-bit storage, 32 in fp32.
@@ -98,8 +99,18 @@ __global__ __launch_bounds__(G_THREADS) void gate_fused_kernel(const unsigned ch
     const int row0 = blockIdx.x * G_BM;
 
     // ---- this wavefront's 1 KB copies per K-tile: 1 of token rows (8 rows x 128 B), B_COPIES of Wg ----
-    const unsigned char* a_base = uniform(x + (size_t)row0 * H * EL);
-    const unsigned char* b_base = uniform(Wg);
+    // Workgroup b starts its K loop at K-tile b % nk and wraps around: at any moment the workgroups read
+    // different 128-byte columns of their token rows (and different tiles of Wg), so the requests in flight
+    // spread over all memory channels instead of marching down one 4 KB-strided column band together.  The
+    // order in which a workgroup accumulates its K-tiles depends on its number only: results are the same
+    // from run to run.
+    const int nk = H / KT;
+    const int k_first = kRotateK ? (int)(blockIdx.x % (unsigned)nk) : 0;
+    const size_t b_step = (size_t)KT * E * EL;
+    const unsigned char* const a_row0 = uniform(x + (size_t)row0 * H * EL);
+    const unsigned char* a_base = uniform(a_row0 + (size_t)k_first * 128);
+    const unsigned char* b_base = uniform(Wg + (size_t)k_first * b_step);
+    int k_issue = k_first;                              // K-tile the next request fetches
     uint32_t a_off, b_off[C::B_COPIES];
     {
         const int r = wave * 8 + (lane >> 3), p = lane & 7;
@@ -115,9 +126,7 @@ __global__ __launch_bounds__(G_THREADS) void gate_fused_kernel(const unsigned ch
         const int n = min(c * VEC, E - VEC);            // columns beyond E repeat the last experts (masked later)
         b_off[j] = (uint32_t)kk * (uint32_t)(E * EL) + n * EL;
     }
-    const size_t b_step = (size_t)KT * E * EL;
     const uint32_t lds_base = (uint32_t)(size_t)(__attribute__((address_space(3))) unsigned char*)smem;
-    const int nk = H / KT;
 
     auto issue = [&](int t) __attribute__((always_inline)) {
         const uint32_t d = lds_base + (t % D) * STAGE;
@@ -127,6 +136,11 @@ __global__ __launch_bounds__(G_THREADS) void gate_fused_kernel(const unsigned ch
             copy_to_lds(b_base, b_off[j], d + G_A_STAGE + (wave * C::B_COPIES + j) * 1024);
         a_base += 128;
         b_base += b_step;
+        if (++k_issue == nk) {
+            k_issue = 0;
+            a_base = a_row0;
+            b_base = uniform(Wg);
+        }
     };
 
     // ---- per-lane LDS read offsets ----

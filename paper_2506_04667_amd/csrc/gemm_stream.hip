@@ -60,6 +60,23 @@ namespace {
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
+// Layout-study switches: the library is built with all three swizzles on.  Building with one of them set to 0
+// (python -m paper_2506_04667_amd.build --define MOE_STREAM_SWIZZLE_A=0 --out <file>) stores that operand in
+// LDS unswizzled, which changes nothing but the bank-conflict behaviour: the 16-bit LDS layouts are the part the
+// paper's own "FP16 memory throughput" appendix names as its weak spot.
+#ifndef MOE_STREAM_SWIZZLE_A
+#define MOE_STREAM_SWIZZLE_A 1
+#endif
+#ifndef MOE_STREAM_SWIZZLE_B
+#define MOE_STREAM_SWIZZLE_B 1
+#endif
+#ifndef MOE_STREAM_SWIZZLE_EPILOGUE
+#define MOE_STREAM_SWIZZLE_EPILOGUE 1
+#endif
+__device__ __forceinline__ int swz_a(int r) { return MOE_STREAM_SWIZZLE_A ? (r >> 1) & 7 : 0; }
+__device__ __forceinline__ int swz_b(int k) { return MOE_STREAM_SWIZZLE_B ? ((k & 3) << 1) | (((k >> 3) & 1) << 3) : 0; }
+__device__ __forceinline__ int swz_e(int r) { return MOE_STREAM_SWIZZLE_EPILOGUE ? (r >> 1) & 7 : 0; }
+
 constexpr int BN = 256, BK = 32, THREADS = 512;
 constexpr int TN = 4, WN = 4;                           // 16-column MFMA tiles per wavefront; wavefronts along N
 // Row tile: 128 G rows, G = 2 (the design above) or G = 1 (wavefronts hold 64 x 64: half the MFMAs and half
@@ -226,7 +243,7 @@ __device__ __forceinline__ void stream_body(const StreamArgs& a, int32_t* list, 
 #pragma unroll
         for (int j = 0; j < A_COPIES; ++j) {
             const int r = (wave * A_COPIES + j) * 8 + (lane >> 3), p = lane & 7;
-            const int c = p ^ ((r >> 1) & 7);
+            const int c = p ^ swz_a(r);
             int grow = min(t.row0 + r, t.rows - 1);
             if (row_index) grow = row_index[(size_t)t.grp * P.a_index_stride + grow];
             oa[j] = (uint32_t)grow * (uint32_t)(lda * 2) + c * 16;
@@ -234,7 +251,7 @@ __device__ __forceinline__ void stream_body(const StreamArgs& a, int32_t* list, 
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
             const int k = (wave * 2 + j) * 2 + (lane >> 5), p = lane & 31;
-            const int c = p ^ (((k & 3) << 1) | (((k >> 3) & 1) << 3));
+            const int c = p ^ swz_b(k);
             const int n = min(t.n0 + c * 8, N - 8);
             ob[j] = (uint32_t)k * (uint32_t)(ldb * 2) + n * 2;
         }
@@ -311,9 +328,9 @@ __device__ __forceinline__ void stream_body(const StreamArgs& a, int32_t* list, 
     // ---- per-lane LDS read offsets ----
     const int r16 = lane & 15, kq = lane >> 4;          // row/column inside a 16-wide MFMA tile; k-octet of the lane
     const int a_row = wm * TM * 16 + r16;
-    const int a_sw = (a_row >> 1) & 7;                  // same for every 16-row tile of this lane
+    const int a_sw = swz_a(a_row);                      // same for every 16-row tile of this lane
     const int bk = kq * 8 + (r16 >> 2);                 // k of the first transpose read; the second is k + 4
-    const int b_sw = ((bk & 3) << 1) | (((bk >> 3) & 1) << 3);
+    const int b_sw = swz_b(bk);
     int a_rd[2], b_rd[TN];                              // [half of the 64-wide activation stage]
 #pragma unroll
     for (int h = 0; h < 2; ++h) a_rd[h] = a_row * 128 + ((((h << 2) | kq) ^ a_sw) << 4);
@@ -379,7 +396,7 @@ __device__ __forceinline__ void stream_body(const StreamArgs& a, int32_t* list, 
                         v[b] = apply_act16_t<ACT>(acc[tm][tn][b] + bias);
                         acc[tm][tn][b] = 0.0f;
                     }
-                    const int chunk = (tn * 2 + (kq >> 1)) ^ ((rl >> 1) & 7);
+                    const int chunk = (tn * 2 + (kq >> 1)) ^ swz_e(rl);
                     *(u32x2*)(epi + rl * 128 + (chunk << 4) + (kq & 1) * 8) = u32x2{pack2<S>(v[0], v[1]), pack2<S>(v[2], v[3])};
                 }
             }
@@ -388,7 +405,7 @@ __device__ __forceinline__ void stream_body(const StreamArgs& a, int32_t* list, 
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const int r_local = i * 8 + (lane_e >> 3), chunk = lane_e & 7;
-                const u32x4 v = *(const u32x4*)(epi + r_local * 128 + ((chunk ^ ((r_local >> 1) & 7)) << 4));
+                const u32x4 v = *(const u32x4*)(epi + r_local * 128 + ((chunk ^ swz_e(r_local)) << 4));
                 const int row = cur.row0 + wm * (TM * 16) + pass * 32 + r_local, col = col_w + chunk * 8;
                 if (row < cur.rows && col < N) *(u32x4*)((elem*)P.C + c_base + (size_t)row * P.ldc + col) = v;
             }
