@@ -68,6 +68,8 @@ def parse_args():
     ap.add_argument("--single-launch-ffn", action="store_true",
                     help="both FFN GEMMs in one persistent launch (MOE_FLAG_FFN_SINGLE_LAUNCH)")
     ap.add_argument("--lib", default="", help="load this build of the library instead of the product (layout studies; see build.py --define)")
+    ap.add_argument("--backward", action="store_true",
+                    help="also time moe_backward (gradients under the forward's routing); reported as backward_ms, not part of value")
     ap.add_argument("--graph", action="store_true",
                     help="replay the step from a captured HIP graph in the timed loop (the same kernels, one launch call)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -207,6 +209,32 @@ def main():
             run_step()
         steady_ms = timed(max(args.steps, 32))
 
+    # ---- backward pass (optional; the metric is the forward latency)
+    backward = None
+    if args.backward:
+        f32 = lambda *shape: torch.empty(shape, dtype=torch.float32, device="cuda")
+        grads = [f32(w.T, w.H), f32(w.H, w.E), f32(w.E), f32(w.E, w.H, w.I), f32(w.E, w.I), f32(w.E, w.I, w.H), f32(w.E, w.H)]
+        bws = torch.empty(moe.moe_backward_workspace_bytes(cfg), dtype=torch.uint8, device="cuda")
+        dout = torch.randn((w.T, w.H), device="cuda").to(dev["x"].dtype)
+
+        def bstep():
+            moe.moe_backward(cfg, bws, dev["x"], dev["Wg"], dev["W1"], dev["b1"], dev["W2"], dev["b2"], b.topk_expert,
+                             b.topk_weight, dout, *grads)
+        for _ in range(3):
+            bstep()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        nb = max(4, args.steps // 4)
+        for _ in range(nb):
+            bstep()
+        torch.cuda.synchronize()
+        bms = (time.perf_counter() - t0) * 1e3 / nb
+        kept = int((b.slot >= 0).sum())
+        backward = {"backward_ms": round(bms, 4), "steps": nb, "workspace_bytes": bws.numel(),
+                    # recomputed forward (4 R H I) + data gradients (4 R H I) + weight gradients (4 R H I on the live rows)
+                    "gemm_tflops_on_live_rows": round(12.0 * kept * w.H * w.I / (bms * 1e-3) / 1e12, 1)}
+        del grads, bws, dout
+
     # ---- yardsticks measured in this run: streaming read, copy, MFMA loop
     measured = None
     if not args.no_probes:
@@ -337,6 +365,7 @@ def main():
         "roofline_other": other,
         "roofline_gemm2": roofline2,
         "measured_peaks": measured,
+        "backward": backward,
         "cpu_baseline": cpu_baseline,
         "input_gen_s": round(gen_s, 1),
     }

@@ -248,6 +248,33 @@ moe_status moe_expert_ffn(const moe_config* cfg, void* workspace, size_t workspa
 moe_status moe_combine(const moe_config* cfg, const void* y, const int32_t* topk_expert,
                        const float* topk_weight, const int32_t* slot, void* out, void* stream);
 
+/* ---- backward pass ---------------------------------------------------------------------------------------
+ * Gradients of the layer for training.  The paper runs the forward pass only and names training support as
+ * future work ("Limitations and Future Work"), so it defines no backward; this is the chain rule applied to
+ * Eq. ffn and Eqs. combine 1/2 with these readings: the routing (which k experts a token selected, which pairs
+ * kept a slot) is a constant of the differentiation; the combine weights are differentiated as the softmax over
+ * the k selected logits (all k enter the normalisation, dropped or not); a dropped pair sends no gradient
+ * anywhere.  With dout = dL/dout for a scalar L:
+ *   per kept pair (i, j), expert e, a = x_i W1_e + b1_e, h = phi(a), y = h W2_e + b2_e:
+ *     dL/dw_ij = <dout_i, y>,  gy = w_ij dout_i,  db2_e += gy,  dW2_e += h^T gy,  da = (gy W2_e^T) * phi'(a),
+ *     db1_e += da,  dW1_e += x_i^T da,  dx_i += da W1_e^T;
+ *   per token: dl_ij = w_ij (dL/dw_ij - sum_j' w_ij' dL/dw_ij'),  dgate_bias[e_ij] += dl_ij,
+ *     dWg[:, e_ij] += x_i dl_ij,  dx_i += dl_ij Wg[:, e_ij].
+ * in : x, Wg, W1, b1 (or NULL), W2, b2 (or NULL) as in moe_forward; topk_expert[T,k], topk_weight[T,k] as
+ *      moe_forward returned them (slots and drops are recomputed from them under cfg's capacity and drop
+ *      policy); dout[T,H] in the storage dtype.
+ * out: fp32, all required: dx[T,H], dWg[H,E], dgate_bias[E], dW1[E,H,I], db1[E,I], dW2[E,I,H], db2[E,H]
+ *      (every element is written; experts without kept rows get zeros).
+ * The expert activations are recomputed (nothing of the forward call's workspace is needed) and kept in the
+ * storage dtype between kernels; accumulation is fp32; every reduction has a fixed order.  k <= 64 and
+ * cfg->flags == 0, else MOE_ERR_UNSUPPORTED.  Workspace: moe_backward_workspace_bytes. */
+moe_status moe_backward_workspace_bytes(const moe_config* cfg, size_t* bytes);
+moe_status moe_backward(const moe_config* cfg, void* workspace, size_t workspace_bytes,
+                        const void* x, const void* Wg, const void* W1, const void* b1, const void* W2, const void* b2,
+                        const int32_t* topk_expert, const float* topk_weight, const void* dout,
+                        float* dx, float* dWg, float* dgate_bias, float* dW1, float* db1, float* dW2, float* db2,
+                        void* stream);
+
 /* Host arithmetic only (no device work): the tasks of one workgroup of the weight-streaming FFN kernels for
  * one GEMM over one of the two lists of live (expert, row tile) units (Sec. 3.1 tasks; the static stand-in for
  * the paper's scheduler, Alg. 3), in the order the workgroup runs them.  The same inline functions deal the

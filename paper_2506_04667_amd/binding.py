@@ -18,7 +18,8 @@ TORCH_DTYPE = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float1
 
 EXPORTS = ["moe_status_string", "moe_init", "moe_row_tile", "moe_capacity", "moe_workspace_bytes", "moe_forward",
            "moe_gate", "moe_route", "moe_dispatch", "moe_expert_ffn", "moe_combine", "moe_ffn_status", "moe_ffn_schedule",
-           "moe_forward_timed", "moe_probe_stream", "moe_probe_mfma", "moe_dispatch_noalloc"]
+           "moe_forward_timed", "moe_probe_stream", "moe_probe_mfma", "moe_dispatch_noalloc",
+           "moe_backward_workspace_bytes", "moe_backward"]
 STATIC_SCRATCH_BYTES = 4 << 20
 FORWARD_EVENTS = 6
 FLAG_FFN_SINGLE_LAUNCH = 1
@@ -83,6 +84,10 @@ def load(path=None):
     lib.moe_dispatch.argtypes = [cfgp, vp, ctypes.c_size_t] + [vp] * 9
     lib.moe_dispatch_noalloc.restype = ctypes.c_int
     lib.moe_dispatch_noalloc.argtypes = [cfgp] + [vp] * 9
+    lib.moe_backward_workspace_bytes.restype = ctypes.c_int
+    lib.moe_backward_workspace_bytes.argtypes = [cfgp, ctypes.POINTER(ctypes.c_size_t)]
+    lib.moe_backward.restype = ctypes.c_int
+    lib.moe_backward.argtypes = [cfgp, vp, ctypes.c_size_t] + [vp] * 17
     lib.moe_expert_ffn.restype = ctypes.c_int
     lib.moe_expert_ffn.argtypes = [cfgp, vp, ctypes.c_size_t] + [vp] * 8
     lib.moe_combine.restype = ctypes.c_int
@@ -229,6 +234,19 @@ def moe_dispatch(cfg, workspace, x, topk_expert, topk_weight, slot, expert_deman
 def moe_dispatch_noalloc(cfg, x, topk_expert, topk_weight, slot, expert_demand, slot_token, slot_weight, xe, stream=None):
     _check(load().moe_dispatch_noalloc(ctypes.byref(cfg), _p(x), _p(topk_expert), _p(topk_weight), _p(slot),
                                        _p(expert_demand), _p(slot_token), _p(slot_weight), _p(xe), _stream(stream)))
+
+
+def moe_backward_workspace_bytes(cfg):
+    n = ctypes.c_size_t()
+    _check(load().moe_backward_workspace_bytes(ctypes.byref(cfg), ctypes.byref(n)))
+    return n.value
+
+
+def moe_backward(cfg, workspace, x, Wg, W1, b1, W2, b2, topk_expert, topk_weight, dout, dx, dWg, dgate_bias, dW1, db1,
+                 dW2, db2, stream=None):
+    _check(load().moe_backward(ctypes.byref(cfg), _p(workspace), _ws_bytes(workspace), _p(x), _p(Wg), _p(W1), _p(b1),
+                               _p(W2), _p(b2), _p(topk_expert), _p(topk_weight), _p(dout), _p(dx), _p(dWg),
+                               _p(dgate_bias), _p(dW1), _p(db1), _p(dW2), _p(db2), _stream(stream)))
 
 
 def moe_expert_ffn(cfg, workspace, xe, expert_demand, W1, b1, W2, b2, y, stream=None):

@@ -283,6 +283,127 @@ moe_status forward_impl(const moe_config* cfg, void* workspace, size_t workspace
     return mark(5) ? MOE_OK : MOE_ERR_HIP;
 }
 
+// ---- backward pass: workspace carving and launch order -------------------------------------------------------
+struct BwdPlan {
+    Plan p;
+    int ldL, T_pad;
+    size_t off_counts, off_units, off_slot_token, off_slot_weight, off_slot, off_demand, off_dl, off_dL, off_wgt, off_xe,
+        off_gy, off_a, off_h, off_dh, off_y, off_hT, off_xeT, off_xT, total;
+};
+
+moe_status make_bwd_plan(const moe_config* c, BwdPlan* b) {
+    moe_status st = make_plan(c, &b->p);
+    if (st != MOE_OK) return st;
+    if (c->k > 64) return MOE_ERR_UNSUPPORTED;          // the gate's Jacobian kernel keeps a token's choices in one wavefront
+    if (c->flags != 0) return MOE_ERR_UNSUPPORTED;
+    const Plan& p = b->p;
+    const size_t T = c->T, H = c->H, I = c->I, E = c->E, k = c->k, el = p.elem;
+    const size_t rows = E * (size_t)p.C_pad;
+    b->ldL = (int)align_up(E, 8);
+    b->T_pad = (int)align_up(T, 8);
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, kAlign); return o; };
+    b->off_counts = take((size_t)moe::route_chunks(c->T) * E * 4);
+    b->off_units = take(moe::ffn_units_ints(c->E, p.C) * 4);
+    b->off_slot_token = take(E * (size_t)p.C * 4);
+    b->off_slot_weight = take(E * (size_t)p.C * 4);
+    b->off_slot = take(T * k * 4);
+    b->off_demand = take(E * 4);
+    b->off_dl = take(T * k * 4);
+    b->off_dL = take(T * (size_t)b->ldL * el);
+    b->off_wgt = take((size_t)p.E_pad * H * el);
+    b->off_xe = take(rows * H * el);
+    b->off_gy = take(rows * H * el);
+    b->off_a = take(rows * I * el);
+    b->off_h = take(rows * I * el);
+    b->off_dh = take(rows * I * el);
+    b->off_y = take(rows * H * el);
+    b->off_hT = take(rows * I * el);
+    b->off_xeT = take(rows * H * el);
+    b->off_xT = take(H * (size_t)b->T_pad * el);
+    b->total = off;
+    return MOE_OK;
+}
+
+moe_status run_backward(const moe_config* c, const BwdPlan& b, void* ws, const void* x, const void* Wg, const void* W1,
+                        const void* b1, const void* W2, const void* b2, const int32_t* topk_expert, const float* topk_weight,
+                        const void* dout, float* dx, float* dWg, float* dgate_bias, float* dW1, float* db1, float* dW2,
+                        float* db2, hipStream_t s) {
+    const Plan& p = b.p;
+    const int T = c->T, H = c->H, I = c->I, E = c->E, k = c->k, C = p.C, C_pad = p.C_pad, dt = c->dtype;
+    int32_t* counts = (int32_t*)ws_at(ws, b.off_counts);
+    int32_t* units = dt != MOE_F32 ? (int32_t*)ws_at(ws, b.off_units) : nullptr;
+    int32_t* slot_token = (int32_t*)ws_at(ws, b.off_slot_token);
+    float* slot_weight = (float*)ws_at(ws, b.off_slot_weight);
+    int32_t* slot = (int32_t*)ws_at(ws, b.off_slot);
+    int32_t* demand = (int32_t*)ws_at(ws, b.off_demand);
+    float* dl = (float*)ws_at(ws, b.off_dl);
+    void *dL = ws_at(ws, b.off_dL), *wgt = ws_at(ws, b.off_wgt), *xe = ws_at(ws, b.off_xe), *gy = ws_at(ws, b.off_gy);
+    void *a = ws_at(ws, b.off_a), *h = ws_at(ws, b.off_h), *dh = ws_at(ws, b.off_dh), *y = ws_at(ws, b.off_y);
+    void *hT = ws_at(ws, b.off_hT), *xeT = ws_at(ws, b.off_xeT), *xT = ws_at(ws, b.off_xT);
+#define MOE_TRY(call) do { if ((call) != hipSuccess) return MOE_ERR_HIP; } while (0)
+    // the routing tables again, from the selection the forward pass made (slots are a function of it)
+    MOE_TRY(moe::launch_route(topk_expert, topk_weight, T, E, k, C, c->drop_policy == MOE_DROP_CHOICE_MAJOR, counts, false, slot,
+                              demand, slot_token, slot_weight, units, s));
+    MOE_TRY(moe::launch_transpose_pad(Wg, wgt, H, E, p.E_pad, dt, s));
+    MOE_TRY(moe::launch_bwd_gather(x, dout, slot_token, slot_weight, H, E, C, C_pad, dt, xe, gy, s));
+    // grouped GEMMs over the experts' live rows
+    moe::GemmArgs g{};
+    g.rows_dev = demand; g.rows_fixed = 0; g.rows_cap = C; g.groups = E; g.max_rows = C;
+    g.dtype = dt; g.act = MOE_ACT_IDENTITY; g.a_rows_total = C_pad;
+    const long long rH = (long long)C_pad * H, rI = (long long)C_pad * I, HI = (long long)H * I;
+    // forward again, keeping the pre-activation: a = xe W1 + b1, h = phi(a), y = h W2 + b2
+    moe::GemmArgs f1 = g;
+    f1.A = xe; f1.a_group_stride = rH; f1.lda = H; f1.B = W1; f1.b_group_stride = HI; f1.ldb = I;
+    f1.C = a; f1.c_group_stride = rI; f1.ldc = I; f1.bias = b1; f1.bias_group_stride = I; f1.N = I; f1.K = H; f1.units = units;
+    MOE_TRY(moe::launch_grouped_gemm(f1, s));
+    MOE_TRY(moe::launch_bwd_act(a, nullptr, demand, E, C, C_pad, I, c->act, dt, false, h, s));
+    moe::GemmArgs f2 = g;
+    f2.A = h; f2.a_group_stride = rI; f2.lda = I; f2.B = W2; f2.b_group_stride = HI; f2.ldb = H;
+    f2.C = y; f2.c_group_stride = rH; f2.ldc = H; f2.bias = b2; f2.bias_group_stride = H; f2.N = H; f2.K = I; f2.units = units;
+    MOE_TRY(moe::launch_grouped_gemm(f2, s));
+    // gate: dL/dw from <dout, y>, then the softmax Jacobian
+    MOE_TRY(moe::launch_bwd_gate(dout, y, topk_expert, topk_weight, slot, T, H, k, E, C, C_pad, b.ldL, dt, dl, dL, s));
+    // dh = gy W2^T (W2[e] read as [N = I][K = H]); da = dh * phi'(a); dxe = da W1^T (W1[e] as [N = H][K = I])
+    moe::GemmArgs d1 = g;
+    d1.A = gy; d1.a_group_stride = rH; d1.lda = H; d1.B = W2; d1.b_group_stride = HI; d1.ldb = H; d1.b_is_nk = true;
+    d1.C = dh; d1.c_group_stride = rI; d1.ldc = I; d1.N = I; d1.K = H;
+    MOE_TRY(moe::launch_grouped_gemm(d1, s));
+    MOE_TRY(moe::launch_bwd_act(a, dh, demand, E, C, C_pad, I, c->act, dt, true, dh, s));
+    moe::GemmArgs d2 = g;
+    d2.A = dh; d2.a_group_stride = rI; d2.lda = I; d2.B = W1; d2.b_group_stride = HI; d2.ldb = I; d2.b_is_nk = true;
+    d2.C = y; d2.c_group_stride = rH; d2.ldc = H; d2.N = H; d2.K = I;       // dxe takes y's place
+    MOE_TRY(moe::launch_grouped_gemm(d2, s));
+    // weight gradients as row-major GEMMs over all C_pad rows (rows beyond the live ones are zero in gy and da):
+    // dW2[e] = h[e]^T gy[e], dW1[e] = xe[e]^T da[e]
+    MOE_TRY(moe::launch_bwd_transpose(h, hT, E, C_pad, I, C_pad, dt, s));
+    MOE_TRY(moe::launch_bwd_transpose(xe, xeT, E, C_pad, H, C_pad, dt, s));
+    moe::GemmArgs w{};
+    w.rows_dev = nullptr; w.groups = E; w.dtype = dt; w.act = MOE_ACT_IDENTITY; w.c_f32 = true; w.K = C_pad; w.lda = C_pad;
+    moe::GemmArgs w2 = w;
+    w2.A = hT; w2.a_group_stride = rI; w2.a_rows_total = I; w2.rows_fixed = I; w2.rows_cap = I; w2.max_rows = I;
+    w2.B = gy; w2.b_group_stride = rH; w2.ldb = H; w2.C = dW2; w2.c_group_stride = HI; w2.ldc = H; w2.N = H;
+    MOE_TRY(moe::launch_grouped_gemm(w2, s));
+    moe::GemmArgs w1 = w;
+    w1.A = xeT; w1.a_group_stride = rH; w1.a_rows_total = H; w1.rows_fixed = H; w1.rows_cap = H; w1.max_rows = H;
+    w1.B = dh; w1.b_group_stride = rI; w1.ldb = I; w1.C = dW1; w1.c_group_stride = HI; w1.ldc = I; w1.N = I;
+    MOE_TRY(moe::launch_grouped_gemm(w1, s));
+    MOE_TRY(moe::launch_bwd_colsum(gy, demand, E, C, C_pad, H, dt, db2, s));
+    MOE_TRY(moe::launch_bwd_colsum(dh, demand, E, C, C_pad, I, dt, db1, s));
+    // gate weights: dWg = x^T dL, dgate_bias = column sums of dl
+    MOE_TRY(moe::launch_bwd_transpose(x, xT, 1, T, H, b.T_pad, dt, s));
+    moe::GemmArgs wg{};
+    wg.rows_dev = nullptr; wg.groups = 1; wg.dtype = dt; wg.act = MOE_ACT_IDENTITY; wg.c_f32 = true;
+    wg.A = xT; wg.lda = b.T_pad; wg.a_rows_total = H; wg.rows_fixed = H; wg.rows_cap = H; wg.max_rows = H;
+    wg.B = dL; wg.ldb = b.ldL; wg.C = dWg; wg.ldc = E; wg.N = E; wg.K = T;
+    MOE_TRY(moe::launch_grouped_gemm(wg, s));
+    MOE_TRY(moe::launch_bwd_gate_bias(topk_expert, dl, T, k, E, dgate_bias, s));
+    // dx: the kept choices' rows of dxe plus the gate path
+    MOE_TRY(moe::launch_bwd_dx(y, wgt, topk_expert, slot, dl, T, H, k, E, C, C_pad, dt, dx, s));
+#undef MOE_TRY
+    return MOE_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -463,6 +584,30 @@ moe_status moe_expert_ffn(const moe_config* cfg, void* workspace, size_t workspa
     st = check_single_launch(cfg, p, false);
     if (st != MOE_OK) return st;
     return run_ffn(cfg, p, workspace, xe, nullptr, expert_demand, W1, b1, W2, b2, y, false, nullptr, (hipStream_t)stream);
+}
+
+moe_status moe_backward_workspace_bytes(const moe_config* cfg, size_t* bytes) {
+    if (!bytes) return MOE_ERR_INVALID_ARG;
+    BwdPlan b;
+    moe_status st = make_bwd_plan(cfg, &b);
+    if (st != MOE_OK) return st;
+    *bytes = b.total;
+    return MOE_OK;
+}
+
+moe_status moe_backward(const moe_config* cfg, void* workspace, size_t workspace_bytes, const void* x, const void* Wg,
+                        const void* W1, const void* b1, const void* W2, const void* b2, const int32_t* topk_expert,
+                        const float* topk_weight, const void* dout, float* dx, float* dWg, float* dgate_bias, float* dW1,
+                        float* db1, float* dW2, float* db2, void* stream) {
+    BwdPlan b;
+    moe_status st = make_bwd_plan(cfg, &b);
+    if (st != MOE_OK) return st;
+    if (bad_required({workspace, x, Wg, W1, W2, topk_expert, topk_weight, dout, dx, dWg, dgate_bias, dW1, db1, dW2, db2}) ||
+        bad_optional({b1, b2}))
+        return MOE_ERR_INVALID_ARG;
+    if (workspace_bytes < b.total) return MOE_ERR_WORKSPACE_TOO_SMALL;
+    return run_backward(cfg, b, workspace, x, Wg, W1, b1, W2, b2, topk_expert, topk_weight, dout, dx, dWg, dgate_bias, dW1, db1,
+                        dW2, db2, (hipStream_t)stream);
 }
 
 moe_status moe_combine(const moe_config* cfg, const void* y, const int32_t* topk_expert,

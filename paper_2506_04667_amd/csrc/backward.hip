@@ -1,0 +1,250 @@
+// Helper kernels of the layer's backward pass (gradients under a fixed routing; the paper leaves training to
+// future work, so this follows the chain rule of Eq. "ffn" and Eqs. "combine 1/2" as stated in include/moe.h).
+// The dense contractions of the backward pass run on the grouped GEMM kernels; what is here is the data movement
+// and elementwise work between them: gathering rows through the routing table, the activation and its
+// derivative, the softmax Jacobian of the gate, transposes that turn weight-gradient products into row-major
+// GEMMs, column sums for the bias gradients, and the final gather of dx.  Every reduction has a fixed order, so
+// gradients are bit-identical from run to run.
+#include "common.h"
+#include "kernels.h"
+
+namespace moe {
+namespace {
+
+// derivative of phi_1 at the pre-activation v (act codes of moe_act)
+__device__ __forceinline__ float act_grad(float v, int act) {
+    switch (act) {
+        case 0: return v > 0.0f ? 1.0f : 0.0f;
+        case 1: {
+            const float c = 0.7978845608028654f;
+            const float t = tanh_fast(c * (v + 0.044715f * v * v * v));
+            return 0.5f * (1.0f + t) + 0.5f * v * (1.0f - t * t) * c * (1.0f + 3.0f * 0.044715f * v * v);
+        }
+        case 2: return 0.5f * (1.0f + erf_as(v * 0.7071067811865476f)) + v * __expf(-0.5f * v * v) * 0.3989422804014327f;
+        default: return 1.0f;
+    }
+}
+
+// One workgroup per slot row (e, s), s < C_pad: xe[e, s, :] = x[token, :] and gy[e, s, :] = w * dout[token, :]
+// for a live slot, zeros for an empty one (so that the rows beyond an expert's live rows contribute nothing to
+// the weight-gradient products, which run over all C_pad rows).
+template <class S>
+__global__ __launch_bounds__(256) void bwd_gather_kernel(const void* __restrict__ x, const void* __restrict__ dout,
+                                                         const int32_t* __restrict__ slot_token, const float* __restrict__ slot_weight,
+                                                         int H, int C, int C_pad, void* __restrict__ xe, void* __restrict__ gy) {
+    const size_t row = blockIdx.x;
+    const int e = (int)(row / C_pad), s = (int)(row % C_pad);
+    const int tok = s < C ? slot_token[(size_t)e * C + s] : -1;
+    const float w = tok >= 0 ? slot_weight[(size_t)e * C + s] : 0.0f;
+    for (int c = threadIdx.x; c < H; c += 256) {
+        float xv = 0.0f, gv = 0.0f;
+        if (tok >= 0) {
+            xv = load_as_float<S>(x, (size_t)tok * H + c);
+            gv = w * load_as_float<S>(dout, (size_t)tok * H + c);
+        }
+        store_from_float<S>(xe, row * H + c, xv);
+        store_from_float<S>(gy, row * H + c, gv);
+    }
+}
+
+// Over [E, C_pad, I]: MODE 0: out = phi(a); MODE 1: out = g * phi'(a); rows at or beyond the expert's live rows give 0.
+template <class S, int MODE>
+__global__ __launch_bounds__(256) void bwd_act_kernel(const void* __restrict__ a, const void* __restrict__ g,
+                                                      const int32_t* __restrict__ expert_demand, int C, int C_pad, int I, int act,
+                                                      void* __restrict__ out) {
+    const size_t row = blockIdx.x;
+    const int e = (int)(row / C_pad), s = (int)(row % C_pad);
+    const bool live = s < min(expert_demand[e], C);
+    for (int c = threadIdx.x; c < I; c += 256) {
+        float v = 0.0f;
+        if (live) {
+            const float av = load_as_float<S>(a, row * I + c);
+            v = MODE == 0 ? apply_act(av, act) : load_as_float<S>(g, row * I + c) * act_grad(av, act);
+        }
+        store_from_float<S>(out, row * I + c, v);
+    }
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off);
+    return v;
+}
+
+// One wavefront per token (k <= 64): dL/dw_ij = <dout_i, y_ij> for kept pairs (0 for dropped ones), then the
+// Jacobian of the softmax over the k selected logits: dl_ij = w_ij (dL/dw_ij - sum_j' w_ij' dL/dw_ij').
+// Writes dl[T, k] (fp32) and the dense matrix dL[T, ld] (storage type, zero where the token did not select the
+// expert), which turns dWg = x^T dL into a GEMM.
+template <class S>
+__global__ __launch_bounds__(256) void bwd_gate_kernel(const void* __restrict__ dout, const void* __restrict__ y,
+                                                       const int32_t* __restrict__ topk_expert, const float* __restrict__ topk_weight,
+                                                       const int32_t* __restrict__ slot, int T, int H, int k, int E, int C, int C_pad,
+                                                       int ld, float* __restrict__ dl, void* __restrict__ dL) {
+    const int t = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+    if (t >= T) return;
+    int e_l = -1, s_l = -1;
+    float w_l = 0.0f, dw_l = 0.0f;
+    if (lane < k) {
+        e_l = topk_expert[(size_t)t * k + lane];
+        s_l = slot[(size_t)t * k + lane];
+        w_l = topk_weight[(size_t)t * k + lane];
+    }
+    for (int j = 0; j < k; ++j) {
+        const int e = __shfl(e_l, j), s = __shfl(s_l, j);
+        if (s < 0 || s >= C || e < 0 || e >= E) continue;      // wave-uniform
+        const size_t row = (size_t)e * C_pad + s;
+        float part = 0.0f;
+        for (int c = lane; c < H; c += 64) part = fmaf(load_as_float<S>(dout, (size_t)t * H + c), load_as_float<S>(y, row * H + c), part);
+        const float d = wave_sum(part);
+        if (lane == j) dw_l = d;
+    }
+    const float mean = wave_sum(w_l * dw_l);
+    const float dl_l = w_l * (dw_l - mean);
+    if (lane < k) dl[(size_t)t * k + lane] = dl_l;
+    for (int c = lane; c < ld; c += 64) {
+        float v = 0.0f;
+        for (int j = 0; j < k; ++j) {
+            const int e = __shfl(e_l, j);
+            const float d = __shfl(dl_l, j);
+            if (e == c) v = d;
+        }
+        store_from_float<S>(dL, (size_t)t * ld + c, v);
+    }
+}
+
+// out[g][c][r] = in[g][r][c] for r < R, c < Cc; out rows have ld_out >= R entries, those at and beyond R are zero.
+template <class elem>
+__global__ __launch_bounds__(256) void bwd_transpose_kernel(const elem* __restrict__ in, elem* __restrict__ out, int R, int Cc,
+                                                            int ld_out) {
+    __shared__ elem tile[32][33];
+    const size_t g = blockIdx.z;
+    const int r0 = blockIdx.x * 32, c0 = blockIdx.y * 32;
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+    for (int i = ty; i < 32; i += 8) {
+        const int r = r0 + i, c = c0 + tx;
+        tile[i][tx] = (r < R && c < Cc) ? in[(g * R + r) * Cc + c] : (elem)0;
+    }
+    __syncthreads();
+    for (int i = ty; i < 32; i += 8) {
+        const int c = c0 + i, r = r0 + tx;
+        if (c < Cc && r < ld_out) out[(g * Cc + c) * ld_out + r] = tile[tx][i];
+    }
+}
+
+// out[e][c] = sum over the live rows r of in[e][r][c], rows in ascending order (fp32).
+template <class S>
+__global__ __launch_bounds__(256) void bwd_colsum_kernel(const void* __restrict__ in, const int32_t* __restrict__ expert_demand, int C,
+                                                         int C_pad, int cols, float* __restrict__ out) {
+    const int e = blockIdx.y, c = blockIdx.x * 256 + threadIdx.x;
+    if (c >= cols) return;
+    const int n = min(expert_demand[e], C);
+    float acc = 0.0f;
+    for (int r = 0; r < n; ++r) acc += load_as_float<S>(in, ((size_t)e * C_pad + r) * cols + c);
+    out[(size_t)e * cols + c] = acc;
+}
+
+// dgate_bias[e] = sum of dl over the pairs that selected e: one workgroup per expert, fixed reduction tree.
+__global__ __launch_bounds__(256) void bwd_gate_bias_kernel(const int32_t* __restrict__ topk_expert, const float* __restrict__ dl,
+                                                            long long P, float* __restrict__ dgate_bias) {
+    __shared__ float part[256];
+    const int e = blockIdx.x;
+    float acc = 0.0f;
+    for (long long p = threadIdx.x; p < P; p += 256)
+        if (topk_expert[p] == e) acc += dl[p];
+    part[threadIdx.x] = acc;
+    __syncthreads();
+    for (int s = 128; s >= 1; s >>= 1) {
+        if ((int)threadIdx.x < s) part[threadIdx.x] += part[threadIdx.x + s];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) dgate_bias[e] = part[0];
+}
+
+// One wavefront per token: dx_i = sum over kept choices of dxe[e_ij, slot_ij, :] (ascending j), then
+// + sum over all k choices of dl_ij * Wg[:, e_ij] (rows of WgT), in fp32.
+template <class S>
+__global__ __launch_bounds__(256) void bwd_dx_kernel(const void* __restrict__ dxe, const void* __restrict__ WgT,
+                                                     const int32_t* __restrict__ topk_expert, const int32_t* __restrict__ slot,
+                                                     const float* __restrict__ dl, int T, int H, int k, int E, int C, int C_pad,
+                                                     float* __restrict__ dx) {
+    const int t = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+    if (t >= T) return;
+    for (int c = lane; c < H; c += 64) {
+        float acc = 0.0f;
+        for (int j = 0; j < k; ++j) {
+            const int s = slot[(size_t)t * k + j], e = topk_expert[(size_t)t * k + j];
+            if (s >= 0 && s < C && e >= 0 && e < E) acc += load_as_float<S>(dxe, ((size_t)e * C_pad + s) * H + c);
+        }
+        for (int j = 0; j < k; ++j) {
+            const int e = topk_expert[(size_t)t * k + j];
+            if (e >= 0 && e < E) acc = fmaf(dl[(size_t)t * k + j], load_as_float<S>(WgT, (size_t)e * H + c), acc);
+        }
+        dx[(size_t)t * H + c] = acc;
+    }
+}
+
+}  // namespace
+
+hipError_t launch_bwd_gather(const void* x, const void* dout, const int32_t* slot_token, const float* slot_weight, int H, int E,
+                             int C, int C_pad, int dtype, void* xe, void* gy, hipStream_t s) {
+    const dim3 g((unsigned)((size_t)E * C_pad)), b(256);
+    if (dtype == 0) hipLaunchKernelGGL(bwd_gather_kernel<F32>, g, b, 0, s, x, dout, slot_token, slot_weight, H, C, C_pad, xe, gy);
+    else if (dtype == 1) hipLaunchKernelGGL(bwd_gather_kernel<BF16>, g, b, 0, s, x, dout, slot_token, slot_weight, H, C, C_pad, xe, gy);
+    else hipLaunchKernelGGL(bwd_gather_kernel<F16>, g, b, 0, s, x, dout, slot_token, slot_weight, H, C, C_pad, xe, gy);
+    return hipGetLastError();
+}
+
+hipError_t launch_bwd_act(const void* a, const void* g_in, const int32_t* expert_demand, int E, int C, int C_pad, int I, int act,
+                          int dtype, bool grad, void* out, hipStream_t s) {
+    const dim3 g((unsigned)((size_t)E * C_pad)), b(256);
+#define MOE_BWD_ACT(S_, M_) hipLaunchKernelGGL((bwd_act_kernel<S_, M_>), g, b, 0, s, a, g_in, expert_demand, C, C_pad, I, act, out)
+    if (dtype == 0) { if (grad) MOE_BWD_ACT(F32, 1); else MOE_BWD_ACT(F32, 0); }
+    else if (dtype == 1) { if (grad) MOE_BWD_ACT(BF16, 1); else MOE_BWD_ACT(BF16, 0); }
+    else { if (grad) MOE_BWD_ACT(F16, 1); else MOE_BWD_ACT(F16, 0); }
+#undef MOE_BWD_ACT
+    return hipGetLastError();
+}
+
+hipError_t launch_bwd_gate(const void* dout, const void* y, const int32_t* topk_expert, const float* topk_weight, const int32_t* slot,
+                           int T, int H, int k, int E, int C, int C_pad, int ld, int dtype, float* dl, void* dL, hipStream_t s) {
+    const dim3 g((unsigned)((T + 3) / 4)), b(256);
+    if (dtype == 0) hipLaunchKernelGGL(bwd_gate_kernel<F32>, g, b, 0, s, dout, y, topk_expert, topk_weight, slot, T, H, k, E, C, C_pad, ld, dl, dL);
+    else if (dtype == 1) hipLaunchKernelGGL(bwd_gate_kernel<BF16>, g, b, 0, s, dout, y, topk_expert, topk_weight, slot, T, H, k, E, C, C_pad, ld, dl, dL);
+    else hipLaunchKernelGGL(bwd_gate_kernel<F16>, g, b, 0, s, dout, y, topk_expert, topk_weight, slot, T, H, k, E, C, C_pad, ld, dl, dL);
+    return hipGetLastError();
+}
+
+hipError_t launch_bwd_transpose(const void* in, void* out, int groups, int R, int Cc, int ld_out, int dtype, hipStream_t s) {
+    if (groups <= 0 || R <= 0 || Cc <= 0) return hipSuccess;
+    if (groups > 65535 || (Cc + 31) / 32 > 65535) return hipErrorInvalidValue;
+    const dim3 g((unsigned)((ld_out + 31) / 32), (unsigned)((Cc + 31) / 32), (unsigned)groups), b(256);
+    if (dtype == 0) hipLaunchKernelGGL(bwd_transpose_kernel<float>, g, b, 0, s, (const float*)in, (float*)out, R, Cc, ld_out);
+    else hipLaunchKernelGGL(bwd_transpose_kernel<uint16_t>, g, b, 0, s, (const uint16_t*)in, (uint16_t*)out, R, Cc, ld_out);
+    return hipGetLastError();
+}
+
+hipError_t launch_bwd_colsum(const void* in, const int32_t* expert_demand, int E, int C, int C_pad, int cols, int dtype, float* out,
+                             hipStream_t s) {
+    if (E > 65535) return hipErrorInvalidValue;
+    const dim3 g((unsigned)((cols + 255) / 256), (unsigned)E), b(256);
+    if (dtype == 0) hipLaunchKernelGGL(bwd_colsum_kernel<F32>, g, b, 0, s, in, expert_demand, C, C_pad, cols, out);
+    else if (dtype == 1) hipLaunchKernelGGL(bwd_colsum_kernel<BF16>, g, b, 0, s, in, expert_demand, C, C_pad, cols, out);
+    else hipLaunchKernelGGL(bwd_colsum_kernel<F16>, g, b, 0, s, in, expert_demand, C, C_pad, cols, out);
+    return hipGetLastError();
+}
+
+hipError_t launch_bwd_gate_bias(const int32_t* topk_expert, const float* dl, int T, int k, int E, float* dgate_bias, hipStream_t s) {
+    hipLaunchKernelGGL(bwd_gate_bias_kernel, dim3((unsigned)E), dim3(256), 0, s, topk_expert, dl, (long long)T * k, dgate_bias);
+    return hipGetLastError();
+}
+
+hipError_t launch_bwd_dx(const void* dxe, const void* WgT, const int32_t* topk_expert, const int32_t* slot, const float* dl, int T, int H,
+                         int k, int E, int C, int C_pad, int dtype, float* dx, hipStream_t s) {
+    const dim3 g((unsigned)((T + 3) / 4)), b(256);
+    if (dtype == 0) hipLaunchKernelGGL(bwd_dx_kernel<F32>, g, b, 0, s, dxe, WgT, topk_expert, slot, dl, T, H, k, E, C, C_pad, dx);
+    else if (dtype == 1) hipLaunchKernelGGL(bwd_dx_kernel<BF16>, g, b, 0, s, dxe, WgT, topk_expert, slot, dl, T, H, k, E, C, C_pad, dx);
+    else hipLaunchKernelGGL(bwd_dx_kernel<F16>, g, b, 0, s, dxe, WgT, topk_expert, slot, dl, T, H, k, E, C, C_pad, dx);
+    return hipGetLastError();
+}
+
+}  // namespace moe

@@ -102,4 +102,24 @@ hipError_t launch_combine(const void* y, const int32_t* topk_expert, const float
                           const int32_t* slot, int T, int H, int k, int E, int C, int C_pad,
                           int dtype, void* out, hipStream_t stream);
 
+// ---- backward pass helpers (backward.hip); buffers per expert have C_pad rows ----------------------------
+// xe[e, s, :] = x[token] and gy[e, s, :] = weight * dout[token] for live slots, zeros for empty ones (s < C_pad)
+hipError_t launch_bwd_gather(const void* x, const void* dout, const int32_t* slot_token, const float* slot_weight, int H, int E,
+                             int C, int C_pad, int dtype, void* xe, void* gy, hipStream_t s);
+// over [E, C_pad, I]: out = phi(a), or with grad: out = g_in * phi'(a); rows beyond an expert's live rows give 0
+hipError_t launch_bwd_act(const void* a, const void* g_in, const int32_t* expert_demand, int E, int C, int C_pad, int I, int act,
+                          int dtype, bool grad, void* out, hipStream_t s);
+// dl[T, k] (fp32) and dL[T, ld] (storage type, dense): gradient with respect to the selected gate logits (k <= 64)
+hipError_t launch_bwd_gate(const void* dout, const void* y, const int32_t* topk_expert, const float* topk_weight, const int32_t* slot,
+                           int T, int H, int k, int E, int C, int C_pad, int ld, int dtype, float* dl, void* dL, hipStream_t s);
+// out[g][c][r] = in[g][r][c], r < R, c < Cc; rows of out have ld_out entries, zero at and beyond R
+hipError_t launch_bwd_transpose(const void* in, void* out, int groups, int R, int Cc, int ld_out, int dtype, hipStream_t s);
+// out[e][c] = sum over live rows of in[e][r][c] (fp32)
+hipError_t launch_bwd_colsum(const void* in, const int32_t* expert_demand, int E, int C, int C_pad, int cols, int dtype, float* out,
+                             hipStream_t s);
+hipError_t launch_bwd_gate_bias(const int32_t* topk_expert, const float* dl, int T, int k, int E, float* dgate_bias, hipStream_t s);
+// dx[t, :] = sum of the kept choices' rows of dxe + sum over choices of dl * WgT[expert, :]
+hipError_t launch_bwd_dx(const void* dxe, const void* WgT, const int32_t* topk_expert, const int32_t* slot, const float* dl, int T, int H,
+                         int k, int E, int C, int C_pad, int dtype, float* dx, hipStream_t s);
+
 }  // namespace moe

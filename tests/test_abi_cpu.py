@@ -104,6 +104,22 @@ def test_null_and_misaligned_pointers_are_rejected(lib):
     assert lib.moe_forward(ctypes.byref(cfg), ok, 16, *args) == -3
 
 
+def test_backward_entry_points_validate_on_the_host(lib):
+    ok = ctypes.c_void_p(4096)
+    cfg = moe.make_config(128, 64, 128, 4, 1, 2.0, "relu", "f32")
+    n = ctypes.c_size_t()
+    assert lib.moe_backward_workspace_bytes(ctypes.byref(cfg), ctypes.byref(n)) == 0 and n.value > 0
+    assert lib.moe_backward_workspace_bytes(ctypes.byref(cfg), None) == -1
+    assert lib.moe_backward(ctypes.byref(cfg), ok, 16, *([ok] * 17)) == -3          # workspace too small
+    args = [ok] * 17
+    args[9] = None                                                                 # dx missing
+    assert lib.moe_backward(ctypes.byref(cfg), ok, 1 << 40, *args) == -1
+    many = moe.make_config(128, 64, 128, 128, 65, 2.0, "relu", "f32")               # k > 64
+    assert lib.moe_backward_workspace_bytes(ctypes.byref(many), ctypes.byref(n)) == -2
+    flagged = moe.make_config(512, 256, 256, 4, 2, 1.0, "relu", "bf16", flags=1)
+    assert lib.moe_backward_workspace_bytes(ctypes.byref(flagged), ctypes.byref(n)) == -2
+
+
 def test_status_strings(lib):
     assert moe.moe_status_string(0) == "ok"
     assert len({moe.moe_status_string(c) for c in (0, -1, -2, -3, -4, -5, -6, -7)}) == 8

@@ -157,3 +157,35 @@ def test_backward_16bit_storage_is_widened_exactly(oracle):
                         base["slot"], G, T, H, I, E, "gelu_erf", "bf16")
     for n in a:
         np.testing.assert_array_equal(a[n], b[n], err_msg=n)
+
+
+def test_storage_rounding_of_16bit_intermediates_sets_the_gpu_tolerance(oracle):
+    # What a bf16 backward pass cannot avoid: the weight-gradient contraction takes h = phi(a) and gy = w dout as
+    # matrix-core operands, i.e. rounded to bf16 (and a was rounded before phi).  Emulated here with torch on the CPU
+    # (fp64 sums, roundings at exactly those three points) against the oracle: the worst element is off by about
+    # 3 % of the tensor's rms, more than the forward's 2e-2 bar and within the 5e-2 the GPU parity test allows.
+    import torch
+    from paper_2506_04667_amd.inputs import WORKLOADS, make_inputs, scaled
+    w = scaled(WORKLOADS["paper_bf16_e128"], name="emulation", seed=51, T=400, H=128, I=256, E=2, k=2, capacity_factor=1.0,
+               dtype="bf16", with_bias=True, act="gelu_tanh")
+    cpu = make_inputs(w)
+    r = oracle.forward(cpu["x"], cpu["Wg"], None, cpu["W1"], cpu["b1"], cpu["W2"], cpu["b2"], w.T, w.H, w.I, w.E, w.k, 1.0, w.act,
+                       w.dtype, compute_out=False)
+    te, sl, tw = r["topk_expert"], r["slot"], r["topk_weight"]
+    dout = torch.from_numpy(np.random.default_rng(8).standard_normal((w.T, w.H)).astype(np.float32)).to(torch.bfloat16)
+    ref = oracle.backward(cpu["x"], cpu["Wg"], None, cpu["W1"], cpu["b1"], cpu["W2"], cpu["b2"], te, sl, dout.double().numpy(),
+                          w.T, w.H, w.I, w.E, w.act, w.dtype)
+    bf = lambda t: t.to(torch.bfloat16).double()
+    worst = 0.0
+    rms = float(np.sqrt((ref["dW2"] ** 2).mean()))
+    for e in range(w.E):
+        idx = [(i, j) for i in range(w.T) for j in range(w.k) if te[i, j] == e and sl[i, j] >= 0]
+        toks = torch.tensor([i for i, _ in idx])
+        ws = torch.tensor([float(tw[i, j]) for i, j in idx], dtype=torch.float64)
+        a = bf(cpu["x"].double()[toks] @ cpu["W1"][e].double() + cpu["b1"][e].double())
+        h = bf(0.5 * a * (1 + torch.tanh(math.sqrt(2 / math.pi) * (a + 0.044715 * a ** 3))))
+        gy = bf(ws[:, None] * dout.double()[toks])
+        err = np.abs((h.T @ gy).numpy() - ref["dW2"][e])
+        bound = np.abs(ref["dW2"][e]) + rms
+        worst = max(worst, float((err / bound).max()))
+    assert 5e-3 < worst < 5e-2, worst
