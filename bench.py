@@ -70,6 +70,8 @@ def parse_args():
     ap.add_argument("--lib", default="", help="load this build of the library instead of the product (layout studies; see build.py --define)")
     ap.add_argument("--backward", action="store_true",
                     help="also time moe_backward (gradients under the forward's routing); reported as backward_ms, not part of value")
+    ap.add_argument("--single-launch-layer", action="store_true",
+                    help="the whole layer from one persistent launch (MOE_FLAG_LAYER_SINGLE_LAUNCH)")
     ap.add_argument("--graph", action="store_true",
                     help="replay the step from a captured HIP graph in the timed loop (the same kernels, one launch call)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -112,6 +114,7 @@ def main():
     if args.capacity_mode: over["capacity_mode"] = args.capacity_mode
     if args.drop_policy: over["drop_policy"] = args.drop_policy
     if args.single_launch_ffn: over["flags"] = 1
+    if args.single_launch_layer: over["flags"] = 4
     if over:
         w = scaled(w, name=w.name + "+" + ",".join("%s=%s" % kv for kv in sorted(over.items())), **over)
     if args.lib:
@@ -303,7 +306,7 @@ def main():
         binding_is_hbm = nbytes / (PEAK["hbm_gbs"] * 1e9) >= flops / (PEAK["mfma_tflops"][w.dtype] * 1e12)
         return (hbm, mfma) if binding_is_hbm else (mfma, hbm)
 
-    single = bool(getattr(w, "flags", 0) & 1)
+    single = bool(getattr(w, "flags", 0) & 5)
     if single:                                                     # one launch does both GEMMs: price them together
         roofline, other = roofs(ffn_ms / 2.0, H, I, "both FFN GEMMs in one launch: half its duration")
         roofline2 = None

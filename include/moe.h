@@ -94,7 +94,19 @@ typedef enum {
     /* Test aid, with MOE_FLAG_FFN_SINGLE_LAUNCH only: every dependency wait gets a target that cannot be
      * met and gives up after 16 polls, so that the give-up path runs with every kernel exiting normally;
      * y and out are then meaningless and moe_ffn_status returns MOE_ERR_FFN_DEPENDENCY_TIMEOUT. */
-    MOE_FLAG_DEBUG_DEPENDENCY_NEVER_MET = 2
+    MOE_FLAG_DEBUG_DEPENDENCY_NEVER_MET = 2,
+    /* moe_forward only, on its own (no other flag): the whole layer from ONE persistent launch, the paper's
+     * single-kernel operator (Alg. 1) on one GPU: gate, slot assignment, both FFN tasks and the combine are
+     * stages of one kernel, one workgroup per CU, separated by four device-wide barriers (where the paper has
+     * its scheduler and subscriber: on one GPU the stage boundaries are the only global dependencies), with
+     * the FFN tasks ordered by the completion counters of MOE_FLAG_FFN_SINGLE_LAUNCH.  The stages are the
+     * default path's device functions, so all outputs are bit-identical to it; it is no faster (back-to-back
+     * launches leave no gaps on this GPU).  16-bit storage, E <= 128 (a multiple of 8), H and I multiples of
+     * 64 and at least 256, token-order drop priority: otherwise MOE_ERR_UNSUPPORTED.  The barriers' state is
+     * a few words inside the library, shared by every launch on a GPU: calls with this flag must not overlap on
+     * one GPU.  All workgroups must be resident together (never more than one per CU is launched); the
+     * barriers' polls are bounded all the same, and moe_ffn_status reports a give-up (and resets the barrier). */
+    MOE_FLAG_LAYER_SINGLE_LAUNCH = 4
 } moe_flags;
 
 #define MOE_MAX_EXPERTS 8192

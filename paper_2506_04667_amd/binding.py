@@ -24,6 +24,7 @@ STATIC_SCRATCH_BYTES = 4 << 20
 FORWARD_EVENTS = 6
 FLAG_FFN_SINGLE_LAUNCH = 1
 FLAG_DEBUG_DEPENDENCY_NEVER_MET = 2
+FLAG_LAYER_SINGLE_LAUNCH = 4
 
 
 class MoeConfig(ctypes.Structure):

@@ -61,7 +61,9 @@ moe_status check_config(const moe_config* c) {
     if (c->E > MOE_MAX_EXPERTS) return MOE_ERR_UNSUPPORTED;
     if (c->drop_policy < MOE_DROP_TOKEN_MAJOR || c->drop_policy > MOE_DROP_CHOICE_MAJOR) return MOE_ERR_UNSUPPORTED;
     if (c->capacity_mode < MOE_CAPACITY_PER_CHOICE || c->capacity_mode > MOE_CAPACITY_LAYOUT) return MOE_ERR_UNSUPPORTED;
-    if (c->flags & ~(MOE_FLAG_FFN_SINGLE_LAUNCH | MOE_FLAG_DEBUG_DEPENDENCY_NEVER_MET)) return MOE_ERR_INVALID_ARG;
+    if (c->flags & ~(MOE_FLAG_FFN_SINGLE_LAUNCH | MOE_FLAG_DEBUG_DEPENDENCY_NEVER_MET | MOE_FLAG_LAYER_SINGLE_LAUNCH))
+        return MOE_ERR_INVALID_ARG;
+    if ((c->flags & MOE_FLAG_LAYER_SINGLE_LAUNCH) && (c->flags & ~MOE_FLAG_LAYER_SINGLE_LAUNCH)) return MOE_ERR_INVALID_ARG;
     if ((c->flags & MOE_FLAG_DEBUG_DEPENDENCY_NEVER_MET) && !(c->flags & MOE_FLAG_FFN_SINGLE_LAUNCH)) return MOE_ERR_INVALID_ARG;
     return MOE_OK;
 }
@@ -169,27 +171,20 @@ moe_status run_dispatch(const moe_config* c, const Plan& p, int32_t* counts, int
     return hip_status(moe::launch_pack(x, topk_expert, slot, c->T, c->H, c->k, c->E, p.C, p.C_pad, c->dtype, xe, s));
 }
 
+// The two GEMMs of the expert FFN as grouped-GEMM arguments.
 // xe: packed rows [E, C_pad, H]; or, with slot_token given, the token matrix x[T, H] whose rows the
 // first GEMM gathers through slot_token[E, C] (no packed copy).
-moe_status run_ffn(const moe_config* c, const Plan& p, void* ws, const void* xe, const int32_t* slot_token,
-                   const int32_t* expert_demand, const void* W1, const void* b1, const void* W2,
-                   const void* b2, void* y, bool units_ready, hipEvent_t between, hipStream_t s) {
+void ffn_gemms(const moe_config* c, const Plan& p, void* ws, const void* xe, const int32_t* slot_token,
+               const int32_t* expert_demand, const void* W1, const void* b1, const void* W2, const void* b2, void* y,
+               moe::GemmArgs* g1_out, moe::GemmArgs* g2_out) {
     void* h = ws_at(ws, p.off_h);
     const long long H = c->H, I = c->I;
     moe::GemmArgs g{};
     g.rows_dev = expert_demand; g.rows_fixed = 0; g.rows_cap = p.C;
     g.groups = c->E; g.max_rows = p.C;
     g.dtype = c->dtype; g.b_is_nk = false; g.c_f32 = false;
-    // both tasks walk the same live (expert, row tile) units
-    int32_t* units = (int32_t*)ws_at(ws, p.off_units);
-    hipError_t e = hipSuccess;
-    if (c->dtype != MOE_F32) {                          // only the 16-bit streaming kernels use the list
-        if (!units_ready) {
-            e = moe::launch_ffn_units(expert_demand, p.C, c->E, p.C, units, s);
-            if (e != hipSuccess) return MOE_ERR_HIP;
-        }
-        g.units = units;
-    }
+    // both tasks walk the same live (expert, row tile) units (only the 16-bit streaming kernels use the list)
+    if (c->dtype != MOE_F32) g.units = (int32_t*)ws_at(ws, p.off_units);
     // task t1: h = phi1(xe W1 + b1)
     moe::GemmArgs g1 = g;
     g1.A = xe; g1.a_group_stride = (long long)p.C_pad * H; g1.lda = c->H;
@@ -208,6 +203,20 @@ moe_status run_ffn(const moe_config* c, const Plan& p, void* ws, const void* xe,
     g2.C = y; g2.c_group_stride = (long long)p.C_pad * H; g2.ldc = c->H;
     g2.bias = b2; g2.bias_group_stride = H;
     g2.N = c->H; g2.K = c->I; g2.act = MOE_ACT_IDENTITY;
+    *g1_out = g1;
+    *g2_out = g2;
+}
+
+moe_status run_ffn(const moe_config* c, const Plan& p, void* ws, const void* xe, const int32_t* slot_token,
+                   const int32_t* expert_demand, const void* W1, const void* b1, const void* W2,
+                   const void* b2, void* y, bool units_ready, hipEvent_t between, hipStream_t s) {
+    moe::GemmArgs g1, g2;
+    ffn_gemms(c, p, ws, xe, slot_token, expert_demand, W1, b1, W2, b2, y, &g1, &g2);
+    hipError_t e = hipSuccess;
+    if (c->dtype != MOE_F32 && !units_ready) {
+        e = moe::launch_ffn_units(expert_demand, p.C, c->E, p.C, g1.units, s);
+        if (e != hipSuccess) return MOE_ERR_HIP;
+    }
     // Optional: one persistent launch for both tasks, a t2 tile starting when the t1 tiles it reads are stored
     // (the tile-level dependency of the paper's processors, Alg. 2).  No faster than two launches on one
     // MI355X at the paper's shapes, so it is opt-in (MOE_FLAG_FFN_SINGLE_LAUNCH; shapes checked by the caller).
@@ -257,6 +266,10 @@ moe_status forward_impl(const moe_config* cfg, void* workspace, size_t workspace
     if (workspace_bytes < p.total) return MOE_ERR_WORKSPACE_TOO_SMALL;
     st = check_single_launch(cfg, p, true);
     if (st != MOE_OK) return st;
+    const bool one_launch = (cfg->flags & MOE_FLAG_LAYER_SINGLE_LAUNCH) != 0;
+    if (one_launch && (cfg->drop_policy != MOE_DROP_TOKEN_MAJOR ||
+                       !moe::layer_fused_eligible(cfg->T, cfg->H, cfg->I, cfg->E, cfg->k, p.C_pad, cfg->dtype)))
+        return MOE_ERR_UNSUPPORTED;
     auto mark = [&](int i) { return !ev || hipEventRecord(ev[i], s) == hipSuccess; };
     float* logits = gate_logits ? gate_logits : (float*)ws_at(workspace, p.off_logits);
     int32_t* slot_token = (int32_t*)ws_at(workspace, p.off_slot_token);
@@ -264,6 +277,18 @@ moe_status forward_impl(const moe_config* cfg, void* workspace, size_t workspace
     void* y = ws_at(workspace, p.off_y);
     bool counts_ready = false;
     if (!mark(0)) return MOE_ERR_HIP;
+    if (one_launch) {
+        // Alg. 1 as one persistent kernel: the same stages from one launch, device-wide barriers in between
+        moe::GemmArgs g1, g2;
+        ffn_gemms(cfg, p, workspace, x, slot_token, expert_demand, W1, b1, W2, b2, y, &g1, &g2);
+        if (moe::launch_layer_fused(x, Wg, gate_bias, cfg->T, cfg->H, cfg->E, cfg->k, p.C, p.C_pad, cfg->dtype, logits, topk_expert,
+                                    topk_weight, (int32_t*)ws_at(workspace, p.off_counts), slot, expert_demand, slot_token,
+                                    slot_weight, g1, g2, out, s) != hipSuccess)
+            return MOE_ERR_HIP;
+        for (int i = 1; i < MOE_FORWARD_EVENTS; ++i)
+            if (!mark(i)) return MOE_ERR_HIP;
+        return MOE_OK;
+    }
     st = run_gate(cfg, p, workspace, x, Wg, gate_bias, logits, topk_expert, topk_weight, &counts_ready, s);
     if (st != MOE_OK) return st;
     if (!mark(1)) return MOE_ERR_HIP;
@@ -428,6 +453,7 @@ moe_status moe_init(void) {
     hipError_t e = moe::prepare_gate_fused();
     if (e == hipSuccess) e = moe::prepare_grouped_gemm();
     if (e == hipSuccess) e = moe::prepare_grouped_gemm_stream();
+    if (e == hipSuccess) e = moe::prepare_layer_fused();
     void* scratch_here = nullptr;
     if (e == hipSuccess) e = static_scratch(&scratch_here);
     if (e != hipSuccess) return MOE_ERR_HIP;
@@ -473,6 +499,10 @@ moe_status moe_ffn_status(const moe_config* cfg, const void* workspace, size_t w
         hipStreamSynchronize(s) != hipSuccess)
         return MOE_ERR_HIP;
     const int32_t f = f0 | f1;
+    if ((f & 1) && (cfg->flags & MOE_FLAG_LAYER_SINGLE_LAUNCH)) {
+        // a device-wide barrier of the single-launch layer may have been left half-way: start the next launch clean
+        if (moe::reset_layer_sync(s) != hipSuccess || hipStreamSynchronize(s) != hipSuccess) return MOE_ERR_HIP;
+    }
     if (f & 1) return MOE_ERR_FFN_DEPENDENCY_TIMEOUT;
     if (f & 2) return MOE_ERR_FFN_PLACEMENT;
     return MOE_OK;

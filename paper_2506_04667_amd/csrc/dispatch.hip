@@ -16,20 +16,12 @@
 //               slot is base + (pairs of the same expert in earlier steps) +
 //               (lower lanes naming the same expert in this step).  One more workgroup of
 //               this launch builds the FFN kernels' list of live (expert, row tile) units.
-#include "common.h"
-#include "kernels.h"
-#include "ffn_units.h"
+#include "route_body.h"
 
 namespace moe {
 namespace {
 
 constexpr int kChunkTokens = 64;                        // tokens per chunk = tokens per fused-gate workgroup
-
-// Position q in the order in which pairs claim slots -> index of the pair in the [T, k] tables.
-// Token-major: the tables' own order.  Choice-major: q = j * T + token.
-__device__ __forceinline__ long long pair_index(long long q, int T, int k, bool choice_major) {
-    return choice_major ? (q % T) * k + q / T : q;
-}
 
 // One workgroup per chunk: per-expert counts in an LDS histogram (integer atomics, so the result does not
 // depend on their order).
@@ -49,37 +41,18 @@ __global__ __launch_bounds__(256) void route_count_kernel(const int32_t* __restr
     for (int e = threadIdx.x; e < E; e += 256) counts[(size_t)blockIdx.x * E + e] = hist[e];
 }
 
-// One wavefront per expert: exclusive scan of its per-chunk counts, 64 chunks at a time.  The launch also
-// empties the routing table (slot_token = -1, slot_weight = 0).
+// One wavefront per expert: exclusive scan of its per-chunk counts.  The launch also empties the routing table
+// (slot_token = -1, slot_weight = 0).
 __global__ __launch_bounds__(256) void route_scan_kernel(int32_t* __restrict__ counts, int n_chunks, int E,
                                                          int32_t* __restrict__ expert_demand,
                                                          int32_t* __restrict__ slot_token,
                                                          float* __restrict__ slot_weight, long long EC) {
-    const long long gid = blockIdx.x * (long long)blockDim.x + threadIdx.x;
-    const long long stride = (long long)gridDim.x * blockDim.x;
-    for (long long q = gid; q < EC; q += stride) {
-        slot_token[q] = -1;
-        slot_weight[q] = 0.0f;
-    }
+    route_clear_tables(slot_token, slot_weight, EC, blockIdx.x * (long long)blockDim.x + threadIdx.x, (long long)gridDim.x * blockDim.x);
     const int e = blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
-    const int lane = threadIdx.x % kWave;
-    if (e >= E) return;
-    int carry = 0;
-    for (int c0 = 0; c0 < n_chunks; c0 += kWave) {
-        const int c = c0 + lane;
-        const int v = c < n_chunks ? counts[(size_t)c * E + e] : 0;
-        int incl = v;
-#pragma unroll
-        for (int off = 1; off < kWave; off <<= 1) {
-            const int t = __shfl_up(incl, off);
-            if (lane >= off) incl += t;
-        }
-        if (c < n_chunks) counts[(size_t)c * E + e] = carry + incl - v;
-        carry += __shfl(incl, kWave - 1);
-    }
-    if (lane == 0) expert_demand[e] = carry;
+    if (e < E) route_scan_expert(counts, n_chunks, E, e, expert_demand);
 }
 
+// One wavefront (one workgroup of 64 threads) per chunk; one more workgroup builds the FFN kernels' unit lists.
 __global__ __launch_bounds__(64) void route_scatter_kernel(const int32_t* __restrict__ topk_expert,
                                                            const float* __restrict__ topk_weight, long long P,
                                                            int chunk_pairs, int n_chunks, int T, bool choice_major,
@@ -95,40 +68,8 @@ __global__ __launch_bounds__(64) void route_scatter_kernel(const int32_t* __rest
         build_ffn_units(expert_demand, C, E, C, ffn_units, wave_total, 64);
         return;
     }
-    const int c = blockIdx.x, lane = threadIdx.x;
-    for (int e = lane; e < E; e += kWave) run[e] = base[(size_t)c * E + e];
-    __syncthreads();
-    const int nbits = E > 1 ? 32 - __clz(E - 1) : 0;
-    const long long p_end = ((long long)c + 1) * chunk_pairs < P ? ((long long)c + 1) * chunk_pairs : P;
-    for (long long p0 = (long long)c * chunk_pairs; p0 < p_end; p0 += kWave) {
-        const long long p = p0 + lane;
-        const long long m = p < p_end ? pair_index(p, T, k, choice_major) : 0;   // index in the [T, k] tables
-        int e = p < p_end ? topk_expert[m] : -1;
-        const bool valid = (e >= 0 && e < E);
-        if (!valid) e = 0;
-        // lanes naming the same expert: intersect ballots over the bits of e
-        unsigned long long same = __ballot(valid);
-        for (int b = 0; b < nbits; ++b) {
-            const bool bit = (e >> b) & 1;
-            const unsigned long long bal = __ballot(valid && bit);
-            same &= bit ? bal : ~bal;
-        }
-        const unsigned long long below = (1ull << lane) - 1ull;
-        const int rank = __popcll(same & below);
-        const int group = __popcll(same);
-        const int s = valid ? run[e] + rank : 0;
-        __syncthreads();
-        if (valid && rank == group - 1) run[e] = s + 1;
-        __syncthreads();
-        if (p < p_end) {
-            const bool kept = valid && s < C;
-            slot[m] = kept ? s : -1;
-            if (kept) {
-                slot_token[(size_t)e * C + s] = (int32_t)(m / k);
-                slot_weight[(size_t)e * C + s] = topk_weight[m];
-            }
-        }
-    }
+    route_scatter_chunk(topk_expert, topk_weight, P, chunk_pairs, T, choice_major, E, k, C, base, slot, slot_token, slot_weight,
+                        (int)blockIdx.x, run);
 }
 
 // One workgroup per token: the row is read once and written to each kept slot.

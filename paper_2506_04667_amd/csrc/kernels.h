@@ -102,6 +102,19 @@ hipError_t launch_combine(const void* y, const int32_t* topk_expert, const float
                           const int32_t* slot, int T, int H, int k, int E, int C, int C_pad,
                           int dtype, void* out, hipStream_t stream);
 
+// The whole layer in one persistent launch (layer_fused.hip): gate, slot assignment, both FFN GEMMs and the combine,
+// separated by device-wide barriers.  16-bit storage, E <= 128, shapes that the fused gate and the weight-streaming
+// FFN kernels take, token-order drop priority.  g1 / g2 describe the FFN GEMMs as for launch_ffn_stream_fused
+// (g1.A = x gathered through slot_token, g2.C = y); counts = route_chunks(T) * E ints.
+bool layer_fused_eligible(int T, int H, int I, int E, int k, int C_pad, int dtype);
+hipError_t launch_layer_fused(const void* x, const void* Wg, const float* gate_bias, int T, int H, int E, int k, int C, int C_pad,
+                              int dtype, float* logits, int32_t* topk_expert, float* topk_weight, int32_t* counts, int32_t* slot,
+                              int32_t* expert_demand, int32_t* slot_token, float* slot_weight, const GemmArgs& g1, const GemmArgs& g2,
+                              void* out, hipStream_t stream);
+hipError_t prepare_layer_fused();
+// zero the barrier words of the single-launch layer on the current device (after a launch that gave up)
+hipError_t reset_layer_sync(hipStream_t stream);
+
 // ---- backward pass helpers (backward.hip); buffers per expert have C_pad rows ----------------------------
 // xe[e, s, :] = x[token] and gy[e, s, :] = weight * dout[token] for live slots, zeros for empty ones (s < C_pad)
 hipError_t launch_bwd_gather(const void* x, const void* dout, const int32_t* slot_token, const float* slot_weight, int H, int E,

@@ -73,7 +73,7 @@ def test_workspace_covers_the_per_expert_buffers(lib):
     (dict(capacity_factor=0.0), -1), (dict(capacity_factor=float("nan")), -1), (dict(capacity_override=-1), -1),
     (dict(H=60), -2), (dict(I=100), -2), (dict(E=9000, k=1), -2), (dict(dtype=3), -2), (dict(act=9), -2),
     (dict(drop_policy=2), -2), (dict(drop_policy=-1), -2), (dict(capacity_mode=2), -2), (dict(capacity_mode=-1), -2),
-    (dict(flags=4), -1), (dict(flags=2), -1),                      # unknown bit; the test aid without the single launch
+    (dict(flags=8), -1), (dict(flags=2), -1), (dict(flags=5), -1),   # unknown bit; the test aid without the single launch; the layer flag with another
 ])
 def test_invalid_configs_are_rejected(lib, kw, code):
     base = dict(T=128, H=64, I=128, E=4, k=1, capacity_factor=2.0, capacity_override=0, dtype=0, act=0)

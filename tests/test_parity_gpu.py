@@ -176,6 +176,47 @@ def test_single_launch_ffn_opt_in(oracle):
         assert torch.equal(b0.out, b3.out)
 
 
+@pytest.mark.parametrize("case", [
+    dict(T=1500, H=256, I=512, E=16, k=2, capacity_factor=1.0, dtype="bf16", with_bias=True, act="gelu_erf"),
+    dict(T=700, H=256, I=256, E=8, k=1, capacity_factor=0.7, dtype="f16", with_bias=False, act="relu"),
+    dict(T=323, H=256, I=320, E=24, k=3, capacity_factor=1.0, dtype="bf16", with_bias=True, act="gelu_tanh"),   # ragged last tile, C = 41
+    dict(T=40000, H=256, I=256, E=64, k=2, capacity_factor=1.25, dtype="f16", with_bias=False, act="identity"),  # more gate tiles than workgroups
+    "paper_bf16_e128", "skew_f16_e128",
+])
+def test_single_launch_layer_opt_in(oracle, case):
+    # MOE_FLAG_LAYER_SINGLE_LAUNCH: the whole layer from one persistent kernel with device-wide barriers between
+    # its stages.  The stages are the default path's device functions, so every output must equal the default
+    # path's bit for bit; one case is also checked against the oracle on every row.
+    w = WORKLOADS[case] if isinstance(case, str) else scaled(WORKLOADS["paper_bf16_e128"], name="one_launch", seed=61, **case)
+    print("case", w, flush=True)
+    cpu = make_inputs(w)
+    dev = parity.to_device(cpu)
+    b0, host0 = parity.gpu_forward(w, dev)
+    w1 = scaled(w, flags=moe.FLAG_LAYER_SINGLE_LAUNCH)
+    for rep in range(2):                                      # twice: the barrier words and counters start clean each time
+        b1, host1 = parity.gpu_forward(w1, dev)
+        assert moe.moe_ffn_status(moe.config_of(w1), b1.workspace) == 0
+        for n in host0:
+            np.testing.assert_array_equal(host0[n], host1[n], err_msg=n)
+        assert torch.equal(b0.out, b1.out)
+    if not isinstance(case, str) and w.T < 2000:
+        print("  ", parity.check_layer(oracle, w, cpu, b1, host1), flush=True)
+
+
+def test_single_launch_layer_rejects_what_it_cannot_run():
+    for kw in (dict(dtype="f32"), dict(E=136), dict(I=200), dict(drop_policy="choice_major")):
+        base = dict(T=512, H=256, I=256, E=8, k=2, capacity_factor=1.0, dtype="bf16", act="relu")
+        base.update(kw)
+        w = scaled(WORKLOADS["paper_bf16_e128"], name="reject", seed=62, flags=moe.FLAG_LAYER_SINGLE_LAUNCH, **base)
+        cfg = moe.config_of(w)
+        b = moe.Buffers(cfg)
+        t = torch.zeros(1 << 20, dtype=torch.uint8, device="cuda")
+        with pytest.raises(moe.MoeError) as e:
+            moe.moe_forward(cfg, b.workspace, t, t, None, t, None, t, None, b.out, b.gate_logits, b.topk_expert, b.topk_weight, b.slot,
+                            b.expert_demand)
+        assert e.value.code == -2, kw
+
+
 def test_single_launch_ffn_give_up_is_reported():
     # driven from the host: a completion target no counter reaches and 16 polls per wait, so every second-GEMM
     # task gives up at once; every kernel still exits normally, the call returns ok (it does not synchronise) and
