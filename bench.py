@@ -181,6 +181,9 @@ def main():
     names = ["gate", "route", "ffn_gemm1", "ffn_gemm2", "combine"]
     fwd_ms = {n: sum(e[i].elapsed_time(e[i + 1]) for e in ev) / args.steps for i, n in enumerate(names)}
     fwd_ms["layer"] = sum(e[0].elapsed_time(e[NE - 1]) for e in ev) / args.steps
+    layer_stage_ms = None
+    if getattr(w, "flags", 0) & 4:                                 # the one launch's own stage clocks (last step, workgroup 0)
+        layer_stage_ms = {n: round(v, 4) for n, v in moe.moe_layer_stage_ms().items()}
 
     # ---- per-stage times of the staged entry points (the same kernels, called one by one)
     stage_calls = [
@@ -306,8 +309,12 @@ def main():
         binding_is_hbm = nbytes / (PEAK["hbm_gbs"] * 1e9) >= flops / (PEAK["mfma_tflops"][w.dtype] * 1e12)
         return (hbm, mfma) if binding_is_hbm else (mfma, hbm)
 
-    single = bool(getattr(w, "flags", 0) & 5)
-    if single:                                                     # one launch does both GEMMs: price them together
+    flags = getattr(w, "flags", 0)
+    if flags & 4:                                                  # one launch does the whole layer: the events see only its ends
+        roofline, other = roofs(fwd_ms["layer"] / 2.0, H, I, "whole layer in one launch: half its duration, an upper "
+                                "bound on one FFN GEMM's time")
+        roofline2 = None
+    elif flags & 1:                                                # one launch does both GEMMs: price them together
         roofline, other = roofs(ffn_ms / 2.0, H, I, "both FFN GEMMs in one launch: half its duration")
         roofline2 = None
     else:
@@ -325,7 +332,7 @@ def main():
     stage_gbs = {n: round(v / (stage_ms[n] * 1e-3) / 1e9, 1) for n, v in stage_bytes.items()}
     # the same for the stages as they run inside moe_forward (no packing there: routing tables only)
     fwd_bytes = {"gate": stage_bytes["gate"], "route": T * k * 4 + (T * k + 2 * E * C + E) * 4, "combine": stage_bytes["combine"]}
-    fwd_gbs = {n: round(v / (fwd_ms[n] * 1e-3) / 1e9, 1) for n, v in fwd_bytes.items()}
+    fwd_gbs = {n: round(v / (max(fwd_ms[n], 1e-6) * 1e-3) / 1e9, 1) for n, v in fwd_bytes.items()}
 
     cpu_baseline = None
     if args.cpu_baseline_tokens > 0:
@@ -359,6 +366,7 @@ def main():
         "ms_per_step_with_events": round(ms_with_events, 4),
         "steady_ms": None if steady_ms is None else round(steady_ms, 4),
         "forward_stage_ms": {n: round(v, 4) for n, v in fwd_ms.items()},
+        "single_launch_layer_stage_ms": layer_stage_ms,
         "forward_stage_hbm_gbs": fwd_gbs,
         "staged_stage_ms": {n: round(v, 4) for n, v in stage_ms.items()},
         "staged_stage_hbm_gbs": stage_gbs,

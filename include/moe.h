@@ -242,6 +242,19 @@ moe_status moe_dispatch_noalloc(const moe_config* cfg, const void* x, const int3
                                 const float* topk_weight, int32_t* slot, int32_t* expert_demand,
                                 int32_t* slot_token, float* slot_weight, void* xe, void* stream);
 
+/* Where the time of the last MOE_FLAG_LAYER_SINGLE_LAUNCH call on the current device went, as seen by its
+ * workgroup 0 (wall-clock stamps at the stage boundaries of the one kernel; HIP events cannot look inside a
+ * launch).  Waits for `stream`, then writes n <= MOE_LAYER_STAGES intervals in milliseconds to host_ms (host):
+ *   0 gate tiles              1 wait at barrier 1
+ *   2 table clearing + scan   3 wait at barrier 2
+ *   4 scatter (+ unit lists)  5 wait at barrier 3
+ *   6 first-GEMM tasks        7 second-GEMM tasks (their dependency waits included)
+ *   8 wait at barrier 4       9 combine
+ * A wait is short for the workgroup that arrives last and long for one that ran out of work early.  Meaningless
+ * before the first such call.  MOE_ERR_INVALID_ARG for a null pointer or n outside 0..MOE_LAYER_STAGES. */
+#define MOE_LAYER_STAGES 10
+moe_status moe_layer_stage_ms(double* host_ms, int32_t n, void* stream);
+
 /* Expert FFNs (tasks t1, t2 of Sec. 3.1; Eq. ffn in row-vector form): for each
  * expert e and each row r < min(expert_demand[e], C):
  *   y[e,r,:] = phi(xe[e,r,:] W1[e] + b1[e]) W2[e] + b2[e].

@@ -19,7 +19,9 @@ TORCH_DTYPE = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float1
 EXPORTS = ["moe_status_string", "moe_init", "moe_row_tile", "moe_capacity", "moe_workspace_bytes", "moe_forward",
            "moe_gate", "moe_route", "moe_dispatch", "moe_expert_ffn", "moe_combine", "moe_ffn_status", "moe_ffn_schedule",
            "moe_forward_timed", "moe_probe_stream", "moe_probe_mfma", "moe_dispatch_noalloc",
-           "moe_backward_workspace_bytes", "moe_backward"]
+           "moe_backward_workspace_bytes", "moe_backward", "moe_layer_stage_ms"]
+LAYER_STAGES = ("gate", "barrier1", "clear_scan", "barrier2", "scatter_units", "barrier3", "ffn_gemm1", "ffn_gemm2", "barrier4",
+                "combine")
 STATIC_SCRATCH_BYTES = 4 << 20
 FORWARD_EVENTS = 6
 FLAG_FFN_SINGLE_LAUNCH = 1
@@ -63,6 +65,8 @@ def load(path=None):
     lib.moe_ffn_status.argtypes = [cfgp, vp, ctypes.c_size_t, vp]
     lib.moe_ffn_schedule.restype = ctypes.c_int32
     lib.moe_ffn_schedule.argtypes = [ctypes.c_int32] * 8 + [i32p, i32p, ctypes.c_int32]
+    lib.moe_layer_stage_ms.restype = ctypes.c_int
+    lib.moe_layer_stage_ms.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.c_int32, vp]
     lib.moe_row_tile.restype = ctypes.c_int32
     lib.moe_row_tile.argtypes = []
     lib.moe_capacity.restype = ctypes.c_int
@@ -160,6 +164,13 @@ def moe_ffn_schedule(large_list, n_units_large, n_units_small, nrow_large, ncol,
 def moe_ffn_status(cfg, workspace, stream=None):
     """Status code of the last single-launch FFN on this workspace (synchronises the stream)."""
     return load().moe_ffn_status(ctypes.byref(cfg), _p(workspace), _ws_bytes(workspace), _stream(stream))
+
+
+def moe_layer_stage_ms(stream=None):
+    """Stage times (ms, by name) of the last single-launch layer, as seen by its workgroup 0 (synchronises the stream)."""
+    ms = (ctypes.c_double * len(LAYER_STAGES))()
+    _check(load().moe_layer_stage_ms(ms, len(LAYER_STAGES), _stream(stream)))
+    return dict(zip(LAYER_STAGES, ms))
 
 
 def moe_capacity(cfg):

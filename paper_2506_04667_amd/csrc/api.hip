@@ -508,6 +508,11 @@ moe_status moe_ffn_status(const moe_config* cfg, const void* workspace, size_t w
     return MOE_OK;
 }
 
+moe_status moe_layer_stage_ms(double* host_ms, int32_t n, void* stream) {
+    if (!host_ms || n < 0 || n > MOE_LAYER_STAGES) return MOE_ERR_INVALID_ARG;
+    return moe::layer_stage_ms(host_ms, n, (hipStream_t)stream) == hipSuccess ? MOE_OK : MOE_ERR_HIP;
+}
+
 moe_status moe_capacity(const moe_config* cfg, int32_t* C, int32_t* C_pad) {
     moe_status st = check_config(cfg);
     if (st != MOE_OK) return st;

@@ -114,6 +114,8 @@ hipError_t launch_layer_fused(const void* x, const void* Wg, const float* gate_b
 hipError_t prepare_layer_fused();
 // zero the barrier words of the single-launch layer on the current device (after a launch that gave up)
 hipError_t reset_layer_sync(hipStream_t stream);
+// Workgroup 0's stage times (ms) of the last single-launch layer on the current device; synchronises the stream.
+hipError_t layer_stage_ms(double* ms, int n, hipStream_t stream);
 
 // ---- backward pass helpers (backward.hip); buffers per expert have C_pad rows ----------------------------
 // xe[e, s, :] = x[token] and gy[e, s, :] = weight * dout[token] for live slots, zeros for empty ones (s < C_pad)

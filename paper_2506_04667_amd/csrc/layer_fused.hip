@@ -29,7 +29,8 @@
 
 // Barrier state of the single-launch layer: { arrivals, generation }.  A fixed array in device memory, zero when
 // the code object is loaded; every barrier leaves the arrival count at zero again.  In host code this name is only
-// a handle for hipGetSymbolAddress.
+// a handle for hipGetSymbolAddress.  Words 16.. hold workgroup 0's wall-clock stamps of the last launch (kLayerStamps
+// of 64 bits each), which moe_layer_stage_ms turns into stage times.
 static __device__ __align__(256) int32_t layer_sync[64];
 
 namespace moe {
@@ -37,6 +38,12 @@ namespace {
 
 constexpr int L_THREADS = 512, L_WAVES = L_THREADS / 64;
 constexpr int L_GATE_BN = 128;                          // experts covered by the gate tile of this kernel
+constexpr int kLayerStamps = 11, kLayerStampWord = 16;  // stamps of workgroup 0: start, before/after each barrier, ...
+
+// Workgroup 0 notes the constant-rate wall clock at the stage boundaries it passes.
+__device__ __forceinline__ void stamp(int32_t* sync, int i) {
+    if (blockIdx.x == 0 && threadIdx.x == 0) ((long long*)(sync + kLayerStampWord))[i] = (long long)wall_clock64();
+}
 
 struct LayerArgs {
     const unsigned char* x; const unsigned char* Wg; const float* gate_bias;
@@ -50,8 +57,11 @@ struct LayerArgs {
 };
 
 // Device-wide barrier for a grid whose workgroups are all resident.  Every thread calls it.
+// The workgroup barrier orders every thread's stores before thread 0 (they have reached the XCD's L2 by then: the
+// vector L1 writes through), so thread 0's agent-scope release, which writes that L2 back, covers them all: one
+// write-back per workgroup instead of one per wavefront.  Likewise thread 0's agent-scope acquire drops the stale
+// lines of the CU's L1 and of the L2 before the second workgroup barrier lets the other wavefronts read.
 __device__ __forceinline__ void grid_barrier(int32_t* sync, int nblocks, int spin_limit, int32_t* fault) {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");  // this thread's stores are visible to the whole device
     __syncthreads();
     if (threadIdx.x == 0) {
         // read the generation, then arrive: it cannot advance before this workgroup has arrived
@@ -66,12 +76,12 @@ __device__ __forceinline__ void grid_barrier(int32_t* sync, int nblocks, int spi
                     __hip_atomic_fetch_or(fault, kFaultWaitGaveUp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     break;
                 }
-                __builtin_amdgcn_s_sleep(8);
+                __builtin_amdgcn_s_sleep(2);
             }
         }
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
     }
     __syncthreads();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");  // nothing read from here on is a stale line
 }
 
 template <class S, int ACT>
@@ -83,17 +93,22 @@ __global__ __launch_bounds__(L_THREADS) void moe_layer_kernel(LayerArgs a) {
     int32_t* const fault = a.ffn.lists + ffn_units_small_offset(a.ffn.groups, a.ffn.max_rows);
     const int n_chunks = (a.T + G_BM - 1) / G_BM;       // a gate tile is one chunk of the slot assignment
 
+    stamp(a.sync, 0);
     // ---- gate: logits, top-k, combine weights, per-chunk expert counts
     for (int tile = bid; tile < n_chunks; tile += nb) {
         gate_fused_tile<S, L_GATE_BN>(a.x, a.Wg, a.gate_bias, a.T, a.H, a.E, a.k, a.logits, a.topk_expert, a.topk_weight, a.counts, tile);
         __syncthreads();                                // the tile's LDS is free again
     }
+    stamp(a.sync, 1);
     grid_barrier(a.sync, nb, a.ffn.spin_limit, fault);
+    stamp(a.sync, 2);
 
     // ---- slot assignment, part 1: chunk bases per expert; the routing table emptied
     route_clear_tables(a.slot_token, a.slot_weight, (long long)a.E * a.C, (long long)bid * L_THREADS + threadIdx.x, (long long)nb * L_THREADS);
     for (int e = gwave; e < a.E; e += waves) route_scan_expert(a.counts, n_chunks, a.E, e, a.expert_demand);
+    stamp(a.sync, 3);
     grid_barrier(a.sync, nb, a.ffn.spin_limit, fault);
+    stamp(a.sync, 4);
 
     // ---- slot assignment, part 2: slots and the routing table; the last workgroup also lists the live FFN units
     {
@@ -106,7 +121,9 @@ __global__ __launch_bounds__(L_THREADS) void moe_layer_kernel(LayerArgs a) {
             build_ffn_units(a.expert_demand, a.C, a.E, a.C, a.ffn.lists, (int*)smem, L_THREADS);
         }
     }
+    stamp(a.sync, 5);
     grid_barrier(a.sync, nb, a.ffn.spin_limit, fault);
+    stamp(a.sync, 6);
 
     // ---- expert FFNs: all first-GEMM tasks of this workgroup, then its second-GEMM tasks, each of which waits for
     // its unit's first-GEMM tiles (tile-level dependency by completion counter, as in the single-launch FFN)
@@ -115,12 +132,17 @@ __global__ __launch_bounds__(L_THREADS) void moe_layer_kernel(LayerArgs a) {
         if (threadIdx.x == 0) check_xcd_placement(a.ffn, xcd);
         stream_gemm<S, ACT, 0, true, false>(a.ffn, xcd, wg, wgs);
         __syncthreads();
+        stamp(a.sync, 7);
         stream_gemm<S, 3, 1, false, true>(a.ffn, xcd, wg, wgs);
     }
+    stamp(a.sync, 8);
     grid_barrier(a.sync, nb, a.ffn.spin_limit, fault);
+    stamp(a.sync, 9);
 
     // ---- combine
     combine_tokens<S>(a.ffn.ph[1].C, a.topk_expert, a.topk_weight, a.slot, a.T, a.H, a.k, a.E, a.C, a.C_pad, a.out, gwave, waves);
+    __syncthreads();
+    stamp(a.sync, 10);
 }
 
 // Device address of the barrier words on the current device, looked up once per device with that device current.
@@ -187,6 +209,20 @@ hipError_t reset_layer_sync(hipStream_t stream) {
     int32_t* p = nullptr;
     if (hipError_t e = layer_sync_ptr(&p); e != hipSuccess) return e;
     return hipMemsetAsync(p, 0, 2 * sizeof(int32_t), stream);
+}
+
+hipError_t layer_stage_ms(double* ms, int n, hipStream_t stream) {
+    int32_t* p = nullptr;
+    if (hipError_t e = layer_sync_ptr(&p); e != hipSuccess) return e;
+    long long t[kLayerStamps];
+    if (hipError_t e = hipMemcpyAsync(t, p + kLayerStampWord, sizeof(t), hipMemcpyDeviceToHost, stream); e != hipSuccess) return e;
+    if (hipError_t e = hipStreamSynchronize(stream); e != hipSuccess) return e;
+    int dev = 0, khz = 0;
+    if (hipError_t e = hipGetDevice(&dev); e != hipSuccess) return e;
+    if (hipError_t e = hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev); e != hipSuccess) return e;
+    if (khz <= 0) return hipErrorInvalidValue;
+    for (int i = 0; i < n && i < kLayerStamps - 1; ++i) ms[i] = (double)(t[i + 1] - t[i]) / (double)khz;
+    return hipSuccess;
 }
 
 bool layer_fused_eligible(int T, int H, int I, int E, int k, int C_pad, int dtype) {

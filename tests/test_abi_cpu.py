@@ -120,6 +120,14 @@ def test_backward_entry_points_validate_on_the_host(lib):
     assert lib.moe_backward_workspace_bytes(ctypes.byref(flagged), ctypes.byref(n)) == -2
 
 
+def test_layer_stage_clock_arguments_are_checked_on_the_host(lib):
+    ms = (ctypes.c_double * 10)()
+    assert lib.moe_layer_stage_ms(None, 10, None) == -1
+    assert lib.moe_layer_stage_ms(ms, 11, None) == -1
+    assert lib.moe_layer_stage_ms(ms, -1, None) == -1
+    assert len(moe.LAYER_STAGES) == 10
+
+
 def test_status_strings(lib):
     assert moe.moe_status_string(0) == "ok"
     assert len({moe.moe_status_string(c) for c in (0, -1, -2, -3, -4, -5, -6, -7)}) == 8

@@ -199,6 +199,8 @@ def test_single_launch_layer_opt_in(oracle, case):
         for n in host0:
             np.testing.assert_array_equal(host0[n], host1[n], err_msg=n)
         assert torch.equal(b0.out, b1.out)
+    stages = moe.moe_layer_stage_ms()                          # workgroup 0's clocks of the launch just checked
+    assert all(0.0 <= v < 1e3 for v in stages.values()) and sum(stages.values()) > 0.0, stages
     if not isinstance(case, str) and w.T < 2000:
         print("  ", parity.check_layer(oracle, w, cpu, b1, host1), flush=True)
 
