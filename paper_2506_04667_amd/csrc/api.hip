@@ -46,7 +46,8 @@ size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 struct Plan {
     int C, C_pad, E_pad, elem;
-    size_t off_wgt, off_logits, off_slot_token, off_slot_weight, off_counts, off_units, off_h, off_y, total;
+    size_t off_wgt, off_logits, off_slot_token, off_slot_weight, off_counts, off_units, off_partials, off_h, off_y, total;
+    int ldh;                                             // row pitch of h in elements
 };
 
 moe_status check_config(const moe_config* c) {
@@ -101,8 +102,12 @@ moe_status make_plan(const moe_config* c, Plan* p) {
     p->off_slot_token = take(E * (size_t)p->C * 4);
     p->off_slot_weight = take(E * (size_t)p->C * 4);
     p->off_counts = take((size_t)moe::route_chunks(c->T) * E * 4);
-    p->off_units = take(moe::ffn_units_ints(c->E, p->C) * 4);
-    p->off_h = take(rows * I * el);
+    // 16-bit storage: the two lists of live row tiles of the weight-streaming kernels; fp32: the list of live 64-row
+    // tiles of the equal-span kernel and its partial tiles
+    p->off_units = take((c->dtype == MOE_F32 ? moe::f32_units_ints(c->E, p->C) : moe::ffn_units_ints(c->E, p->C)) * 4);
+    p->off_partials = take(c->dtype == MOE_F32 ? moe::f32_partials_bytes(c->E, p->C, c->H, c->I) : 0);
+    p->ldh = c->I;                                       // (a pitch padded by one 128-byte line measured no different)
+    p->off_h = take(rows * (size_t)p->ldh * el);
     p->off_y = take(rows * H * el);
     p->total = off;
     return MOE_OK;
@@ -115,8 +120,8 @@ bool misaligned(const void* p) { return ((uintptr_t)p & 15u) != 0; }
 // through the routing table (moe_forward) instead of packed rows (moe_expert_ffn).
 moe_status check_single_launch(const moe_config* c, const Plan& p, bool gather) {
     if (!(c->flags & MOE_FLAG_FFN_SINGLE_LAUNCH)) return MOE_OK;
-    const bool ok = moe::stream_gemm_shape_ok(c->dtype, c->I, c->H, c->H, c->I, c->I, gather ? c->T : p.C_pad) &&
-                    moe::stream_gemm_shape_ok(c->dtype, c->H, c->I, c->I, c->H, c->H, p.C_pad);
+    const bool ok = moe::stream_gemm_shape_ok(c->dtype, c->I, c->H, c->H, c->I, p.ldh, gather ? c->T : p.C_pad) &&
+                    moe::stream_gemm_shape_ok(c->dtype, c->H, c->I, p.ldh, c->H, c->H, p.C_pad);
     return ok ? MOE_OK : MOE_ERR_UNSUPPORTED;
 }
 
@@ -165,7 +170,7 @@ moe_status run_dispatch(const moe_config* c, const Plan& p, int32_t* counts, int
     const bool choice_major = c->drop_policy == MOE_DROP_CHOICE_MAJOR;
     hipError_t e = moe::launch_route(topk_expert, topk_weight, c->T, c->E, c->k, p.C, choice_major,
                                      counts, counts_ready && !choice_major, slot, expert_demand,
-                                     slot_token, slot_weight, units, s);
+                                     slot_token, slot_weight, units, c->dtype == MOE_F32, s);
     if (e != hipSuccess) return MOE_ERR_HIP;
     if (!xe) return MOE_OK;
     return hip_status(moe::launch_pack(x, topk_expert, slot, c->T, c->H, c->k, c->E, p.C, p.C_pad, c->dtype, xe, s));
@@ -183,20 +188,21 @@ void ffn_gemms(const moe_config* c, const Plan& p, void* ws, const void* xe, con
     g.rows_dev = expert_demand; g.rows_fixed = 0; g.rows_cap = p.C;
     g.groups = c->E; g.max_rows = p.C;
     g.dtype = c->dtype; g.b_is_nk = false; g.c_f32 = false;
-    // both tasks walk the same live (expert, row tile) units (only the 16-bit streaming kernels use the list)
-    if (c->dtype != MOE_F32) g.units = (int32_t*)ws_at(ws, p.off_units);
+    // both tasks walk the same live (expert, row tile) units
+    g.units = (int32_t*)ws_at(ws, p.off_units);
+    if (c->dtype == MOE_F32) g.partials = (float*)ws_at(ws, p.off_partials);
     // task t1: h = phi1(xe W1 + b1)
     moe::GemmArgs g1 = g;
     g1.A = xe; g1.a_group_stride = (long long)p.C_pad * H; g1.lda = c->H;
     g1.a_row_index = slot_token; g1.a_index_stride = p.C;
     g1.a_rows_total = slot_token ? c->T : p.C_pad;
     g1.B = W1; g1.b_group_stride = H * I; g1.ldb = c->I;
-    g1.C = h; g1.c_group_stride = (long long)p.C_pad * I; g1.ldc = c->I;
+    g1.C = h; g1.c_group_stride = (long long)p.C_pad * p.ldh; g1.ldc = p.ldh;
     g1.bias = b1; g1.bias_group_stride = I;
     g1.N = c->I; g1.K = c->H; g1.act = c->act;
     // task t2: y = h W2 + b2
     moe::GemmArgs g2 = g;
-    g2.A = h; g2.a_group_stride = (long long)p.C_pad * I; g2.lda = c->I;
+    g2.A = h; g2.a_group_stride = (long long)p.C_pad * p.ldh; g2.lda = p.ldh;
     g2.a_row_index = nullptr; g2.a_index_stride = 0;
     g2.a_rows_total = p.C_pad;
     g2.B = W2; g2.b_group_stride = I * H; g2.ldb = c->H;
@@ -213,8 +219,9 @@ moe_status run_ffn(const moe_config* c, const Plan& p, void* ws, const void* xe,
     moe::GemmArgs g1, g2;
     ffn_gemms(c, p, ws, xe, slot_token, expert_demand, W1, b1, W2, b2, y, &g1, &g2);
     hipError_t e = hipSuccess;
-    if (c->dtype != MOE_F32 && !units_ready) {
-        e = moe::launch_ffn_units(expert_demand, p.C, c->E, p.C, g1.units, s);
+    if (!units_ready) {
+        e = c->dtype == MOE_F32 ? moe::launch_f32_units(expert_demand, p.C, c->E, p.C, g1.units, s)
+                                : moe::launch_ffn_units(expert_demand, p.C, c->E, p.C, g1.units, s);
         if (e != hipSuccess) return MOE_ERR_HIP;
     }
     // Optional: one persistent launch for both tasks, a t2 tile starting when the t1 tiles it reads are stored
@@ -268,7 +275,7 @@ moe_status forward_impl(const moe_config* cfg, void* workspace, size_t workspace
     if (st != MOE_OK) return st;
     const bool one_launch = (cfg->flags & MOE_FLAG_LAYER_SINGLE_LAUNCH) != 0;
     if (one_launch && (cfg->drop_policy != MOE_DROP_TOKEN_MAJOR ||
-                       !moe::layer_fused_eligible(cfg->T, cfg->H, cfg->I, cfg->E, cfg->k, p.C_pad, cfg->dtype)))
+                       !moe::layer_fused_eligible(cfg->T, cfg->H, cfg->I, p.ldh, cfg->E, cfg->k, p.C_pad, cfg->dtype)))
         return MOE_ERR_UNSUPPORTED;
     auto mark = [&](int i) { return !ev || hipEventRecord(ev[i], s) == hipSuccess; };
     float* logits = gate_logits ? gate_logits : (float*)ws_at(workspace, p.off_logits);
@@ -294,13 +301,12 @@ moe_status forward_impl(const moe_config* cfg, void* workspace, size_t workspace
     if (!mark(1)) return MOE_ERR_HIP;
     // Dispatch builds the routing table only; the first FFN GEMM gathers its rows from x through
     // slot_token, so the packed copy xe is never materialised on this path.
-    const bool units_here = cfg->dtype != MOE_F32;      // the scatter launch also lists the live FFN units
-    st = run_dispatch(cfg, p, (int32_t*)ws_at(workspace, p.off_counts),
-                      units_here ? (int32_t*)ws_at(workspace, p.off_units) : nullptr, x, topk_expert, topk_weight, slot,
-                      expert_demand, slot_token, slot_weight, nullptr, counts_ready, s);
+    // the scatter launch also lists the live FFN units
+    st = run_dispatch(cfg, p, (int32_t*)ws_at(workspace, p.off_counts), (int32_t*)ws_at(workspace, p.off_units), x, topk_expert,
+                      topk_weight, slot, expert_demand, slot_token, slot_weight, nullptr, counts_ready, s);
     if (st != MOE_OK) return st;
     if (!mark(2)) return MOE_ERR_HIP;
-    st = run_ffn(cfg, p, workspace, x, slot_token, expert_demand, W1, b1, W2, b2, y, units_here, ev ? ev[3] : nullptr, s);
+    st = run_ffn(cfg, p, workspace, x, slot_token, expert_demand, W1, b1, W2, b2, y, true, ev ? ev[3] : nullptr, s);
     if (st != MOE_OK) return st;
     if (!mark(4)) return MOE_ERR_HIP;
     st = run_combine(cfg, p, y, topk_expert, topk_weight, slot, out, s);
@@ -369,7 +375,7 @@ moe_status run_backward(const moe_config* c, const BwdPlan& b, void* ws, const v
 #define MOE_TRY(call) do { if ((call) != hipSuccess) return MOE_ERR_HIP; } while (0)
     // the routing tables again, from the selection the forward pass made (slots are a function of it)
     MOE_TRY(moe::launch_route(topk_expert, topk_weight, T, E, k, C, c->drop_policy == MOE_DROP_CHOICE_MAJOR, counts, false, slot,
-                              demand, slot_token, slot_weight, units, s));
+                              demand, slot_token, slot_weight, units, false, s));
     MOE_TRY(moe::launch_transpose_pad(Wg, wgt, H, E, p.E_pad, dt, s));
     MOE_TRY(moe::launch_bwd_gather(x, dout, slot_token, slot_weight, H, E, C, C_pad, dt, xe, gy, s));
     // grouped GEMMs over the experts' live rows
@@ -454,6 +460,7 @@ moe_status moe_init(void) {
     if (e == hipSuccess) e = moe::prepare_grouped_gemm();
     if (e == hipSuccess) e = moe::prepare_grouped_gemm_stream();
     if (e == hipSuccess) e = moe::prepare_layer_fused();
+    if (e == hipSuccess) e = moe::prepare_gemm_f32();
     void* scratch_here = nullptr;
     if (e == hipSuccess) e = static_scratch(&scratch_here);
     if (e != hipSuccess) return MOE_ERR_HIP;

@@ -61,11 +61,12 @@ __global__ __launch_bounds__(64) void route_scatter_kernel(const int32_t* __rest
                                                            int32_t* __restrict__ slot_token,
                                                            float* __restrict__ slot_weight,
                                                            const int32_t* __restrict__ expert_demand,
-                                                           int32_t* __restrict__ ffn_units) {
+                                                           int32_t* __restrict__ ffn_units, bool f32_units) {
     extern __shared__ int32_t run[];                 // [E] slots handed out so far, per expert
     __shared__ int wave_total[32];
     if ((int)blockIdx.x == n_chunks) {               // the extra workgroup: list of live FFN units
-        build_ffn_units(expert_demand, C, E, C, ffn_units, wave_total, 64);
+        if (f32_units) build_row_units(expert_demand, C, E, C, ffn_units, wave_total, 64);
+        else build_ffn_units(expert_demand, C, E, C, ffn_units, wave_total, 64);
         return;
     }
     route_scatter_chunk(topk_expert, topk_weight, P, chunk_pairs, T, choice_major, E, k, C, base, slot, slot_token, slot_weight,
@@ -96,7 +97,7 @@ int route_chunks(int T) { return (T + kChunkTokens - 1) / kChunkTokens; }
 
 hipError_t launch_route(const int32_t* topk_expert, const float* topk_weight, int T, int E, int k, int C,
                         bool choice_major, int32_t* counts, bool counts_ready, int32_t* slot, int32_t* expert_demand,
-                        int32_t* slot_token, float* slot_weight, int32_t* ffn_units, hipStream_t stream) {
+                        int32_t* slot_token, float* slot_weight, int32_t* ffn_units, bool f32_units, hipStream_t stream) {
     const long long P = (long long)T * k;
     const int n_chunks = route_chunks(T);
     const int chunk_pairs = kChunkTokens * k;
@@ -108,7 +109,7 @@ hipError_t launch_route(const int32_t* topk_expert, const float* topk_weight, in
                        expert_demand, slot_token, slot_weight, EC);
     hipLaunchKernelGGL(route_scatter_kernel, dim3(n_chunks + (ffn_units ? 1 : 0)), dim3(64),
                        (size_t)E * sizeof(int32_t), stream, topk_expert, topk_weight, P, chunk_pairs, n_chunks, T,
-                       choice_major, E, k, C, counts, slot, slot_token, slot_weight, expert_demand, ffn_units);
+                       choice_major, E, k, C, counts, slot, slot_token, slot_weight, expert_demand, ffn_units, f32_units);
     return hipGetLastError();
 }
 

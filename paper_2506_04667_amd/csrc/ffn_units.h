@@ -118,4 +118,69 @@ __device__ __forceinline__ void build_ffn_units(const int32_t* __restrict__ rows
     }
 }
 
+// ---- fp32 storage: one list of live (group, 256-row tile) units for the kernel whose workgroups each take an equal
+// share of the matrix-core work of all live tiles:
+//   { n, ids[cap], cum[cap + 1] },  cap = groups * nrow,  id = g * nrow + row tile, in order of group;
+//   cum[u] = sum of the weights of the units before u (cum[n] = their total).  A unit's weight is the time one of
+//   its iterations takes, in twelfths of a full tile's: its b live 32-row MFMA tiles are dealt to the two wavefront
+//   rows in turn, so the matrix cores need ceil(b / 2) / 4 of the full time; an iteration of a unit with one or two
+//   live MFMA tiles is bound by its operand copies, which do not shrink with b (measured: 1.95 us against 8.6 us).
+constexpr int kF32UnitRows = 256, kF32BlockRows = 32, kF32FullWeight = 12;
+__host__ __device__ inline int f32_unit_weight(int live_blocks) {
+    const int w = 3 * ((live_blocks + 1) / 2);
+    return w > kF32FullWeight ? kF32FullWeight : w;
+}
+constexpr int kF32MaxWorkgroups = 256;                  // its grid is min(CUs, this); two partial tiles per workgroup
+__host__ __device__ inline int f32_units_nrow(int max_rows) { return (max_rows + kF32UnitRows - 1) / kF32UnitRows; }
+__host__ __device__ inline long long f32_units_total_ints(int groups, int max_rows) {
+    return 2 + 2ll * groups * f32_units_nrow(max_rows);
+}
+
+// Called by every thread of ONE workgroup of `nthreads` threads (a multiple of 64, at most 1024);
+// `wave_total` is an LDS array of at least 32 ints.
+__device__ __forceinline__ void build_row_units(const int32_t* __restrict__ rows_dev, int rows_cap, int groups, int max_rows,
+                                                int32_t* __restrict__ out, int* wave_total, int nthreads) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nwaves = nthreads >> 6;
+    const int nrow = f32_units_nrow(max_rows);
+    constexpr int unit_blocks = kF32UnitRows / kF32BlockRows;
+    int32_t* ids = out + 1;
+    int32_t* cum = out + 1 + (long long)groups * nrow;
+    int carry_u = 0, carry_b = 0;                       // units and their weights of the groups before this pass
+    for (int g0 = 0; g0 < groups; g0 += nthreads) {
+        const int g = g0 + tid;
+        const int rows = g < groups ? max(min(min(rows_dev[g], rows_cap), max_rows), 0) : 0;
+        const int nu = (rows + kF32UnitRows - 1) / kF32UnitRows;
+        const int last_blocks = (rows + kF32BlockRows - 1) / kF32BlockRows - (nu - 1) * unit_blocks;   // of the last unit
+        const int nb = nu > 0 ? (nu - 1) * kF32FullWeight + f32_unit_weight(last_blocks) : 0;          // the group's weight
+        int incl_u = nu, incl_b = nb;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const int up_u = __shfl_up(incl_u, d), up_b = __shfl_up(incl_b, d);
+            if (lane >= d) { incl_u += up_u; incl_b += up_b; }
+        }
+        if (lane == 63) { wave_total[wave] = incl_u; wave_total[16 + wave] = incl_b; }
+        __syncthreads();
+        int before_u = 0, total_u = 0, before_b = 0, total_b = 0;
+        for (int wv = 0; wv < nwaves; ++wv) {
+            const int tu = wave_total[wv], tb = wave_total[16 + wv];
+            before_u += wv < wave ? tu : 0;
+            total_u += tu;
+            before_b += wv < wave ? tb : 0;
+            total_b += tb;
+        }
+        const int start_u = carry_u + before_u + incl_u - nu, start_b = carry_b + before_b + incl_b - nb;
+        for (int rt = 0; rt < nu; ++rt) {
+            ids[start_u + rt] = g * nrow + rt;
+            cum[start_u + rt] = start_b + rt * kF32FullWeight;
+        }
+        carry_u += total_u;
+        carry_b += total_b;
+        __syncthreads();
+    }
+    if (tid == 0) {
+        out[0] = carry_u;
+        cum[carry_u] = carry_b;
+    }
+}
+
 }  // namespace moe

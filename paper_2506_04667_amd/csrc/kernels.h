@@ -25,6 +25,9 @@ struct GemmArgs {
     // optional scratch block written by launch_ffn_units for the same rows_dev / rows_cap / groups / max_rows
     // (list of live units and completion counters); the weight-streaming kernels need it
     int32_t* units;
+    // fp32 storage only, optional: scratch of f32_partials_bytes() for the sums of tiles that two or more workgroups
+    // share (units is then the list written by launch_f32_units)
+    float* partials;
     int groups; int max_rows;                               // grid extent in rows
     int N; int K;
     int act;                                                // moe_act, applied after the bias
@@ -65,6 +68,16 @@ hipError_t launch_ffn_stream_fused(const GemmArgs& g1, const GemmArgs& g2, bool 
 // Offsets (in ints) of the scratch block's two fault words (equal when there is no large-tile list).
 void ffn_units_fault_words(int groups, int max_rows, long long* first, long long* second);
 
+// fp32 expert FFN tasks over the live work only: persistent workgroups that each take an equal span of the K-tiles of
+// all live 64-row tiles (gemm_f32.hip); launch_grouped_gemm routes eligible calls to it.  GemmArgs::units is the list
+// written by launch_f32_units (f32_units_ints() ints) for the same rows_dev / rows_cap / groups / max_rows.
+bool f32_stream_eligible(const GemmArgs& a);
+hipError_t launch_gemm_f32_stream(const GemmArgs& a, hipStream_t stream);
+size_t f32_units_ints(int groups, int max_rows);
+size_t f32_partials_bytes(int groups, int max_rows, int H, int I);   // shared by the H -> I and the I -> H GEMM
+hipError_t launch_f32_units(const int32_t* rows_dev, int rows_cap, int groups, int max_rows, int32_t* units, hipStream_t stream);
+hipError_t prepare_gemm_f32();
+
 // WgT[n][h] = Wg[h][n] for n < E, zero rows for E <= n < E_pad.
 hipError_t launch_transpose_pad(const void* Wg, void* WgT, int H, int E, int E_pad, int dtype,
                                 hipStream_t stream);
@@ -85,13 +98,13 @@ hipError_t launch_topk(const float* logits, int T, int E, int k, int32_t* topk_e
 // Token-order slot assignment.  The pairs are cut into chunks of route_chunk_tokens() tokens; `counts` is
 // scratch of route_chunks(T) * E ints.  With counts_ready the per-chunk expert counts are already there (the
 // fused gate wrote them).  With ffn_units != nullptr the last launch also builds the FFN kernels' unit list
-// for rows_cap = max_rows = C (see launch_ffn_units).
+// for rows_cap = max_rows = C (see launch_ffn_units), or with f32_units the fp32 kernel's list (launch_f32_units).
 int route_chunk_tokens();
 int route_chunks(int T);
 // choice_major: the pairs are taken in the order (choice rank, token) instead of (token, choice rank).
 hipError_t launch_route(const int32_t* topk_expert, const float* topk_weight, int T, int E, int k, int C,
                         bool choice_major, int32_t* counts, bool counts_ready, int32_t* slot, int32_t* expert_demand,
-                        int32_t* slot_token, float* slot_weight, int32_t* ffn_units, hipStream_t stream);
+                        int32_t* slot_token, float* slot_weight, int32_t* ffn_units, bool f32_units, hipStream_t stream);
 
 // xe[e][slot][:] = x[token][:] for every kept (token, choice).
 hipError_t launch_pack(const void* x, const int32_t* topk_expert, const int32_t* slot, int T, int H,
@@ -106,7 +119,7 @@ hipError_t launch_combine(const void* y, const int32_t* topk_expert, const float
 // separated by device-wide barriers.  16-bit storage, E <= 128, shapes that the fused gate and the weight-streaming
 // FFN kernels take, token-order drop priority.  g1 / g2 describe the FFN GEMMs as for launch_ffn_stream_fused
 // (g1.A = x gathered through slot_token, g2.C = y); counts = route_chunks(T) * E ints.
-bool layer_fused_eligible(int T, int H, int I, int E, int k, int C_pad, int dtype);
+bool layer_fused_eligible(int T, int H, int I, int ldh, int E, int k, int C_pad, int dtype);
 hipError_t launch_layer_fused(const void* x, const void* Wg, const float* gate_bias, int T, int H, int E, int k, int C, int C_pad,
                               int dtype, float* logits, int32_t* topk_expert, float* topk_weight, int32_t* counts, int32_t* slot,
                               int32_t* expert_demand, int32_t* slot_token, float* slot_weight, const GemmArgs& g1, const GemmArgs& g2,

@@ -225,11 +225,11 @@ hipError_t layer_stage_ms(double* ms, int n, hipStream_t stream) {
     return hipSuccess;
 }
 
-bool layer_fused_eligible(int T, int H, int I, int E, int k, int C_pad, int dtype) {
+bool layer_fused_eligible(int T, int H, int I, int ldh, int E, int k, int C_pad, int dtype) {
     static_assert(G_THREADS == L_THREADS && THREADS == L_THREADS, "every stage of the layer runs with the same workgroup size");
     static_assert(GateCfg<BF16, L_GATE_BN>::LDS_BYTES <= LDS_BYTES, "the gate tile fits in the FFN kernel's LDS");
     return dtype != 0 && E <= L_GATE_BN && gate_fused_eligible(T, H, E, k, dtype) &&
-           stream_gemm_shape_ok(dtype, I, H, H, I, I, T) && stream_gemm_shape_ok(dtype, H, I, I, H, H, C_pad) &&
+           stream_gemm_shape_ok(dtype, I, H, H, I, ldh, T) && stream_gemm_shape_ok(dtype, H, I, ldh, H, H, C_pad) &&
            (long long)L_WAVES * E * 4 + 64 * 4 <= LDS_BYTES;
 }
 

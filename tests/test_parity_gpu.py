@@ -119,6 +119,42 @@ def test_streaming_ffn_shapes(oracle, case):
     assert torch.equal(b.out, b2.out)
 
 
+# ------------------------------------------------------------ fp32 storage: the equal-span FFN kernel and its fix-up pass
+
+# (the kernel takes a GEMM with fewer than 4 x 256 tiles of 256 x 256 at full capacity and at least 8 x 256 K-tiles of 32)
+@pytest.mark.parametrize("case", [
+    # one live expert of nine, long K: one or two live tiles for all the workgroups, so every tile is cut into many pieces
+    dict(T=150, H=4096, I=512, E=9, k=1, capacity_factor=9.0, with_bias=True, act="gelu_erf", empty=(0, 1, 2, 3, 4, 5, 7, 8)),
+    # short K (four K-tiles per tile): ranges of whole tiles with few cuts; 128 units
+    dict(T=6000, H=128, I=1024, E=64, k=2, capacity_factor=1.5, with_bias=True, act="relu"),
+    # two units per expert, the second one light; experts nobody picks; K not a multiple of the K-tile, ragged last column tile
+    dict(T=2000, H=1000, I=776, E=11, k=2, capacity_factor=1.25, with_bias=True, act="gelu_tanh", empty=(0, 4, 5, 10)),
+    # drops (C = 47: every unit has two live MFMA row tiles), more experts than XCDs, no bias
+    dict(T=520, H=2048, I=512, E=20, k=3, capacity_factor=0.6, with_bias=False, act="identity", empty=(3, 19)),
+    # a few rows per expert, very long K
+    dict(T=5, H=8192, I=256, E=8, k=2, capacity_factor=1.0, with_bias=False, act="relu"),
+    # skewed routing: units of every weight
+    dict(T=4096, H=256, I=1024, E=32, k=2, capacity_factor=2.0, with_bias=True, act="gelu_erf", zipf_s=1.2),
+])
+def test_f32_equal_span_ffn_shapes(oracle, case):
+    case = dict(case)
+    empty = case.pop("empty", ())
+    w = scaled(WORKLOADS["small_f32"], name="f32_span", seed=71, dtype="f32", **case)
+    gb = None
+    if empty:
+        gb = torch.zeros(w.E)
+        gb[list(empty)] = -1.0e4
+    cpu, dev, b, host, rep = _run(oracle, w, gate_bias=gb)
+    for e in empty:
+        assert host["expert_demand"][e] == 0
+    # the staged path (its own launch for the unit list, packed rows) and the fused call agree bit for bit, and so
+    # does a second run: the pieces of a shared tile are added in a fixed order
+    b2, host2 = parity.gpu_forward(w, dict(dev), staged=True)
+    assert torch.equal(b.out, b2.out)
+    b3, host3 = parity.gpu_forward(w, dict(dev))
+    assert torch.equal(b.out, b3.out)
+
+
 def test_many_experts_few_rows_each(oracle):
     # 2048 experts of at most 40 rows: the unit lists are built in several passes of the builder's workgroup, every
     # live unit is a 128-row tile, most experts get a handful of rows and some none; gate on the unfused path (E > 256)
