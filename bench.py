@@ -284,7 +284,7 @@ def main():
     ffn_ms = fwd_ms["ffn_gemm1"] + fwd_ms["ffn_gemm2"]
     live = int((demand > 0).sum())                                 # experts nobody picked cost no weight traffic
     traffic = read_traffic(w.name, w.dtype)
-    kname = "ffn_gemm_stream_kernel" if w.dtype != "f32" else "grouped_gemm_kernel"
+    kname = "ffn_gemm_stream_kernel" if w.dtype != "f32" else "grouped_gemm_kernel, or ffn_f32_stream_kernel with its fix-up pass"
 
     def roofs(launch_ms, K, N, which):
         flops = 2.0 * R * K * N
