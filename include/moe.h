@@ -312,6 +312,20 @@ int32_t moe_ffn_schedule(int32_t large_list, int32_t n_units_large, int32_t n_un
                          int32_t ncol, int32_t xcd, int32_t wg, int32_t wgs, int32_t* list_index, int32_t* col_tile,
                          int32_t max_tasks);
 
+/* Host arithmetic only (no device work): how the fp32 FFN kernel that gives every workgroup an equal share of the
+ * live work deals one GEMM (Sec. 3.1 tasks, cut along K as well; the same inline functions run inside the kernels).
+ * rows[groups] (host): live rows per expert (values above `capacity` count as capacity); N, K: the GEMM's width and
+ * depth; `workgroups`: the grid.  Writes the list of live (expert, 256-row tile) units as the device builds it:
+ * unit_id[u] = expert * ceil(capacity / 256) + row tile, unit_cum[u] = sum of the weights of the units before u
+ * (n + 1 entries; a unit's weight is the time of one of its iterations in twelfths of a full tile's).  Iterations are
+ * numbered unit * ncol * nk + column tile * nk + K-tile (ncol = ceil(N / 256), nk = ceil(K / 32));
+ * first_iteration[w] (workgroups + 1 entries) is where workgroup w starts, fix_tile[w] the tile (unit * ncol + column
+ * tile) whose pieces the second pass adds up in workgroup w's name, or -1.  Returns the number of units, or -1 on
+ * invalid arguments (null pointers, non-positive sizes, max_units < groups * ceil(capacity / 256)).  For tests. */
+int32_t moe_f32_ffn_schedule(const int32_t* rows, int32_t groups, int32_t capacity, int32_t N, int32_t K,
+                             int32_t workgroups, int64_t* first_iteration, int64_t* fix_tile, int32_t* unit_id,
+                             int32_t* unit_cum, int32_t max_units);
+
 /* Outcome of the single-launch FFN of the last moe_forward / moe_expert_ffn enqueued on `stream` with this
  * configuration and workspace (Alg. 2's dependency between t1 and t2 tiles, resolved by bounded waits).
  * Unlike every other call this one SYNCHRONISES: it copies the two fault words of the workspace to the host

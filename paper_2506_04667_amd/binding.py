@@ -19,7 +19,7 @@ TORCH_DTYPE = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float1
 EXPORTS = ["moe_status_string", "moe_init", "moe_row_tile", "moe_capacity", "moe_workspace_bytes", "moe_forward",
            "moe_gate", "moe_route", "moe_dispatch", "moe_expert_ffn", "moe_combine", "moe_ffn_status", "moe_ffn_schedule",
            "moe_forward_timed", "moe_probe_stream", "moe_probe_mfma", "moe_dispatch_noalloc",
-           "moe_backward_workspace_bytes", "moe_backward", "moe_layer_stage_ms"]
+           "moe_backward_workspace_bytes", "moe_backward", "moe_layer_stage_ms", "moe_f32_ffn_schedule"]
 LAYER_STAGES = ("gate", "barrier1", "clear_scan", "barrier2", "scatter_units", "barrier3", "ffn_gemm1", "ffn_gemm2", "barrier4",
                 "combine")
 STATIC_SCRATCH_BYTES = 4 << 20
@@ -65,6 +65,9 @@ def load(path=None):
     lib.moe_ffn_status.argtypes = [cfgp, vp, ctypes.c_size_t, vp]
     lib.moe_ffn_schedule.restype = ctypes.c_int32
     lib.moe_ffn_schedule.argtypes = [ctypes.c_int32] * 8 + [i32p, i32p, ctypes.c_int32]
+    i64p = ctypes.POINTER(ctypes.c_int64)
+    lib.moe_f32_ffn_schedule.restype = ctypes.c_int32
+    lib.moe_f32_ffn_schedule.argtypes = [i32p] + [ctypes.c_int32] * 5 + [i64p, i64p, i32p, i32p, ctypes.c_int32]
     lib.moe_layer_stage_ms.restype = ctypes.c_int
     lib.moe_layer_stage_ms.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.c_int32, vp]
     lib.moe_row_tile.restype = ctypes.c_int32
@@ -164,6 +167,22 @@ def moe_ffn_schedule(large_list, n_units_large, n_units_small, nrow_large, ncol,
 def moe_ffn_status(cfg, workspace, stream=None):
     """Status code of the last single-launch FFN on this workspace (synchronises the stream)."""
     return load().moe_ffn_status(ctypes.byref(cfg), _p(workspace), _ws_bytes(workspace), _stream(stream))
+
+
+def moe_f32_ffn_schedule(rows, capacity, N, K, workgroups):
+    """Host replay of the fp32 equal-share FFN dealing: (unit ids, weight prefix sums, first iteration per workgroup
+    [workgroups + 1], tile to fix per workgroup [-1 = none])."""
+    groups = len(rows)
+    cap = groups * (-(-capacity // 256))
+    r = (ctypes.c_int32 * groups)(*[int(v) for v in rows])
+    first = (ctypes.c_int64 * (workgroups + 1))()
+    fix = (ctypes.c_int64 * workgroups)()
+    ids = (ctypes.c_int32 * max(cap, 1))()
+    cum = (ctypes.c_int32 * (cap + 1))()
+    n = load().moe_f32_ffn_schedule(r, groups, capacity, N, K, workgroups, first, fix, ids, cum, cap)
+    if n < 0:
+        raise MoeError(-1, "moe_f32_ffn_schedule")
+    return list(ids[:n]), list(cum[:n + 1]), list(first), list(fix)
 
 
 def moe_layer_stage_ms(stream=None):

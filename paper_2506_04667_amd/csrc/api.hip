@@ -489,6 +489,18 @@ int32_t moe_ffn_schedule(int32_t large_list, int32_t n_units_large, int32_t n_un
     return n;
 }
 
+int32_t moe_f32_ffn_schedule(const int32_t* rows, int32_t groups, int32_t capacity, int32_t N, int32_t K, int32_t workgroups,
+                             int64_t* first_iteration, int64_t* fix_tile, int32_t* unit_id, int32_t* unit_cum, int32_t max_units) {
+    if (!rows || groups <= 0 || capacity <= 0 || N <= 0 || K <= 0 || workgroups <= 0 || !first_iteration || !fix_tile || !unit_id ||
+        !unit_cum || (long long)groups * moe::f32_units_nrow(capacity) > max_units)
+        return -1;
+    const int n = moe::f32_build_units_host(rows, capacity, groups, capacity, unit_id, unit_cum);
+    const moe::F32Work k(unit_id, unit_cum, n, (N + moe::kF32TileCols - 1) / moe::kF32TileCols, (K + moe::kF32TileK - 1) / moe::kF32TileK);
+    for (int w = 0; w <= workgroups; ++w) first_iteration[w] = k.boundary(w, workgroups);
+    for (int w = 0; w < workgroups; ++w) fix_tile[w] = k.tile_to_fix(first_iteration[w], first_iteration[w + 1]);
+    return n;
+}
+
 moe_status moe_ffn_status(const moe_config* cfg, const void* workspace, size_t workspace_bytes, void* stream) {
     Plan p;
     moe_status st = make_plan(cfg, &p);

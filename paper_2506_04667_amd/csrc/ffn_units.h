@@ -131,10 +131,68 @@ __host__ __device__ inline int f32_unit_weight(int live_blocks) {
     return w > kF32FullWeight ? kF32FullWeight : w;
 }
 constexpr int kF32MaxWorkgroups = 256;                  // its grid is min(CUs, this); two partial tiles per workgroup
+constexpr int kF32TileCols = 256, kF32TileK = 32;       // the kernel's column tile and K-tile
+// units and total weight of a group with `rows` live rows
+__host__ __device__ inline void f32_group_units(int rows, int& units, int& weight) {
+    units = (rows + kF32UnitRows - 1) / kF32UnitRows;
+    const int last_blocks = (rows + kF32BlockRows - 1) / kF32BlockRows - (units - 1) * (kF32UnitRows / kF32BlockRows);
+    weight = units > 0 ? (units - 1) * kF32FullWeight + f32_unit_weight(last_blocks) : 0;
+}
+// The list as build_row_units writes it, computed on the host (ids[cap], cum[cap + 1]); returns the number of units.
+inline int f32_build_units_host(const int32_t* rows_of, int rows_cap, int groups, int max_rows, int32_t* ids, int32_t* cum) {
+    const int nrow = (max_rows + kF32UnitRows - 1) / kF32UnitRows;
+    int n = 0, c = 0;
+    for (int g = 0; g < groups; ++g) {
+        int rows = rows_of[g] < rows_cap ? rows_of[g] : rows_cap;
+        rows = rows < max_rows ? rows : max_rows;
+        if (rows < 0) rows = 0;
+        int nu, wt;
+        f32_group_units(rows, nu, wt);
+        for (int rt = 0; rt < nu; ++rt) {
+            ids[n] = g * nrow + rt;
+            cum[n++] = c + rt * kF32FullWeight;
+        }
+        c += wt;
+    }
+    cum[n] = c;
+    return n;
+}
 __host__ __device__ inline int f32_units_nrow(int max_rows) { return (max_rows + kF32UnitRows - 1) / kF32UnitRows; }
 __host__ __device__ inline long long f32_units_total_ints(int groups, int max_rows) {
     return 2 + 2ll * groups * f32_units_nrow(max_rows);
 }
+
+// The live work of one fp32 GEMM and how it is dealt.  Iterations are numbered L = unit * per_unit + column tile *
+// nk + K-tile; an iteration of unit u costs cum[u + 1] - cum[u] (the unit's weight).  Workgroup w of G works on the
+// iterations [boundary(w), boundary(w + 1)).
+struct F32Work {
+    const int32_t* ids; const int32_t* cum;
+    int n_units, ncol, nk, per_unit;
+    long long total_cost;
+    __host__ __device__ inline F32Work(const int32_t* ids_, const int32_t* cum_, int n_units_, int ncol_, int nk_)
+        : ids(ids_), cum(cum_), n_units(n_units_), ncol(ncol_), nk(nk_), per_unit(ncol_ * nk_),
+          total_cost(n_units_ > 0 ? (long long)cum_[n_units_] * (ncol_ * nk_) : 0) {}
+    // first iteration of workgroup w of G: where the running cost reaches total * w / G; w == G: the end
+    __host__ __device__ inline long long boundary(int w, int G) const {
+        if (n_units <= 0) return 0;
+        if (w >= G) return (long long)n_units * per_unit;
+        const long long c = total_cost / G * w + total_cost % G * w / G;
+        int lo = 0, hi = n_units;                       // the unit u with cum[u] * per_unit <= c < cum[u + 1] * per_unit
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if ((long long)cum[mid] * per_unit <= c) lo = mid; else hi = mid;
+        }
+        return (long long)lo * per_unit + (c - (long long)cum[lo] * per_unit) / (cum[lo + 1] - cum[lo]);
+    }
+    // The tile (unit * ncol + column tile) whose pieces workgroup w adds up in the second pass, or -1: the tile that
+    // range w begins (its first K-tile lies in the range) but does not finish.  Every tile that is cut has exactly
+    // one such workgroup; the pieces are those of w, w + 1, ... up to the range that holds the tile's last K-tile.
+    __host__ __device__ inline long long tile_to_fix(long long begin, long long end) const {
+        if (begin >= end) return -1;
+        const long long tile = (end - 1) / nk, tb = tile * nk;
+        return (tb + nk <= end || tb < begin) ? -1 : tile;
+    }
+};
 
 // Called by every thread of ONE workgroup of `nthreads` threads (a multiple of 64, at most 1024);
 // `wave_total` is an LDS array of at least 32 ints.
@@ -142,16 +200,14 @@ __device__ __forceinline__ void build_row_units(const int32_t* __restrict__ rows
                                                 int32_t* __restrict__ out, int* wave_total, int nthreads) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nwaves = nthreads >> 6;
     const int nrow = f32_units_nrow(max_rows);
-    constexpr int unit_blocks = kF32UnitRows / kF32BlockRows;
     int32_t* ids = out + 1;
     int32_t* cum = out + 1 + (long long)groups * nrow;
     int carry_u = 0, carry_b = 0;                       // units and their weights of the groups before this pass
     for (int g0 = 0; g0 < groups; g0 += nthreads) {
         const int g = g0 + tid;
         const int rows = g < groups ? max(min(min(rows_dev[g], rows_cap), max_rows), 0) : 0;
-        const int nu = (rows + kF32UnitRows - 1) / kF32UnitRows;
-        const int last_blocks = (rows + kF32BlockRows - 1) / kF32BlockRows - (nu - 1) * unit_blocks;   // of the last unit
-        const int nb = nu > 0 ? (nu - 1) * kF32FullWeight + f32_unit_weight(last_blocks) : 0;          // the group's weight
+        int nu, nb;                                     // the group's units and weight
+        f32_group_units(rows, nu, nb);
         int incl_u = nu, incl_b = nb;
 #pragma unroll
         for (int d = 1; d < 64; d <<= 1) {

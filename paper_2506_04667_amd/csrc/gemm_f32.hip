@@ -30,7 +30,7 @@ long long f32_workgroups_bound(int groups, int max_rows, int N, int K) {
     const long long t = (long long)groups * f32_units_nrow(max_rows) * ((N + F_BN - 1) / F_BN) * ((K + F_BK - 1) / F_BK);
     return t < kF32MaxWorkgroups ? (t > 0 ? t : 1) : kF32MaxWorkgroups;
 }
-static_assert(F_BM == kF32UnitRows, "the unit list is cut in the tile's rows");
+static_assert(F_BM == kF32UnitRows && F_BN == kF32TileCols && F_BK == kF32TileK, "the unit list and the dealing are cut in the tile's sizes");
 constexpr int kFixupSplit = 4;                          // workgroups that share the fix-up of one cut tile, by rows
 static_assert(F_BN % 4 == 0 && F_BM * F_BN / 4 % (F_THREADS * kFixupSplit) == 0, "fix-up thread mapping");
 
@@ -41,34 +41,10 @@ struct F32StreamArgs {
     int nrow;                                           // row tiles per group the ids are numbered with
 };
 
-// The live work of one GEMM and how it is dealt.  Iterations are numbered L = unit * per_unit + column tile * nk +
-// K-tile; an iteration of unit u costs cum[u + 1] - cum[u] (the unit's weight).
-struct Work {
-    const int32_t* ids; const int32_t* cum;
-    int n_units, ncol, nk, per_unit;
-    long long total_cost;
-    __device__ __forceinline__ Work(const F32StreamArgs& a) {
-        n_units = a.list[0];
-        ids = a.list + 1;
-        cum = ids + (long long)a.g.groups * a.nrow;
-        ncol = (a.g.N + F_BN - 1) / F_BN;
-        nk = (a.g.K + F_BK - 1) / F_BK;
-        per_unit = ncol * nk;
-        total_cost = n_units > 0 ? (long long)cum[n_units] * per_unit : 0;
-    }
-    // first iteration of workgroup w of G: where the running cost reaches total * w / G; w == G: the end
-    __device__ __forceinline__ long long boundary(int w, int G) const {
-        if (n_units <= 0) return 0;
-        if (w >= G) return (long long)n_units * per_unit;
-        const long long c = total_cost / G * w + total_cost % G * w / G;
-        int lo = 0, hi = n_units;                       // the unit u with cum[u] * per_unit <= c < cum[u + 1] * per_unit
-        while (hi - lo > 1) {
-            const int mid = (lo + hi) >> 1;
-            if ((long long)cum[mid] * per_unit <= c) lo = mid; else hi = mid;
-        }
-        return (long long)lo * per_unit + (c - (long long)cum[lo] * per_unit) / (cum[lo + 1] - cum[lo]);
-    }
-};
+__device__ __forceinline__ F32Work work_of(const F32StreamArgs& a) {
+    const int32_t* ids = a.list + 1;
+    return F32Work(ids, ids + (long long)a.g.groups * a.nrow, a.list[0], (a.g.N + F_BN - 1) / F_BN, (a.g.K + F_BK - 1) / F_BK);
+}
 
 // One piece of a tile.  Not inlined: inside the loop over a workgroup's pieces the compiler would keep the tile
 // body's per-thread addresses alive across iterations and run out of registers.  The LDS array is named here, not
@@ -95,7 +71,7 @@ __global__ __launch_bounds__(F_THREADS) void ffn_f32_stream_kernel(F32StreamArgs
     int n_pieces = 0, n_light = 0;
 #endif
     const int w = blockIdx.x, G = gridDim.x;
-    const Work k(a);
+    const F32Work k = work_of(a);
     const long long begin = k.boundary(w, G), end = k.boundary(w + 1, G);
     bool first = true;
     for (long long it = begin; it < end;) {
@@ -129,11 +105,11 @@ __global__ __launch_bounds__(F_THREADS) void ffn_f32_stream_kernel(F32StreamArgs
 // workgroups after it, in order, until the tile's last K-tile; then bias, activation and the store.
 __global__ __launch_bounds__(F_THREADS) void ffn_f32_fixup_kernel(F32StreamArgs a, int G) {
     const int w = blockIdx.x;
-    const Work k(a);
+    const F32Work k = work_of(a);
     const long long begin = k.boundary(w, G), end = k.boundary(w + 1, G);
-    if (begin >= end) return;
-    const long long tile = (end - 1) / k.nk, tb = tile * k.nk, te = tb + k.nk;
-    if (te <= end || tb < begin) return;                // finished inside this range, or begun by an earlier workgroup
+    const long long tile = k.tile_to_fix(begin, end);
+    if (tile < 0) return;                               // nothing cut here, or the cut tile was begun by an earlier workgroup
+    const long long tb = tile * k.nk, te = tb + k.nk;
     const int id = k.ids[tile / k.ncol], ct = (int)(tile % k.ncol);
     const int grp = id / a.nrow, rt = id % a.nrow;
     const int rows = min(a.g.rows_dev[grp], a.g.rows_cap);

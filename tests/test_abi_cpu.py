@@ -25,7 +25,7 @@ def lib():
 def _declared_functions():
     text = open(os.path.join(ROOT, "include", "moe.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(moe_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(moe_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_library_exports_every_declared_symbol(lib):
@@ -241,6 +241,62 @@ def test_ffn_schedule_balances_the_xcds(lib):
             per_xcd.append(sum(len(moe.moe_ffn_schedule(large, n_l, n_s, nrow_l, 1, xcd, wg, 4)) for large in (1, 0) for wg in range(4)))
         assert sum(per_xcd) == n_l + n_s and max(per_xcd) - min(per_xcd) <= 2
     assert lib.moe_ffn_schedule(1, 4, 4, 1, 0, 0, 0, 1, None, None, 0) == -1
+
+
+@pytest.mark.parametrize("case", [
+    dict(rows=[257, 254, 265, 257, 247, 261, 275, 270, 245, 237, 246, 256, 221, 252, 237, 245], cap=320, N=4096, K=1024),   # config 2's shape
+    dict(rows=[257, 254, 265, 257, 247, 261, 275, 270, 245, 237, 246, 256, 221, 252, 237, 245], cap=320, N=1024, K=4096),
+    dict(rows=[0, 0, 0, 0, 0, 0, 150, 0, 0], cap=150, N=512, K=4096),                  # one live expert cut into many pieces
+    dict(rows=[5, 0, 700, 1, 33, 64, 65, 999, 256, 512], cap=600, N=264, K=40),        # every weight; values above the capacity
+    dict(rows=[0] * 7, cap=64, N=256, K=32),                                           # nothing live
+    dict(rows=[3], cap=3, N=8, K=8),                                                   # a single iteration
+])
+@pytest.mark.parametrize("wgs", [1, 3, 8, 128, 256])
+def test_f32_ffn_work_is_dealt_exactly_once_and_every_cut_tile_has_one_owner(lib, case, wgs):
+    rows, cap, N, K = case["rows"], case["cap"], case["N"], case["K"]
+    ids, cum, first, fix = moe.moe_f32_ffn_schedule(rows, cap, N, K, wgs)
+    ncol, nk, nrow = -(-N // 256), -(-K // 32), -(-cap // 256)
+    # the list: every live 256-row tile once, in order of expert, with the documented weights
+    live = [min(r, cap) for r in rows]
+    want = [g * nrow + rt for g, r in enumerate(live) for rt in range(-(-r // 256))]
+    assert ids == want
+    weight = []
+    for r in live:
+        for rt in range(-(-r // 256)):
+            b = min(8, -(-r // 32) - 8 * rt)                  # live 32-row MFMA tiles of the unit
+            weight.append(min(12, 3 * -(-b // 2)))
+    assert [cum[u + 1] - cum[u] for u in range(len(ids))] == weight and cum[0] == 0
+    # the ranges: consecutive, covering every iteration once
+    total = len(ids) * ncol * nk
+    assert first[0] == 0 and first[-1] == total and all(a <= b for a, b in zip(first, first[1:]))
+    # ... and of about equal cost: a range's cost differs from the equal share by less than two iterations of the heaviest unit
+    cost_of = lambda L: cum[L // (ncol * nk)] * ncol * nk + (L % (ncol * nk)) * weight[L // (ncol * nk)] if L < total else cum[-1] * ncol * nk
+    if total:
+        share = cum[-1] * ncol * nk / wgs
+        for w in range(wgs):
+            assert abs(cost_of(first[w + 1]) - cost_of(first[w]) - share) < 2 * 12 + 1
+    # the second pass: a tile is cut if a range boundary falls strictly inside it; each cut tile is fixed by exactly one
+    # workgroup, the one whose range holds the tile's first K-tile; whole tiles by nobody
+    cut = {}
+    for w in range(wgs):
+        a, b = first[w], first[w + 1]
+        L = a
+        while L < b:
+            t = L // nk
+            end = min(b, (t + 1) * nk)
+            if not (L == t * nk and end == (t + 1) * nk):
+                cut.setdefault(t, []).append((w, L, end))
+            L = end
+    owners = {}
+    for w, t in enumerate(fix):
+        if t >= 0:
+            assert t not in owners
+            owners[t] = w
+    assert set(owners) == set(cut)
+    for t, pieces in cut.items():
+        assert pieces[0][0] == owners[t] and pieces[0][1] == t * nk and pieces[-1][2] == (t + 1) * nk
+        assert all(p[2] == q[1] for p, q in zip(pieces, pieces[1:]))       # the pieces tile the K range, in workgroup order
+        assert [p[0] for p in pieces] == sorted(p[0] for p in pieces)
 
 
 def test_binding_fails_loudly_without_the_library(tmp_path):
