@@ -476,16 +476,19 @@ int32_t moe_ffn_schedule(int32_t large_list, int32_t n_units_large, int32_t n_un
         return -1;
     int unit0, unit_step, ux_l, ux;
     moe::ffn_xcd_share(true, n_units_large, nrow_large, xcd, unit0, unit_step, ux_l);
-    int w = wg;
+    int w = wg, handicap = 0;
     if (large_list) {
         ux = ux_l;
     } else {
         moe::ffn_xcd_share(false, n_units_small, 1, xcd, unit0, unit_step, ux);
         w = moe::ffn_small_list_rotation(wg, wgs, ux_l, ncol);
+        handicap = moe::ffn_small_list_handicap(wgs, ux_l, ncol);
     }
-    int n = 0;
-    for (long long p = w; p < (long long)ux * ncol; p += wgs, ++n)
-        if (n < max_tasks) moe::ffn_task_at((int)p, ncol, unit0, unit_step, list_index[n], col_tile[n]);
+    if ((long long)ux * ncol > 0x7fffffffLL - 2ll * wgs) return -1;
+    const int n = moe::ffn_slot_count(w, wgs, handicap, ux * ncol);
+    const int first = moe::ffn_first_slot(w, wgs, handicap);
+    for (int j = 0; j < n && j < max_tasks; ++j)
+        moe::ffn_task_at(moe::ffn_slot_position(first + j * wgs, wgs, handicap), ncol, unit0, unit_step, list_index[j], col_tile[j]);
     return n;
 }
 

@@ -59,6 +59,26 @@ __host__ __device__ inline int ffn_small_list_rotation(int wg, int wgs, int ux_l
     int w = wg - (int)(((long long)ux_large * ncol) % wgs);
     return w < 0 ? w + wgs : w;
 }
+// The small-tile tasks even out the large ones: the `handicap` workgroups that got one more large-tile task than the
+// others (after the rotation they are the last ones, w >= wgs - handicap) sit out the first round of small-tile
+// tasks, so a workgroup's third task, where there is one, is never on top of a large tile.  Workgroup w takes the
+// slots w, w + wgs, ... from ffn_first_slot on; a slot's position in the XCD's task sequence is ffn_slot_position
+// (the slots of the first round that are sat out do not count).  handicap = 0: position = slot (the large list).
+__host__ __device__ inline int ffn_small_list_handicap(int wgs, int ux_large, int ncol) {
+    return (int)(((long long)ux_large * ncol) % wgs);
+}
+__host__ __device__ inline int ffn_first_slot(int w, int wgs, int handicap) { return w < wgs - handicap ? w : w + wgs; }
+__host__ __device__ inline int ffn_slot_position(int slot, int wgs, int handicap) { return slot < wgs ? slot : slot - handicap; }
+// number of tasks of workgroup w among the XCD's xcd_tasks
+__host__ __device__ inline int ffn_slot_count(int w, int wgs, int handicap, int xcd_tasks) {
+    int n = 0, start = ffn_first_slot(w, wgs, handicap);
+    if (start < wgs) {
+        n = start < xcd_tasks ? 1 : 0;
+        start += wgs;
+    }
+    const int left = xcd_tasks + handicap - start;
+    return n + (left > 0 ? (left + wgs - 1) / wgs : 0);
+}
 
 // Called by every thread of ONE workgroup of `nthreads` threads (a multiple of 64, at most 1024);
 // `wave_total` is an LDS array of 32 ints.

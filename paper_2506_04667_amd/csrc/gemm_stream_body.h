@@ -148,9 +148,11 @@ constexpr int kSpinLimit = 1 << 21;
 // { fault word, number of live units, ids[cap], completion counters[cap] }; the workgroup is number wg_local of
 // the wg_stride workgroups of XCD `xcd` that walk this list.  COUNT: after storing a tile every wavefront adds
 // one to its unit's completion counter.  WAIT: before the first copy of a task is requested, its unit's counter
-// must have reached a.wait_target (the tiles this task reads are then in the XCD's L2).
+// must have reached a.wait_target (the tiles this task reads are then in the XCD's L2).  `handicap`: see
+// ffn_small_list_handicap (0 for the large list).
 template <class S, int ACT, int PH, bool COUNT, bool WAIT, int G>
-__device__ __forceinline__ void stream_body(const StreamArgs& a, int32_t* list, int cap, int xcd, int wg_local, int wg_stride) {
+__device__ __forceinline__ void stream_body(const StreamArgs& a, int32_t* list, int cap, int xcd, int wg_local, int wg_stride,
+                                            int handicap) {
     typedef uint16_t elem;
     const StreamPhase& P = a.ph[PH];
     int32_t* const fault = list;
@@ -179,12 +181,15 @@ __device__ __forceinline__ void stream_body(const StreamArgs& a, int32_t* list, 
     int unit0, unit_step, ux;
     ffn_xcd_share(G == 2, n_units, nrow, xcd, unit0, unit_step, ux);
     const int xcd_tasks = ux * ncol;
-    if (wg_local >= xcd_tasks) return;
+    const int my_tasks = ffn_slot_count(wg_local, wg_stride, handicap, xcd_tasks);
+    if (my_tasks == 0) return;
+    const int first_slot = ffn_first_slot(wg_local, wg_stride, handicap);
+    auto position = [&](int slot) __attribute__((always_inline)) { return ffn_slot_position(slot, wg_stride, handicap); };
     // The unit and the live row count of this workgroup's tasks are fetched 64 tasks at a time, one task per
     // lane, so that moving on to the next task costs two lane reads, not two dependent trips to memory.
     int info_unit = 0, info_rows = 0;                   // of this workgroup's task number j0 + lane
     auto load_task_info = [&](int j0) __attribute__((always_inline)) {
-        const int p = wg_local + (j0 + (int)(threadIdx.x & 63)) * wg_stride;
+        const int p = position(first_slot + (j0 + (int)(threadIdx.x & 63)) * wg_stride);
         if (p < xcd_tasks) {
             int li, ct;
             ffn_task_at(p, ncol, unit0, unit_step, li, ct);
@@ -192,10 +197,10 @@ __device__ __forceinline__ void stream_body(const StreamArgs& a, int32_t* list, 
             info_rows = min(a.rows_dev[info_unit / nrow], a.rows_cap);
         }
     };
-    // task number j of this workgroup, at position p = wg_local + j * wg_stride < xcd_tasks
-    auto task_at = [&](int j, int p, Task& t) __attribute__((always_inline)) {
+    // task number j of this workgroup, in slot first_slot + j * wg_stride, whose position is < xcd_tasks
+    auto task_at = [&](int j, int slot, Task& t) __attribute__((always_inline)) {
         int li, ct;
-        ffn_task_at(p, ncol, unit0, unit_step, li, ct);
+        ffn_task_at(position(slot), ncol, unit0, unit_step, li, ct);
         t.unit = uniform(li);
         const int unit = __builtin_amdgcn_readlane(info_unit, j & 63);
         t.grp = uniform(unit / nrow);
@@ -225,7 +230,7 @@ __device__ __forceinline__ void stream_body(const StreamArgs& a, int32_t* list, 
             asm volatile("" ::: "memory");
         }
     };
-    const int U = uniform(((xcd_tasks - wg_local + wg_stride - 1) / wg_stride) * nk);   // K-tiles in this workgroup's whole stream
+    const int U = uniform(my_tasks * nk);               // K-tiles in this workgroup's whole stream
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -259,7 +264,7 @@ __device__ __forceinline__ void stream_body(const StreamArgs& a, int32_t* list, 
     };
 
     Task cur, nxt;                                      // task being multiplied; the one after it
-    int nxt_j = 0, nxt_p = wg_local;                    // number and position of `nxt` in the XCD's task sequence
+    int nxt_j = 0, nxt_p = first_slot;                  // number and slot of `nxt`
     load_task_info(0);
     task_at(nxt_j, nxt_p, cur);
     wait_for_unit(cur);
@@ -271,7 +276,7 @@ __device__ __forceinline__ void stream_body(const StreamArgs& a, int32_t* list, 
     nxt = cur;
     ++nxt_j;
     nxt_p += wg_stride;
-    if (nxt_p < xcd_tasks) {
+    if (nxt_j < my_tasks) {
         task_at(nxt_j, nxt_p, nxt);
         wait_for_unit(nxt);
         task_bases(nxt, na_base, nb_base);
@@ -419,7 +424,7 @@ __device__ __forceinline__ void stream_body(const StreamArgs& a, int32_t* list, 
         Task after = nxt;
         ++nxt_j;
         nxt_p += wg_stride;
-        if (nxt_p < xcd_tasks) {
+        if (nxt_j < my_tasks) {
             if ((nxt_j & 63) == 0) load_task_info(nxt_j);
             task_at(nxt_j, nxt_p, after);
             wait_for_unit(after);
@@ -555,7 +560,8 @@ __device__ __forceinline__ void stream_body(const StreamArgs& a, int32_t* list, 
 // One persistent workgroup per CU.  A workgroup first walks its share of the XCD's large-tile tasks, then its
 // share of the small-tile tasks; nothing separates the two parts but a workgroup barrier, so workgroups with
 // few or no large tiles start on the small ones at once.  The small-tile tasks are dealt starting with the
-// workgroup after the one that got the XCD's last large-tile task, which evens out the counts.
+// workgroup after the one that got the XCD's last large-tile task, and the workgroups that got one more large-tile
+// task than the others sit out the first round of small ones, which evens out the work (ffn_small_list_handicap).
 // NPH == 2 (both FFN GEMMs in one launch): the workgroup then walks its second-GEMM tasks the same way, each
 // waiting for its unit's first-GEMM tiles.  Since no workgroup waits for anything before all its own first-GEMM
 // tiles are stored, the waits always end (see wait_for_unit).
@@ -568,11 +574,12 @@ __device__ __forceinline__ void stream_gemm(const StreamArgs& a, int xcd, int wg
     int unit0, unit_step, ux_l, ux_s;
     ffn_xcd_share(true, n_l, nrow_l, xcd, unit0, unit_step, ux_l);
     ffn_xcd_share(false, n_s, nrow_s, xcd, unit0, unit_step, ux_s);
-    if (ux_l > 0) stream_body<S, ACT0, PH, COUNT, WAIT, 2>(a, list_l, a.groups * nrow_l, xcd, wg, wgs);
+    if (ux_l > 0) stream_body<S, ACT0, PH, COUNT, WAIT, 2>(a, list_l, a.groups * nrow_l, xcd, wg, wgs, 0);
     if (ux_s > 0) {
         if (ux_l > 0) __syncthreads();                  // every wavefront is done with the LDS stages of the first part
-        const int wg_s = ffn_small_list_rotation(wg, wgs, ux_l, (a.ph[PH].N + BN - 1) / BN);
-        stream_body<S, ACT0, PH, COUNT, WAIT, 1>(a, list_s, a.groups, xcd, wg_s, wgs);
+        const int ncol = (a.ph[PH].N + BN - 1) / BN;
+        const int wg_s = ffn_small_list_rotation(wg, wgs, ux_l, ncol);
+        stream_body<S, ACT0, PH, COUNT, WAIT, 1>(a, list_s, a.groups, xcd, wg_s, wgs, ffn_small_list_handicap(wgs, ux_l, ncol));
     }
 }
 
