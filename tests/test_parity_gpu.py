@@ -538,12 +538,15 @@ def test_choice_major_drop_priority_end_to_end(oracle, dtype):
     assert torch.equal(b.out, b2.out)
 
 
-def test_forward_replays_from_a_hip_graph(oracle):
+@pytest.mark.parametrize("dtype,flags,H", [("bf16", 0, 256), ("bf16", moe.FLAG_LAYER_SINGLE_LAUNCH, 256), ("f32", 0, 2048)])
+def test_forward_replays_from_a_hip_graph(oracle, dtype, flags, H):
     # moe_forward allocates nothing, synchronises nothing and clears its scratch with kernels, so a caller may
     # capture it; every replay (with eager work and synchronisation in between, and new inputs in the same
-    # buffers) must reproduce the eager result bit for bit
-    w = scaled(WORKLOADS["paper_bf16_e128"], name="graph", seed=41, T=1500, H=256, I=512, E=16, k=2,
-               capacity_factor=1.0, with_bias=True)
+    # buffers) must reproduce the eager result bit for bit.  Also for the whole layer as one launch (its barrier
+    # words start and end every launch at zero) and for the fp32 FFN kernel with its second pass (H = 2048 makes
+    # both GEMMs large enough for it).
+    w = scaled(WORKLOADS["paper_bf16_e128"], name="graph", seed=41, T=1500, H=H, I=512, E=16, k=2,
+               capacity_factor=1.0, with_bias=True, dtype=dtype, flags=flags)
     cpu = make_inputs(w)
     dev = parity.to_device(cpu)
     cfg = moe.config_of(w)
