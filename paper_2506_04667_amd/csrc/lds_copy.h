@@ -19,14 +19,14 @@ __device__ __forceinline__ const unsigned char* uniform(const unsigned char* p) 
 // the copy cursors out of the vector registers.
 __device__ __forceinline__ void copy_to_lds(const unsigned char* base, uint32_t lane_off, uint32_t lds_addr) {
     base = uniform(base);
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(lane_off), "s"(base) : "memory");
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(lane_off), "s"(base) : "memory", "m0");
 }
 
 // The same copy for data that is read once (weights streaming past): the non-temporal hint asks the caches to
 // give such lines up first, so that they do not push out lines that other workgroups are about to re-read.
 __device__ __forceinline__ void copy_to_lds_stream(const unsigned char* base, uint32_t lane_off, uint32_t lds_addr) {
     base = uniform(base);
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2 nt" ::"s"(lds_addr), "v"(lane_off), "s"(base) : "memory");
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2 nt" ::"s"(lds_addr), "v"(lane_off), "s"(base) : "memory", "m0");
 }
 
 // own copies older than the newest N have landed; own LDS reads are complete; then meet the other waves
