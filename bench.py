@@ -267,9 +267,21 @@ def main():
         def mf():
             flops[0] = moe.moe_probe_mfma(w.dtype, iters, sink)
         mm = ev_time(mf, 5)
+        # L2 -> LDS fill rate per CU by the two routes (2 MiB per XCD, resident in its L2 after the first lap)
+        region, fsteps = 2 << 20, 512
+        moved = [0.0]
+        def fill(mode):
+            def f():
+                moved[0] = moe.moe_probe_lds_fill(mode, src, region, fsteps, sink)
+            return f
+        fills = {}
+        for mode, name in ((0, "direct_copy"), (1, "load_then_ds_write"), (2, "load_only")):
+            ms = ev_time(fill(mode), 5)
+            fills[name] = round(moved[0] / (ms * 1e-3) / 1e9, 1)
         measured = {"stream_read_gbs": round(src.numel() / (rd * 1e-3) / 1e9, 1),
                     "stream_copy_gbs_read_plus_write": round(2 * src.numel() / (cp * 1e-3) / 1e9, 1),
                     "mfma_loop_tflops": round(flops[0] / (mm * 1e-3) / 1e12, 1), "mfma_dtype": w.dtype,
+                    "l2_to_lds_fill_gbs": fills,
                     "bytes": src.numel(), "kernels": "moe_probe_stream / moe_probe_mfma (csrc/probes.hip)"}
 
     slot = b.slot.cpu()

@@ -198,6 +198,15 @@ moe_status moe_forward_timed(const moe_config* cfg, void* workspace, size_t work
 moe_status moe_probe_stream(const void* src, void* dst, size_t bytes, void* sink, void* stream);
 moe_status moe_probe_mfma(int32_t dtype, int32_t iters, void* sink, double* flops, void* stream);
 
+/* Yardstick, not part of the layer: the rate at which the CUs bring L2-resident data into LDS.  One workgroup per
+ * CU walks a region of region_bytes (a multiple of 64 KiB; the workgroups of an XCD share one region, so `src` must
+ * hold 8 * region_bytes, 16-byte aligned, device) round and round, 64 KiB per step, `steps` steps (even, >= 2).
+ * mode 0: direct global-to-LDS copies (global_load_lds_dwordx4, the route the FFN and gate kernels use);
+ * mode 1: vector loads into registers, then ds_write_b128; mode 2: the vector loads alone.  *bytes_moved (host,
+ * optional) receives the bytes all workgroups moved; time the call with events.  `sink`: 4 bytes of device memory. */
+moe_status moe_probe_lds_fill(int32_t mode, const void* src, size_t region_bytes, int32_t steps, void* sink,
+                              double* bytes_moved, void* stream);
+
 /* ---- staged entry points: the same kernels, one stage each ------------------- */
 
 /* Gate ("FusedGate", Alg. 1): gate_logits = x Wg (+ gate_bias) with fp32

@@ -19,7 +19,7 @@ TORCH_DTYPE = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float1
 EXPORTS = ["moe_status_string", "moe_init", "moe_row_tile", "moe_capacity", "moe_workspace_bytes", "moe_forward",
            "moe_gate", "moe_route", "moe_dispatch", "moe_expert_ffn", "moe_combine", "moe_ffn_status", "moe_ffn_schedule",
            "moe_forward_timed", "moe_probe_stream", "moe_probe_mfma", "moe_dispatch_noalloc",
-           "moe_backward_workspace_bytes", "moe_backward", "moe_layer_stage_ms", "moe_f32_ffn_schedule"]
+           "moe_backward_workspace_bytes", "moe_backward", "moe_layer_stage_ms", "moe_f32_ffn_schedule", "moe_probe_lds_fill"]
 LAYER_STAGES = ("gate", "barrier1", "clear_scan", "barrier2", "scatter_units", "barrier3", "ffn_gemm1", "ffn_gemm2", "barrier4",
                 "combine")
 STATIC_SCRATCH_BYTES = 4 << 20
@@ -80,6 +80,8 @@ def load(path=None):
     lib.moe_forward.argtypes = [cfgp, vp, ctypes.c_size_t] + [vp] * 14
     lib.moe_forward_timed.restype = ctypes.c_int
     lib.moe_forward_timed.argtypes = [cfgp, vp, ctypes.c_size_t] + [vp] * 13 + [ctypes.POINTER(vp), vp]
+    lib.moe_probe_lds_fill.restype = ctypes.c_int
+    lib.moe_probe_lds_fill.argtypes = [ctypes.c_int32, vp, ctypes.c_size_t, ctypes.c_int32, vp, ctypes.POINTER(ctypes.c_double), vp]
     lib.moe_probe_stream.restype = ctypes.c_int
     lib.moe_probe_stream.argtypes = [vp, vp, ctypes.c_size_t, vp, vp]
     lib.moe_probe_mfma.restype = ctypes.c_int
@@ -244,6 +246,13 @@ def moe_probe_mfma(dtype, iters, sink, stream=None):
     flops = ctypes.c_double()
     _check(load().moe_probe_mfma(DTYPE[dtype], int(iters), _p(sink), ctypes.byref(flops), _stream(stream)))
     return flops.value
+
+
+def moe_probe_lds_fill(mode, src, region_bytes, steps, sink, stream=None):
+    """Launch the LDS-fill yardstick (mode 0 direct copies, 1 loads + ds_write, 2 loads alone); returns the bytes moved."""
+    moved = ctypes.c_double()
+    _check(load().moe_probe_lds_fill(int(mode), _p(src), int(region_bytes), int(steps), _p(sink), ctypes.byref(moved), _stream(stream)))
+    return moved.value
 
 
 def moe_gate(cfg, workspace, x, Wg, gate_bias, gate_logits, topk_expert, topk_weight, stream=None):

@@ -5,11 +5,15 @@
 //   stream copy : the same with a 16-byte store per load (the reference kernel for hardware traffic counters);
 //   MFMA loop   : register-resident v_mfma_f32_16x16x32 (bf16 / f16) or v_mfma_f32_32x32x2 (fp32) on operand
 //                 registers that hold pseudo-random finite values and rotate every step, eight independent
-//                 accumulator tiles per wavefront, two wavefronts per SIMD.
+//                 accumulator tiles per wavefront, two wavefronts per SIMD;
+//   LDS fill    : how fast a CU can bring L2-resident data into its LDS, by the two routes there are: direct copies
+//                 (global_load_lds_dwordx4, what the FFN and gate kernels use) and vector loads into registers
+//                 followed by ds_write_b128; and, for reference, the vector loads alone.
 #include "../../include/moe.h"
 
 #include "common.h"
 #include "kernels.h"
+#include "lds_copy.h"
 
 namespace moe {
 namespace {
@@ -119,10 +123,90 @@ __global__ __launch_bounds__(512) void mfma_probe_kernel(int iters, float* __res
     if (total == 12345.678f) sink[0] = total;           // keeps the loop alive
 }
 
+// One workgroup per CU, 8 wavefronts; per step a wavefront moves 8 KB (eight 1 KB pieces, lane i 16 bytes of each),
+// the workgroup 64 KB.  The workgroups of an XCD (block number modulo 8) walk the same region of `region` bytes round
+// and round from different starting points, so after the first lap everything comes from that XCD's L2.
+// MODE 0: direct copies, the previous step's eight still in flight while this step's are issued.
+// MODE 1: vector loads into registers, double-buffered by step, then ds_write_b128.   MODE 2: the loads alone.
+constexpr int kFillThreads = 512, kFillPieces = 8, kFillStep = (kFillThreads / 64) * kFillPieces * 1024;
+template <int MODE>
+__global__ __launch_bounds__(kFillThreads) void lds_fill_probe_kernel(const unsigned char* __restrict__ src, size_t region, int steps,
+                                                                      uint32_t* __restrict__ sink) {
+    extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+    const int lane = threadIdx.x & 63, wave = uniform((int)(threadIdx.x >> 6));
+    const unsigned char* const base = uniform(src + (size_t)(blockIdx.x % 8) * region);
+    const size_t steps_per_lap = region / kFillStep;
+    size_t at = (size_t)(blockIdx.x / 8) % steps_per_lap;             // step position inside the region
+    const uint32_t lds_wave = (uint32_t)(size_t)(__attribute__((address_space(3))) unsigned char*)smem + wave * (2 * kFillPieces * 1024);
+    const uint32_t lane_off = wave * (kFillPieces * 1024) + lane * 16;
+    u32x4 fold = {0u, 0u, 0u, 0u};
+    if constexpr (MODE == 0) {
+        for (int it = 0; it < steps; ++it) {
+            const unsigned char* p = base + at * kFillStep;
+#pragma unroll
+            for (int j = 0; j < kFillPieces; ++j) copy_to_lds(p, lane_off + j * 1024, lds_wave + ((it & 1) * kFillPieces + j) * 1024);
+            asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kFillPieces) : "memory");
+            at = at + 1 == steps_per_lap ? 0 : at + 1;
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    } else {
+        u32x4 a[kFillPieces], b[kFillPieces];
+        auto load = [&](u32x4 (&r)[kFillPieces]) __attribute__((always_inline)) {
+            const unsigned char* p = base + at * kFillStep + lane_off;
+#pragma unroll
+            for (int j = 0; j < kFillPieces; ++j) r[j] = *(const u32x4*)(p + j * 1024);
+            at = at + 1 == steps_per_lap ? 0 : at + 1;
+        };
+        auto put = [&](const u32x4 (&r)[kFillPieces], int half) __attribute__((always_inline)) {
+#pragma unroll
+            for (int j = 0; j < kFillPieces; ++j) {
+                if constexpr (MODE == 1) {
+                    const uint32_t d = lds_wave + (half * kFillPieces + j) * 1024 + lane * 16;
+                    asm volatile("ds_write_b128 %0, %1" ::"v"(d), "v"(r[j]) : "memory");
+                } else {
+                    fold ^= r[j];
+                }
+            }
+        };
+        load(a);
+        for (int it = 0; it + 1 < steps; it += 2) {
+            load(b);
+            put(a, 0);
+            load(a);
+            put(b, 1);
+        }
+        put(a, 0);
+    }
+    __syncthreads();
+    const uint32_t w = fold[0] ^ fold[1] ^ fold[2] ^ fold[3] ^ ((const uint32_t*)smem)[threadIdx.x];
+    if (w == 0x9e3779b9u) sink[0] = w;                  // practically never: keeps the work alive
+}
+
 }  // namespace
 }  // namespace moe
 
 extern "C" {
+
+moe_status moe_probe_lds_fill(int32_t mode, const void* src, size_t region_bytes, int32_t steps, void* sink, double* bytes_moved,
+                              void* stream) {
+    if (!src || !sink || mode < 0 || mode > 2 || steps < 2 || (steps & 1) || region_bytes < (size_t)moe::kFillStep ||
+        region_bytes % moe::kFillStep || ((uintptr_t)src & 15u))
+        return MOE_ERR_INVALID_ARG;
+    const int grid = moe::device_cu_count();
+    const int lds = 8 * 2 * moe::kFillPieces * 1024;                  // two steps of every wavefront
+    auto launch = [&](void (*kernel)(const unsigned char*, size_t, int, uint32_t*)) {
+        // a yardstick, not a hot path: the LDS limit is set on every call
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
+            return MOE_ERR_HIP;
+        hipLaunchKernelGGL(kernel, dim3(grid), dim3(moe::kFillThreads), lds, (hipStream_t)stream, (const unsigned char*)src, region_bytes,
+                           steps, (uint32_t*)sink);
+        return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
+    };
+    if (bytes_moved) *bytes_moved = (double)moe::kFillStep * ((mode == 0) ? steps : steps + 1) * grid;
+    if (mode == 0) return launch(moe::lds_fill_probe_kernel<0>);
+    if (mode == 1) return launch(moe::lds_fill_probe_kernel<1>);
+    return launch(moe::lds_fill_probe_kernel<2>);
+}
 
 moe_status moe_probe_stream(const void* src, void* dst, size_t bytes, void* sink, void* stream) {
     if (!src || !sink || bytes < 16 || (bytes & 15u) || ((uintptr_t)src & 15u) || ((uintptr_t)dst & 15u)) return MOE_ERR_INVALID_ARG;
