@@ -147,8 +147,10 @@ int32_t moe_row_tile(void);
 moe_status moe_capacity(const moe_config* cfg, int32_t* C, int32_t* C_pad);
 
 /* Bytes of device workspace that moe_forward and the staged calls need for this
- * configuration (gate scratch, routing tables, the FFN intermediate h and the
- * expert outputs y; the staged calls take xe and y from the caller). */
+ * configuration (gate scratch, routing tables, the lists of live FFN row tiles,
+ * the FFN intermediate h and the expert outputs y; for fp32 storage also up to
+ * 128 MiB of partial output tiles of the FFN kernel that deals equal shares of
+ * the live work; the staged calls take xe and y from the caller). */
 moe_status moe_workspace_bytes(const moe_config* cfg, size_t* bytes);
 
 /* The whole layer (Alg. 1 restricted to one GPU: gate -> dispatch -> expert FFN
