@@ -319,7 +319,7 @@ struct BwdPlan {
     Plan p;
     int ldL, T_pad;
     size_t off_counts, off_units, off_slot_token, off_slot_weight, off_slot, off_demand, off_dl, off_dL, off_wgt, off_xe,
-        off_gy, off_a, off_h, off_dh, off_y, off_hT, off_xeT, off_xT, total;
+        off_gy, off_a, off_h, off_dh, off_y, off_hT, off_xeT, off_xT, off_wrows, off_wunits1, off_wunits2, total;
 };
 
 moe_status make_bwd_plan(const moe_config* c, BwdPlan* b) {
@@ -352,6 +352,10 @@ moe_status make_bwd_plan(const moe_config* c, BwdPlan* b) {
     b->off_hT = take(rows * I * el);
     b->off_xeT = take(rows * H * el);
     b->off_xT = take(H * (size_t)b->T_pad * el);
+    // the weight-gradient GEMMs as streaming-kernel launches: their "experts" have H (dW1) or I (dW2) rows each
+    b->off_wrows = take(2 * E * 4);
+    b->off_wunits1 = take(moe::ffn_units_ints(c->E, c->H) * 4);
+    b->off_wunits2 = take(moe::ffn_units_ints(c->E, c->I) * 4);
     b->total = off;
     return MOE_OK;
 }
@@ -409,13 +413,26 @@ moe_status run_backward(const moe_config* c, const BwdPlan& b, void* ws, const v
     // dW2[e] = h[e]^T gy[e], dW1[e] = xe[e]^T da[e]
     MOE_TRY(moe::launch_bwd_transpose(h, hT, E, C_pad, I, C_pad, dt, s));
     MOE_TRY(moe::launch_bwd_transpose(xe, xeT, E, C_pad, H, C_pad, dt, s));
+    // 16-bit storage: row counts and lists of row tiles, so that the persistent weight-streaming kernel takes them (each
+    // GEMM writes E H I floats from a contraction over only C_pad rows: its stores must overlap the next tile's loads)
+    int32_t* wrows = (int32_t*)ws_at(ws, b.off_wrows);
+    int32_t *wunits1 = nullptr, *wunits2 = nullptr;
+    if (dt != MOE_F32) {
+        wunits1 = (int32_t*)ws_at(ws, b.off_wunits1);
+        wunits2 = (int32_t*)ws_at(ws, b.off_wunits2);
+        MOE_TRY(moe::launch_bwd_fill_rows(wrows, E, H, I, s));
+        MOE_TRY(moe::launch_ffn_units(wrows, H, E, H, wunits1, s));
+        MOE_TRY(moe::launch_ffn_units(wrows + E, I, E, I, wunits2, s));
+    }
     moe::GemmArgs w{};
     w.rows_dev = nullptr; w.groups = E; w.dtype = dt; w.act = MOE_ACT_IDENTITY; w.c_f32 = true; w.K = C_pad; w.lda = C_pad;
     moe::GemmArgs w2 = w;
+    if (wunits2) { w2.rows_dev = wrows + E; w2.units = wunits2; }
     w2.A = hT; w2.a_group_stride = rI; w2.a_rows_total = I; w2.rows_fixed = I; w2.rows_cap = I; w2.max_rows = I;
     w2.B = gy; w2.b_group_stride = rH; w2.ldb = H; w2.C = dW2; w2.c_group_stride = HI; w2.ldc = H; w2.N = H;
     MOE_TRY(moe::launch_grouped_gemm(w2, s));
     moe::GemmArgs w1 = w;
+    if (wunits1) { w1.rows_dev = wrows; w1.units = wunits1; }
     w1.A = xeT; w1.a_group_stride = rH; w1.a_rows_total = H; w1.rows_fixed = H; w1.rows_cap = H; w1.max_rows = H;
     w1.B = dh; w1.b_group_stride = rI; w1.ldb = I; w1.C = dW1; w1.c_group_stride = HI; w1.ldc = I; w1.N = I;
     MOE_TRY(moe::launch_grouped_gemm(w1, s));

@@ -131,16 +131,58 @@ __global__ __launch_bounds__(256) void bwd_transpose_kernel(const elem* __restri
     }
 }
 
-// out[e][c] = sum over the live rows r of in[e][r][c], rows in ascending order (fp32).
+// out[e][c] = sum over the live rows r of in[e][r][c] (fp32).  A workgroup of four wavefronts owns 64 chunks of 16
+// bytes of the columns of one expert; wavefront w adds the rows w, w + 4, ... in ascending order, four loads in flight
+// per lane, and the four partial sums are added in wavefront order: a fixed order, the same from run to run.
 template <class S>
 __global__ __launch_bounds__(256) void bwd_colsum_kernel(const void* __restrict__ in, const int32_t* __restrict__ expert_demand, int C,
                                                          int C_pad, int cols, float* __restrict__ out) {
-    const int e = blockIdx.y, c = blockIdx.x * 256 + threadIdx.x;
-    if (c >= cols) return;
+    constexpr int VEC = S::kVec;
+    __shared__ float part[3][64][VEC];
+    const int e = blockIdx.y, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int row_chunks = cols / VEC, c = blockIdx.x * 64 + lane;
     const int n = min(expert_demand[e], C);
-    float acc = 0.0f;
-    for (int r = 0; r < n; ++r) acc += load_as_float<S>(in, ((size_t)e * C_pad + r) * cols + c);
-    out[(size_t)e * cols + c] = acc;
+    float acc[VEC];
+#pragma unroll
+    for (int q = 0; q < VEC; ++q) acc[q] = 0.0f;
+    if (c < row_chunks) {
+        const u32x4* p = (const u32x4*)in + (size_t)e * C_pad * row_chunks + c;
+        auto add = [&](const u32x4& v) {
+            if constexpr (S::kBytes == 4) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) { const uint32_t u = v[q]; acc[q] += __builtin_bit_cast(float, u); }
+            } else {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const uint32_t u = v[q];
+                    acc[2 * q] += bits16_to_float<S>((uint16_t)(u & 0xffffu));
+                    acc[2 * q + 1] += bits16_to_float<S>((uint16_t)(u >> 16));
+                }
+            }
+        };
+        int r = wave;
+        for (; r + 12 < n; r += 16) {
+            u32x4 v[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) v[i] = p[(size_t)(r + 4 * i) * row_chunks];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) add(v[i]);
+        }
+        for (; r < n; r += 4) add(p[(size_t)r * row_chunks]);
+    }
+    if (wave > 0) {
+#pragma unroll
+        for (int q = 0; q < VEC; ++q) part[wave - 1][lane][q] = acc[q];
+    }
+    __syncthreads();
+    if (wave == 0 && c < row_chunks) {
+#pragma unroll
+        for (int w = 0; w < 3; ++w)
+#pragma unroll
+            for (int q = 0; q < VEC; ++q) acc[q] += part[w][lane][q];
+#pragma unroll
+        for (int q = 0; q < VEC; ++q) out[(size_t)e * cols + c * VEC + q] = acc[q];
+    }
 }
 
 // dgate_bias[e] = sum of dl over the pairs that selected e: one workgroup per expert, fixed reduction tree.
@@ -161,29 +203,73 @@ __global__ __launch_bounds__(256) void bwd_gate_bias_kernel(const int32_t* __res
 }
 
 // One wavefront per token: dx_i = sum over kept choices of dxe[e_ij, slot_ij, :] (ascending j), then
-// + sum over all k choices of dl_ij * Wg[:, e_ij] (rows of WgT), in fp32.
+// + sum over all k choices of dl_ij * Wg[:, e_ij] (rows of WgT), in fp32.  Lane j holds the routing entries of choice j
+// (k <= 64); a lane owns 16-byte chunks lane, lane + 64, ... of the row.
 template <class S>
 __global__ __launch_bounds__(256) void bwd_dx_kernel(const void* __restrict__ dxe, const void* __restrict__ WgT,
                                                      const int32_t* __restrict__ topk_expert, const int32_t* __restrict__ slot,
                                                      const float* __restrict__ dl, int T, int H, int k, int E, int C, int C_pad,
                                                      float* __restrict__ dx) {
+    constexpr int VEC = S::kVec;
     const int t = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
     if (t >= T) return;
-    for (int c = lane; c < H; c += 64) {
-        float acc = 0.0f;
+    long long row_lane = -1;
+    int e_lane = -1;
+    float dl_lane = 0.0f;
+    if (lane < k) {
+        const int s = slot[(size_t)t * k + lane], e = topk_expert[(size_t)t * k + lane];
+        if (e >= 0 && e < E) {
+            e_lane = e;
+            dl_lane = dl[(size_t)t * k + lane];
+            if (s >= 0 && s < C) row_lane = (long long)e * C_pad + s;
+        }
+    }
+    const int row_chunks = H / VEC;
+    const u32x4* const dv = (const u32x4*)dxe;
+    const u32x4* const wv = (const u32x4*)WgT;
+    auto fma_chunk = [&](float (&acc)[VEC], float w, const u32x4& v) {
+        if constexpr (S::kBytes == 4) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) { const uint32_t u = v[q]; acc[q] = fmaf(w, __builtin_bit_cast(float, u), acc[q]); }
+        } else {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const uint32_t u = v[q];
+                acc[2 * q] = fmaf(w, bits16_to_float<S>((uint16_t)(u & 0xffffu)), acc[2 * q]);
+                acc[2 * q + 1] = fmaf(w, bits16_to_float<S>((uint16_t)(u >> 16)), acc[2 * q + 1]);
+            }
+        }
+    };
+    for (int c = lane; c < row_chunks; c += 64) {
+        float acc[VEC];
+#pragma unroll
+        for (int q = 0; q < VEC; ++q) acc[q] = 0.0f;
         for (int j = 0; j < k; ++j) {
-            const int s = slot[(size_t)t * k + j], e = topk_expert[(size_t)t * k + j];
-            if (s >= 0 && s < C && e >= 0 && e < E) acc += load_as_float<S>(dxe, ((size_t)e * C_pad + s) * H + c);
+            const long long row = __shfl(row_lane, j);
+            if (row >= 0) fma_chunk(acc, 1.0f, dv[(size_t)row * row_chunks + c]);
         }
         for (int j = 0; j < k; ++j) {
-            const int e = topk_expert[(size_t)t * k + j];
-            if (e >= 0 && e < E) acc = fmaf(dl[(size_t)t * k + j], load_as_float<S>(WgT, (size_t)e * H + c), acc);
+            const int e = __shfl(e_lane, j);
+            const float d = __shfl(dl_lane, j);
+            if (e >= 0) fma_chunk(acc, d, wv[(size_t)e * row_chunks + c]);
         }
-        dx[(size_t)t * H + c] = acc;
+#pragma unroll
+        for (int q = 0; q < VEC; q += 4)
+            *(f32x4*)(dx + (size_t)t * H + (size_t)c * VEC + q) = f32x4{acc[q], acc[q + 1], acc[q + 2], acc[q + 3]};
     }
 }
 
 }  // namespace
+
+__global__ __launch_bounds__(256) void bwd_fill_rows_kernel(int32_t* __restrict__ rows, int E, int first, int second) {
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i < 2 * E) rows[i] = i < E ? first : second;
+}
+
+hipError_t launch_bwd_fill_rows(int32_t* rows, int E, int first, int second, hipStream_t s) {
+    hipLaunchKernelGGL(bwd_fill_rows_kernel, dim3((2 * E + 255) / 256), dim3(256), 0, s, rows, E, first, second);
+    return hipGetLastError();
+}
 
 hipError_t launch_bwd_gather(const void* x, const void* dout, const int32_t* slot_token, const float* slot_weight, int H, int E,
                              int C, int C_pad, int dtype, void* xe, void* gy, hipStream_t s) {
@@ -226,7 +312,8 @@ hipError_t launch_bwd_transpose(const void* in, void* out, int groups, int R, in
 hipError_t launch_bwd_colsum(const void* in, const int32_t* expert_demand, int E, int C, int C_pad, int cols, int dtype, float* out,
                              hipStream_t s) {
     if (E > 65535) return hipErrorInvalidValue;
-    const dim3 g((unsigned)((cols + 255) / 256), (unsigned)E), b(256);
+    const int chunks = cols / (dtype == 0 ? 4 : 8);      // 16-byte chunks per row (cols is a multiple of 8)
+    const dim3 g((unsigned)((chunks + 63) / 64), (unsigned)E), b(256);
     if (dtype == 0) hipLaunchKernelGGL(bwd_colsum_kernel<F32>, g, b, 0, s, in, expert_demand, C, C_pad, cols, out);
     else if (dtype == 1) hipLaunchKernelGGL(bwd_colsum_kernel<BF16>, g, b, 0, s, in, expert_demand, C, C_pad, cols, out);
     else hipLaunchKernelGGL(bwd_colsum_kernel<F16>, g, b, 0, s, in, expert_demand, C, C_pad, cols, out);

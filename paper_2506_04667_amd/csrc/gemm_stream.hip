@@ -64,6 +64,9 @@ hipError_t launch_stream_t(const GemmArgs& g1, const GemmArgs* g2, bool never_me
 
 template <class S, int NPH>
 hipError_t launch_stream_act(const GemmArgs& g1, const GemmArgs* g2, bool never_met, hipStream_t stream) {
+    if constexpr (NPH == 1) {
+        if (g1.c_f32) return launch_stream_t<S, kActF32Out, 1>(g1, nullptr, never_met, stream);
+    }
     switch (g1.act) {
         case 0: return launch_stream_t<S, 0, NPH>(g1, g2, never_met, stream);
         case 1: return launch_stream_t<S, 1, NPH>(g1, g2, never_met, stream);
@@ -79,6 +82,7 @@ hipError_t prepare_stream_s() {
     if (e == hipSuccess) e = prepare_stream_t<S, 1, 1>();
     if (e == hipSuccess) e = prepare_stream_t<S, 2, 1>();
     if (e == hipSuccess) e = prepare_stream_t<S, 3, 1>();
+    if (e == hipSuccess) e = prepare_stream_t<S, kActF32Out, 1>();
     if (e == hipSuccess) e = prepare_stream_t<S, 0, 2>();
     if (e == hipSuccess) e = prepare_stream_t<S, 1, 2>();
     if (e == hipSuccess) e = prepare_stream_t<S, 2, 2>();
@@ -126,7 +130,9 @@ bool stream_gemm_shape_ok(int dtype, int N, int K, int lda, int ldb, int ldc, lo
 }
 
 bool stream_gemm_eligible(const GemmArgs& a) {
-    return !a.b_is_nk && !a.c_f32 && a.rows_dev != nullptr && a.units != nullptr &&
+    // fp32 output (the weight gradients of the backward pass): identity epilogue only
+    if (a.c_f32 && a.act != 3) return false;
+    return !a.b_is_nk && a.rows_dev != nullptr && a.units != nullptr &&
            stream_gemm_shape_ok(a.dtype, a.N, a.K, a.lda, a.ldb, a.ldc, a.a_rows_total);
 }
 
@@ -135,7 +141,7 @@ hipError_t launch_grouped_gemm_stream(const GemmArgs& a, hipStream_t stream) {
 }
 
 bool ffn_fused_eligible(const GemmArgs& g1, const GemmArgs& g2) {
-    return stream_gemm_eligible(g1) && stream_gemm_eligible(g2) && g2.act == 3 && g2.a_row_index == nullptr &&
+    return stream_gemm_eligible(g1) && stream_gemm_eligible(g2) && !g1.c_f32 && !g2.c_f32 && g2.act == 3 && g2.a_row_index == nullptr &&
            g1.units == g2.units && g1.rows_dev == g2.rows_dev && g1.rows_cap == g2.rows_cap &&
            g1.groups == g2.groups && g1.max_rows == g2.max_rows && g1.dtype == g2.dtype;
 }

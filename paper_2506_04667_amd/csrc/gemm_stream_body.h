@@ -143,6 +143,7 @@ struct StreamArgs {
 };
 
 constexpr int kSpinLimit = 1 << 21;
+constexpr int kActF32Out = 4;                           // template value of ACT: identity with C (and bias) in fp32
 
 // The work of one workgroup on one list for one GEMM (phase PH of the arguments, activation ACT): `list` =
 // { fault word, number of live units, ids[cap], completion counters[cap] }; the workgroup is number wg_local of
@@ -375,6 +376,27 @@ __device__ __forceinline__ void stream_body(const StreamArgs& a, int32_t* list, 
         const int N = P.N;
         const int col_w = cur.n0 + wn * (TN * 16);      // first column of this wavefront
         const size_t c_base = (size_t)cur.grp * P.c_group_stride;
+        if constexpr (ACT == kActF32Out) {
+            // fp32 output (and fp32 bias), no activation: a lane's four sums of a tile are four consecutive columns of
+            // one row, i.e. one 16-byte store straight from the registers
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm) {
+                const int row = cur.row0 + wm * (TM * 16) + tm * 16 + r16;
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn) {
+                    const int col = col_w + tn * 16 + kq * 4;
+                    f32x4 v = acc[tm][tn];
+                    if (P.bias) {
+                        const f32x4 bv = *(const f32x4*)((const float*)P.bias + (size_t)cur.grp * P.bias_group_stride + min(col, N - 4));
+                        v[0] += bv[0]; v[1] += bv[1]; v[2] += bv[2]; v[3] += bv[3];
+                    }
+#pragma unroll
+                    for (int b = 0; b < 4; ++b) acc[tm][tn][b] = 0.0f;
+                    if (row < cur.rows && col < N) *(f32x4*)((float*)P.C + c_base + (size_t)row * P.ldc + col) = v;
+                }
+            }
+            return;
+        }
         // accumulator elements 0 .. 3 of tile (tm, tn): columns c .. c + 3 (c = 16 tn + 4 kq) of token row r16
         u32x2 bias_bits[TN];
         if (P.bias) {
@@ -399,7 +421,7 @@ __device__ __forceinline__ void stream_body(const StreamArgs& a, int32_t* list, 
                             const uint32_t word = b < 2 ? bias_bits[tn][0] : bias_bits[tn][1];
                             bias = bits16_to_float<S>((uint16_t)((b & 1) ? (word >> 16) : (word & 0xffffu)));
                         }
-                        v[b] = apply_act16_t<ACT>(acc[tm][tn][b] + bias);
+                        v[b] = apply_act16_t<(ACT == kActF32Out ? 3 : ACT)>(acc[tm][tn][b] + bias);
                         acc[tm][tn][b] = 0.0f;
                     }
                     const int chunk = (tn * 2 + (kq >> 1)) ^ swz_e(rl);

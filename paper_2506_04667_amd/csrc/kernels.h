@@ -131,6 +131,8 @@ hipError_t reset_layer_sync(hipStream_t stream);
 hipError_t layer_stage_ms(double* ms, int n, hipStream_t stream);
 
 // ---- backward pass helpers (backward.hip); buffers per expert have C_pad rows ----------------------------
+// rows[0 .. E) = first, rows[E .. 2 E) = second
+hipError_t launch_bwd_fill_rows(int32_t* rows, int E, int first, int second, hipStream_t s);
 // xe[e, s, :] = x[token] and gy[e, s, :] = weight * dout[token] for live slots, zeros for empty ones (s < C_pad)
 hipError_t launch_bwd_gather(const void* x, const void* dout, const int32_t* slot_token, const float* slot_weight, int H, int E,
                              int C, int C_pad, int dtype, void* xe, void* gy, hipStream_t s);
