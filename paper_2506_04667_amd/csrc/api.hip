@@ -318,6 +318,8 @@ moe_status forward_impl(const moe_config* cfg, void* workspace, size_t workspace
 struct BwdPlan {
     Plan p;
     int ldL, T_pad;
+    int wg_slices, wg_slice_k;                           // dWg = x^T dL as wg_slices partial products over wg_slice_k tokens each
+    size_t off_wg_part;
     size_t off_counts, off_units, off_slot_token, off_slot_weight, off_slot, off_demand, off_dl, off_dL, off_wgt, off_xe,
         off_gy, off_a, off_h, off_dh, off_y, off_hT, off_xeT, off_xT, off_wrows, off_wunits1, off_wunits2, total;
 };
@@ -331,7 +333,11 @@ moe_status make_bwd_plan(const moe_config* c, BwdPlan* b) {
     const size_t T = c->T, H = c->H, I = c->I, E = c->E, k = c->k, el = p.elem;
     const size_t rows = E * (size_t)p.C_pad;
     b->ldL = (int)align_up(E, 8);
-    b->T_pad = (int)align_up(T, 8);
+    // dWg has only (H / 128) x (E / 128) output tiles for a contraction over all T tokens: the tokens are cut into up to
+    // 16 slices of at least 1024, each slice one "group" of the grouped GEMM, and the partial products added in slice order
+    b->wg_slices = (int)(T / 1024 < 1 ? 1 : (T / 1024 > 16 ? 16 : T / 1024));
+    b->wg_slice_k = (int)align_up((T + b->wg_slices - 1) / b->wg_slices, 64);
+    b->T_pad = b->wg_slices * b->wg_slice_k;             // >= T: x^T rows and dL are zero beyond T
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, kAlign); return o; };
     b->off_counts = take((size_t)moe::route_chunks(c->T) * E * 4);
@@ -341,7 +347,8 @@ moe_status make_bwd_plan(const moe_config* c, BwdPlan* b) {
     b->off_slot = take(T * k * 4);
     b->off_demand = take(E * 4);
     b->off_dl = take(T * k * 4);
-    b->off_dL = take(T * (size_t)b->ldL * el);
+    b->off_dL = take((size_t)b->T_pad * b->ldL * el);
+    b->off_wg_part = take(b->wg_slices > 1 ? (size_t)b->wg_slices * H * E * 4 : 0);
     b->off_wgt = take((size_t)p.E_pad * H * el);
     b->off_xe = take(rows * H * el);
     b->off_gy = take(rows * H * el);
@@ -398,7 +405,7 @@ moe_status run_backward(const moe_config* c, const BwdPlan& b, void* ws, const v
     f2.C = y; f2.c_group_stride = rH; f2.ldc = H; f2.bias = b2; f2.bias_group_stride = H; f2.N = H; f2.K = I; f2.units = units;
     MOE_TRY(moe::launch_grouped_gemm(f2, s));
     // gate: dL/dw from <dout, y>, then the softmax Jacobian
-    MOE_TRY(moe::launch_bwd_gate(dout, y, topk_expert, topk_weight, slot, T, H, k, E, C, C_pad, b.ldL, dt, dl, dL, s));
+    MOE_TRY(moe::launch_bwd_gate(dout, y, topk_expert, topk_weight, slot, T, b.T_pad, H, k, E, C, C_pad, b.ldL, dt, dl, dL, s));
     // dh = gy W2^T (W2[e] read as [N = I][K = H]); da = dh * phi'(a); dxe = da W1^T (W1[e] as [N = H][K = I])
     moe::GemmArgs d1 = g;
     d1.A = gy; d1.a_group_stride = rH; d1.lda = H; d1.B = W2; d1.b_group_stride = HI; d1.ldb = H; d1.b_is_nk = true;
@@ -444,7 +451,17 @@ moe_status run_backward(const moe_config* c, const BwdPlan& b, void* ws, const v
     wg.rows_dev = nullptr; wg.groups = 1; wg.dtype = dt; wg.act = MOE_ACT_IDENTITY; wg.c_f32 = true;
     wg.A = xT; wg.lda = b.T_pad; wg.a_rows_total = H; wg.rows_fixed = H; wg.rows_cap = H; wg.max_rows = H;
     wg.B = dL; wg.ldb = b.ldL; wg.C = dWg; wg.ldc = E; wg.N = E; wg.K = T;
-    MOE_TRY(moe::launch_grouped_gemm(wg, s));
+    if (b.wg_slices > 1) {
+        float* part = (float*)ws_at(ws, b.off_wg_part);
+        wg.groups = b.wg_slices; wg.K = b.wg_slice_k;
+        wg.a_group_stride = b.wg_slice_k;                // slice g of every row of x^T
+        wg.b_group_stride = (long long)b.wg_slice_k * b.ldL;
+        wg.C = part; wg.c_group_stride = (long long)H * E;
+        MOE_TRY(moe::launch_grouped_gemm(wg, s));
+        MOE_TRY(moe::launch_bwd_sum_slices(part, b.wg_slices, (long long)H * E, dWg, s));
+    } else {
+        MOE_TRY(moe::launch_grouped_gemm(wg, s));
+    }
     MOE_TRY(moe::launch_bwd_gate_bias(topk_expert, dl, T, k, E, dgate_bias, s));
     // dx: the kept choices' rows of dxe plus the gate path
     MOE_TRY(moe::launch_bwd_dx(y, wgt, topk_expert, slot, dl, T, H, k, E, C, C_pad, dt, dx, s));

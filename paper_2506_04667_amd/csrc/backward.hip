@@ -78,10 +78,14 @@ __device__ __forceinline__ float wave_sum(float v) {
 template <class S>
 __global__ __launch_bounds__(256) void bwd_gate_kernel(const void* __restrict__ dout, const void* __restrict__ y,
                                                        const int32_t* __restrict__ topk_expert, const float* __restrict__ topk_weight,
-                                                       const int32_t* __restrict__ slot, int T, int H, int k, int E, int C, int C_pad,
-                                                       int ld, float* __restrict__ dl, void* __restrict__ dL) {
+                                                       const int32_t* __restrict__ slot, int T, int T_pad, int H, int k, int E, int C,
+                                                       int C_pad, int ld, float* __restrict__ dl, void* __restrict__ dL) {
     const int t = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
-    if (t >= T) return;
+    if (t >= T) {                                       // rows T .. T_pad - 1 of dL exist for the GEMM's sake: zeros
+        if (t < T_pad)
+            for (int c = lane; c < ld; c += 64) store_from_float<S>(dL, (size_t)t * ld + c, 0.0f);
+        return;
+    }
     int e_l = -1, s_l = -1;
     float w_l = 0.0f, dw_l = 0.0f;
     if (lane < k) {
@@ -292,11 +296,30 @@ hipError_t launch_bwd_act(const void* a, const void* g_in, const int32_t* expert
 }
 
 hipError_t launch_bwd_gate(const void* dout, const void* y, const int32_t* topk_expert, const float* topk_weight, const int32_t* slot,
-                           int T, int H, int k, int E, int C, int C_pad, int ld, int dtype, float* dl, void* dL, hipStream_t s) {
-    const dim3 g((unsigned)((T + 3) / 4)), b(256);
-    if (dtype == 0) hipLaunchKernelGGL(bwd_gate_kernel<F32>, g, b, 0, s, dout, y, topk_expert, topk_weight, slot, T, H, k, E, C, C_pad, ld, dl, dL);
-    else if (dtype == 1) hipLaunchKernelGGL(bwd_gate_kernel<BF16>, g, b, 0, s, dout, y, topk_expert, topk_weight, slot, T, H, k, E, C, C_pad, ld, dl, dL);
-    else hipLaunchKernelGGL(bwd_gate_kernel<F16>, g, b, 0, s, dout, y, topk_expert, topk_weight, slot, T, H, k, E, C, C_pad, ld, dl, dL);
+                           int T, int T_pad, int H, int k, int E, int C, int C_pad, int ld, int dtype, float* dl, void* dL,
+                           hipStream_t s) {
+    const dim3 g((unsigned)((T_pad + 3) / 4)), b(256);
+    if (dtype == 0) hipLaunchKernelGGL(bwd_gate_kernel<F32>, g, b, 0, s, dout, y, topk_expert, topk_weight, slot, T, T_pad, H, k, E, C, C_pad, ld, dl, dL);
+    else if (dtype == 1) hipLaunchKernelGGL(bwd_gate_kernel<BF16>, g, b, 0, s, dout, y, topk_expert, topk_weight, slot, T, T_pad, H, k, E, C, C_pad, ld, dl, dL);
+    else hipLaunchKernelGGL(bwd_gate_kernel<F16>, g, b, 0, s, dout, y, topk_expert, topk_weight, slot, T, T_pad, H, k, E, C, C_pad, ld, dl, dL);
+    return hipGetLastError();
+}
+
+// out[i] = part[0][i] + part[1][i] + ... in that order, i < n (n a multiple of 4)
+__global__ __launch_bounds__(256) void bwd_sum_slices_kernel(const f32x4* __restrict__ part, int slices, long long n4, f32x4* __restrict__ out) {
+    const long long i = blockIdx.x * 256ll + threadIdx.x;
+    if (i >= n4) return;
+    f32x4 acc = part[i];
+    for (int g = 1; g < slices; ++g) {
+        const f32x4 v = part[(size_t)g * n4 + i];
+        acc[0] += v[0]; acc[1] += v[1]; acc[2] += v[2]; acc[3] += v[3];
+    }
+    out[i] = acc;
+}
+
+hipError_t launch_bwd_sum_slices(const float* part, int slices, long long n, float* out, hipStream_t s) {
+    const long long n4 = n / 4;
+    hipLaunchKernelGGL(bwd_sum_slices_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, s, (const f32x4*)part, slices, n4, (f32x4*)out);
     return hipGetLastError();
 }
 

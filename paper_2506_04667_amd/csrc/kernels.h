@@ -139,9 +139,12 @@ hipError_t launch_bwd_gather(const void* x, const void* dout, const int32_t* slo
 // over [E, C_pad, I]: out = phi(a), or with grad: out = g_in * phi'(a); rows beyond an expert's live rows give 0
 hipError_t launch_bwd_act(const void* a, const void* g_in, const int32_t* expert_demand, int E, int C, int C_pad, int I, int act,
                           int dtype, bool grad, void* out, hipStream_t s);
-// dl[T, k] (fp32) and dL[T, ld] (storage type, dense): gradient with respect to the selected gate logits (k <= 64)
+// dl[T, k] (fp32) and dL[T_pad, ld] (storage type, dense; rows at and beyond T zero): gradient with respect to the
+// selected gate logits (k <= 64)
 hipError_t launch_bwd_gate(const void* dout, const void* y, const int32_t* topk_expert, const float* topk_weight, const int32_t* slot,
-                           int T, int H, int k, int E, int C, int C_pad, int ld, int dtype, float* dl, void* dL, hipStream_t s);
+                           int T, int T_pad, int H, int k, int E, int C, int C_pad, int ld, int dtype, float* dl, void* dL, hipStream_t s);
+// out[i] = sum over g < slices of part[g * n + i], in ascending g (n a multiple of 4, 16-byte aligned buffers)
+hipError_t launch_bwd_sum_slices(const float* part, int slices, long long n, float* out, hipStream_t s);
 // out[g][c][r] = in[g][r][c], r < R, c < Cc; rows of out have ld_out entries, zero at and beyond R
 hipError_t launch_bwd_transpose(const void* in, void* out, int groups, int R, int Cc, int ld_out, int dtype, hipStream_t s);
 // out[e][c] = sum over live rows of in[e][r][c] (fp32)

@@ -51,6 +51,10 @@ def _backward(w, dev, host, dout):
          drop_policy="choice_major"),
     # experts nobody picks and tokens that lose every choice
     dict(T=400, H=64, I=64, E=8, k=2, capacity_factor=0.25, dtype="f32", with_bias=True, act="gelu_erf", empty=(2, 5)),
+    # more than 2048 tokens: the gate-weight gradient is a sum of partial products over token slices (here 2 slices of
+    # 1088 tokens: the last one runs 76 rows past T into the zero padding)
+    dict(T=2100, H=64, I=72, E=8, k=2, capacity_factor=1.0, dtype="f32", with_bias=False, act="relu", gate_bias=True),
+    dict(T=3333, H=128, I=64, E=12, k=3, capacity_factor=1.0, dtype="bf16", with_bias=True, act="gelu_tanh"),
     # the paper's layer shape per expert (H = I = 2048, 256 slots, top-2, erf-GELU, bf16) with 16 experts: the tile
     # shapes, K = 256 weight-gradient GEMMs and streaming kernels of the full-size backward pass
     dict(T=2048, H=2048, I=2048, E=16, k=2, capacity_factor=1.0, dtype="bf16", with_bias=False, act="gelu_erf"),
