@@ -117,21 +117,31 @@ __global__ __launch_bounds__(256) void bwd_gate_kernel(const void* __restrict__ 
 }
 
 // out[g][c][r] = in[g][r][c] for r < R, c < Cc; out rows have ld_out >= R entries, those at and beyond R are zero.
+// 64 x 64 tiles through LDS; 16-bit elements move in pairs (4 bytes per lane on both sides: Cc and ld_out are even).
 template <class elem>
 __global__ __launch_bounds__(256) void bwd_transpose_kernel(const elem* __restrict__ in, elem* __restrict__ out, int R, int Cc,
                                                             int ld_out) {
-    __shared__ elem tile[32][33];
+    constexpr int TS = 64, PAIR = 4 / (int)sizeof(elem), PITCH = TS + 2;       // elements; rows stay 4-byte aligned
+    __shared__ elem tile[TS][PITCH];
     const size_t g = blockIdx.z;
-    const int r0 = blockIdx.x * 32, c0 = blockIdx.y * 32;
-    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
-    for (int i = ty; i < 32; i += 8) {
-        const int r = r0 + i, c = c0 + tx;
-        tile[i][tx] = (r < R && c < Cc) ? in[(g * R + r) * Cc + c] : (elem)0;
+    const int r0 = blockIdx.x * TS, c0 = blockIdx.y * TS;
+    constexpr int PER_ROW = TS / PAIR;                  // 4-byte words per tile row
+    for (int idx = threadIdx.x; idx < TS * PER_ROW; idx += 256) {
+        const int i = idx / PER_ROW, w = idx % PER_ROW;
+        const int r = r0 + i, c = c0 + w * PAIR;
+        uint32_t v = 0u;
+        if (r < R && c < Cc) v = *(const uint32_t*)(in + (g * R + r) * Cc + c);
+        *(uint32_t*)&tile[i][w * PAIR] = v;
     }
     __syncthreads();
-    for (int i = ty; i < 32; i += 8) {
-        const int c = c0 + i, r = r0 + tx;
-        if (c < Cc && r < ld_out) out[(g * Cc + c) * ld_out + r] = tile[tx][i];
+    for (int idx = threadIdx.x; idx < TS * PER_ROW; idx += 256) {
+        const int i = idx / PER_ROW, w = idx % PER_ROW;  // output row c0 + i, entries r0 + w * PAIR ..
+        const int c = c0 + i, r = r0 + w * PAIR;
+        if (c >= Cc || r >= ld_out) continue;
+        uint32_t v;
+        if constexpr (PAIR == 2) v = (uint32_t)tile[w * 2][i] | ((uint32_t)tile[w * 2 + 1][i] << 16);
+        else v = __builtin_bit_cast(uint32_t, tile[w][i]);
+        *(uint32_t*)(out + (g * Cc + c) * ld_out + r) = v;
     }
 }
 
@@ -325,8 +335,8 @@ hipError_t launch_bwd_sum_slices(const float* part, int slices, long long n, flo
 
 hipError_t launch_bwd_transpose(const void* in, void* out, int groups, int R, int Cc, int ld_out, int dtype, hipStream_t s) {
     if (groups <= 0 || R <= 0 || Cc <= 0) return hipSuccess;
-    if (groups > 65535 || (Cc + 31) / 32 > 65535) return hipErrorInvalidValue;
-    const dim3 g((unsigned)((ld_out + 31) / 32), (unsigned)((Cc + 31) / 32), (unsigned)groups), b(256);
+    if (groups > 65535 || (Cc + 63) / 64 > 65535 || (Cc & 1) || (ld_out & 1)) return hipErrorInvalidValue;
+    const dim3 g((unsigned)((ld_out + 63) / 64), (unsigned)((Cc + 63) / 64), (unsigned)groups), b(256);
     if (dtype == 0) hipLaunchKernelGGL(bwd_transpose_kernel<float>, g, b, 0, s, (const float*)in, (float*)out, R, Cc, ld_out);
     else hipLaunchKernelGGL(bwd_transpose_kernel<uint16_t>, g, b, 0, s, (const uint16_t*)in, (uint16_t*)out, R, Cc, ld_out);
     return hipGetLastError();
