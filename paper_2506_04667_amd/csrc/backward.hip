@@ -25,25 +25,59 @@ __device__ __forceinline__ float act_grad(float v, int act) {
     }
 }
 
+// a 16-byte chunk of storage <-> its S::kVec values as floats
+template <class S>
+__device__ __forceinline__ void chunk_to_floats(const u32x4& v, float (&f)[S::kVec]) {
+    if constexpr (S::kBytes == 4) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) { const uint32_t u = v[q]; f[q] = __builtin_bit_cast(float, u); }
+    } else {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const uint32_t u = v[q];
+            f[2 * q] = bits16_to_float<S>((uint16_t)(u & 0xffffu));
+            f[2 * q + 1] = bits16_to_float<S>((uint16_t)(u >> 16));
+        }
+    }
+}
+template <class S>
+__device__ __forceinline__ u32x4 floats_to_chunk(const float (&f)[S::kVec]) {
+    u32x4 v;
+    if constexpr (S::kBytes == 4) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) v[q] = __builtin_bit_cast(uint32_t, f[q]);
+    } else {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) v[q] = (uint32_t)float_to_bits16<S>(f[2 * q]) | ((uint32_t)float_to_bits16<S>(f[2 * q + 1]) << 16);
+    }
+    return v;
+}
+
 // One workgroup per slot row (e, s), s < C_pad: xe[e, s, :] = x[token, :] and gy[e, s, :] = w * dout[token, :]
 // for a live slot, zeros for an empty one (so that the rows beyond an expert's live rows contribute nothing to
-// the weight-gradient products, which run over all C_pad rows).
+// the weight-gradient products, which run over all C_pad rows).  16 bytes per lane.
 template <class S>
 __global__ __launch_bounds__(256) void bwd_gather_kernel(const void* __restrict__ x, const void* __restrict__ dout,
                                                          const int32_t* __restrict__ slot_token, const float* __restrict__ slot_weight,
                                                          int H, int C, int C_pad, void* __restrict__ xe, void* __restrict__ gy) {
+    constexpr int VEC = S::kVec;
     const size_t row = blockIdx.x;
     const int e = (int)(row / C_pad), s = (int)(row % C_pad);
     const int tok = s < C ? slot_token[(size_t)e * C + s] : -1;
     const float w = tok >= 0 ? slot_weight[(size_t)e * C + s] : 0.0f;
-    for (int c = threadIdx.x; c < H; c += 256) {
-        float xv = 0.0f, gv = 0.0f;
+    const int row_chunks = H / VEC;
+    for (int c = threadIdx.x; c < row_chunks; c += 256) {
+        u32x4 xv = {0u, 0u, 0u, 0u}, gv = {0u, 0u, 0u, 0u};
         if (tok >= 0) {
-            xv = load_as_float<S>(x, (size_t)tok * H + c);
-            gv = w * load_as_float<S>(dout, (size_t)tok * H + c);
+            xv = ((const u32x4*)x)[(size_t)tok * row_chunks + c];
+            float f[VEC];
+            chunk_to_floats<S>(((const u32x4*)dout)[(size_t)tok * row_chunks + c], f);
+#pragma unroll
+            for (int q = 0; q < VEC; ++q) f[q] *= w;
+            gv = floats_to_chunk<S>(f);
         }
-        store_from_float<S>(xe, row * H + c, xv);
-        store_from_float<S>(gy, row * H + c, gv);
+        ((u32x4*)xe)[row * row_chunks + c] = xv;
+        ((u32x4*)gy)[row * row_chunks + c] = gv;
     }
 }
 
@@ -52,16 +86,28 @@ template <class S, int MODE>
 __global__ __launch_bounds__(256) void bwd_act_kernel(const void* __restrict__ a, const void* __restrict__ g,
                                                       const int32_t* __restrict__ expert_demand, int C, int C_pad, int I, int act,
                                                       void* __restrict__ out) {
+    constexpr int VEC = S::kVec;
     const size_t row = blockIdx.x;
     const int e = (int)(row / C_pad), s = (int)(row % C_pad);
     const bool live = s < min(expert_demand[e], C);
-    for (int c = threadIdx.x; c < I; c += 256) {
-        float v = 0.0f;
+    const int row_chunks = I / VEC;
+    for (int c = threadIdx.x; c < row_chunks; c += 256) {
+        u32x4 o = {0u, 0u, 0u, 0u};
         if (live) {
-            const float av = load_as_float<S>(a, row * I + c);
-            v = MODE == 0 ? apply_act(av, act) : load_as_float<S>(g, row * I + c) * act_grad(av, act);
+            float av[VEC], v[VEC];
+            chunk_to_floats<S>(((const u32x4*)a)[row * row_chunks + c], av);
+            if constexpr (MODE == 0) {
+#pragma unroll
+                for (int q = 0; q < VEC; ++q) v[q] = apply_act(av[q], act);
+            } else {
+                float gf[VEC];
+                chunk_to_floats<S>(((const u32x4*)g)[row * row_chunks + c], gf);
+#pragma unroll
+                for (int q = 0; q < VEC; ++q) v[q] = gf[q] * act_grad(av[q], act);
+            }
+            o = floats_to_chunk<S>(v);
         }
-        store_from_float<S>(out, row * I + c, v);
+        ((u32x4*)out)[row * row_chunks + c] = o;
     }
 }
 
