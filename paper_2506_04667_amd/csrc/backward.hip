@@ -132,6 +132,7 @@ __global__ __launch_bounds__(256) void bwd_gate_kernel(const void* __restrict__ 
             for (int c = lane; c < ld; c += 64) store_from_float<S>(dL, (size_t)t * ld + c, 0.0f);
         return;
     }
+    const int row_chunks = H / S::kVec;
     int e_l = -1, s_l = -1;
     float w_l = 0.0f, dw_l = 0.0f;
     if (lane < k) {
@@ -144,7 +145,13 @@ __global__ __launch_bounds__(256) void bwd_gate_kernel(const void* __restrict__ 
         if (s < 0 || s >= C || e < 0 || e >= E) continue;      // wave-uniform
         const size_t row = (size_t)e * C_pad + s;
         float part = 0.0f;
-        for (int c = lane; c < H; c += 64) part = fmaf(load_as_float<S>(dout, (size_t)t * H + c), load_as_float<S>(y, row * H + c), part);
+        for (int c = lane; c < row_chunks; c += 64) {   // 16 bytes of both rows per lane and step
+            float dv[S::kVec], yv[S::kVec];
+            chunk_to_floats<S>(((const u32x4*)dout)[(size_t)t * row_chunks + c], dv);
+            chunk_to_floats<S>(((const u32x4*)y)[row * row_chunks + c], yv);
+#pragma unroll
+            for (int q = 0; q < S::kVec; ++q) part = fmaf(dv[q], yv[q], part);
+        }
         const float d = wave_sum(part);
         if (lane == j) dw_l = d;
     }
@@ -251,7 +258,15 @@ __global__ __launch_bounds__(256) void bwd_gate_bias_kernel(const int32_t* __res
     __shared__ float part[256];
     const int e = blockIdx.x;
     float acc = 0.0f;
-    for (long long p = threadIdx.x; p < P; p += 256)
+    const long long P4 = P / 4;                         // four pairs per thread and step (both tables are 16-byte aligned)
+    for (long long p = threadIdx.x; p < P4; p += 256) {
+        const u32x4 ev = ((const u32x4*)topk_expert)[p];
+        const f32x4 dv = ((const f32x4*)dl)[p];
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            if ((int)ev[q] == e) acc += dv[q];
+    }
+    for (long long p = P4 * 4 + threadIdx.x; p < P; p += 256)
         if (topk_expert[p] == e) acc += dl[p];
     part[threadIdx.x] = acc;
     __syncthreads();
