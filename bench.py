@@ -282,7 +282,7 @@ def main():
                     "stream_copy_gbs_read_plus_write": round(2 * src.numel() / (cp * 1e-3) / 1e9, 1),
                     "mfma_loop_tflops": round(flops[0] / (mm * 1e-3) / 1e12, 1), "mfma_dtype": w.dtype,
                     "l2_to_lds_fill_gbs": fills,
-                    "bytes": src.numel(), "kernels": "moe_probe_stream / moe_probe_mfma (csrc/probes.hip)"}
+                    "bytes": src.numel(), "kernels": "moe_probe_stream / moe_probe_mfma / moe_probe_lds_fill (csrc/probes.hip)"}
 
     slot = b.slot.cpu()
     demand = b.expert_demand.cpu()

@@ -132,6 +132,17 @@ def test_layer_stage_clock_arguments_are_checked_on_the_host(lib):
     assert len(moe.LAYER_STAGES) == 10
 
 
+def test_yardstick_arguments_are_checked_on_the_host(lib):
+    ok = ctypes.c_void_p(4096)
+    moved = ctypes.c_double()
+    assert lib.moe_probe_lds_fill(3, ok, 1 << 21, 8, ok, ctypes.byref(moved), None) == -1     # unknown mode
+    assert lib.moe_probe_lds_fill(0, ok, 1 << 21, 7, ok, ctypes.byref(moved), None) == -1     # odd step count
+    assert lib.moe_probe_lds_fill(0, ok, 1000, 8, ok, ctypes.byref(moved), None) == -1        # region not a multiple of 64 KiB
+    assert lib.moe_probe_lds_fill(0, None, 1 << 21, 8, ok, ctypes.byref(moved), None) == -1
+    assert lib.moe_probe_stream(ok, None, 8, ok, None) == -1                                   # fewer than 16 bytes
+    assert lib.moe_probe_mfma(7, 10, ok, None, None) == -1                                     # unknown dtype
+
+
 def test_status_strings(lib):
     assert moe.moe_status_string(0) == "ok"
     assert len({moe.moe_status_string(c) for c in (0, -1, -2, -3, -4, -5, -6, -7)}) == 8
