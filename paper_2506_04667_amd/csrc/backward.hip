@@ -25,6 +25,10 @@ __device__ __forceinline__ float act_grad(float v, int act) {
     }
 }
 
+// 16 bytes that this kernel reads once: the non-temporal hint (on this chip reads of data that is not in any cache run at
+// half the rate without it)
+__device__ __forceinline__ u32x4 load_once(const void* base, size_t chunk) { return __builtin_nontemporal_load((const u32x4*)base + chunk); }
+
 // a 16-byte chunk of storage <-> its S::kVec values as floats
 template <class S>
 __device__ __forceinline__ void chunk_to_floats(const u32x4& v, float (&f)[S::kVec]) {
@@ -69,9 +73,9 @@ __global__ __launch_bounds__(256) void bwd_gather_kernel(const void* __restrict_
     for (int c = threadIdx.x; c < row_chunks; c += 256) {
         u32x4 xv = {0u, 0u, 0u, 0u}, gv = {0u, 0u, 0u, 0u};
         if (tok >= 0) {
-            xv = ((const u32x4*)x)[(size_t)tok * row_chunks + c];
+            xv = load_once(x, (size_t)tok * row_chunks + c);
             float f[VEC];
-            chunk_to_floats<S>(((const u32x4*)dout)[(size_t)tok * row_chunks + c], f);
+            chunk_to_floats<S>(load_once(dout, (size_t)tok * row_chunks + c), f);
 #pragma unroll
             for (int q = 0; q < VEC; ++q) f[q] *= w;
             gv = floats_to_chunk<S>(f);
@@ -95,13 +99,13 @@ __global__ __launch_bounds__(256) void bwd_act_kernel(const void* __restrict__ a
         u32x4 o = {0u, 0u, 0u, 0u};
         if (live) {
             float av[VEC], v[VEC];
-            chunk_to_floats<S>(((const u32x4*)a)[row * row_chunks + c], av);
+            chunk_to_floats<S>(load_once(a, row * row_chunks + c), av);
             if constexpr (MODE == 0) {
 #pragma unroll
                 for (int q = 0; q < VEC; ++q) v[q] = apply_act(av[q], act);
             } else {
                 float gf[VEC];
-                chunk_to_floats<S>(((const u32x4*)g)[row * row_chunks + c], gf);
+                chunk_to_floats<S>(load_once(g, row * row_chunks + c), gf);
 #pragma unroll
                 for (int q = 0; q < VEC; ++q) v[q] = gf[q] * act_grad(av[q], act);
             }
@@ -147,8 +151,8 @@ __global__ __launch_bounds__(256) void bwd_gate_kernel(const void* __restrict__ 
         float part = 0.0f;
         for (int c = lane; c < row_chunks; c += 64) {   // 16 bytes of both rows per lane and step
             float dv[S::kVec], yv[S::kVec];
-            chunk_to_floats<S>(((const u32x4*)dout)[(size_t)t * row_chunks + c], dv);
-            chunk_to_floats<S>(((const u32x4*)y)[row * row_chunks + c], yv);
+            chunk_to_floats<S>(load_once(dout, (size_t)t * row_chunks + c), dv);
+            chunk_to_floats<S>(load_once(y, row * row_chunks + c), yv);
 #pragma unroll
             for (int q = 0; q < S::kVec; ++q) part = fmaf(dv[q], yv[q], part);
         }
@@ -183,7 +187,7 @@ __global__ __launch_bounds__(256) void bwd_transpose_kernel(const elem* __restri
         const int i = idx / PER_ROW, w = idx % PER_ROW;
         const int r = r0 + i, c = c0 + w * PAIR;
         uint32_t v = 0u;
-        if (r < R && c < Cc) v = *(const uint32_t*)(in + (g * R + r) * Cc + c);
+        if (r < R && c < Cc) v = __builtin_nontemporal_load((const uint32_t*)(in + (g * R + r) * Cc + c));
         *(uint32_t*)&tile[i][w * PAIR] = v;
     }
     __syncthreads();
@@ -231,11 +235,11 @@ __global__ __launch_bounds__(256) void bwd_colsum_kernel(const void* __restrict_
         for (; r + 12 < n; r += 16) {
             u32x4 v[4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) v[i] = p[(size_t)(r + 4 * i) * row_chunks];
+            for (int i = 0; i < 4; ++i) v[i] = __builtin_nontemporal_load(p + (size_t)(r + 4 * i) * row_chunks);
 #pragma unroll
             for (int i = 0; i < 4; ++i) add(v[i]);
         }
-        for (; r < n; r += 4) add(p[(size_t)r * row_chunks]);
+        for (; r < n; r += 4) add(__builtin_nontemporal_load(p + (size_t)r * row_chunks));
     }
     if (wave > 0) {
 #pragma unroll
@@ -321,7 +325,7 @@ __global__ __launch_bounds__(256) void bwd_dx_kernel(const void* __restrict__ dx
         for (int q = 0; q < VEC; ++q) acc[q] = 0.0f;
         for (int j = 0; j < k; ++j) {
             const long long row = __shfl(row_lane, j);
-            if (row >= 0) fma_chunk(acc, 1.0f, dv[(size_t)row * row_chunks + c]);
+            if (row >= 0) fma_chunk(acc, 1.0f, __builtin_nontemporal_load(dv + (size_t)row * row_chunks + c));
         }
         for (int j = 0; j < k; ++j) {
             const int e = __shfl(e_lane, j);
